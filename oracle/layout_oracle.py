@@ -1,0 +1,124 @@
+"""Tile-list oracle for the DBSA block layout -- TEST INFRASTRUCTURE ONLY.
+
+Derives, straight from the visibility predicates of ``dbsa_oracle`` and by
+scanning every (Q tile, KV tile) pair, the canonical lists the library's layout
+builder must reproduce bit for bit.  No code is shared with that builder.
+
+Canonical form (Sec. 2.1 for the stage-1 pattern, Sec. 2.2 for the query stage):
+
+* Q tiles are cut every ``block_m`` tokens inside a segment and never straddle
+  segments.  Stage 1: the sink segment ``[0, S)`` first, then each group from
+  its first token.  Query stage: each query's own tokens from its first token.
+  A row of the Q-tile table is ``(q_start, q_len, owner, 0)`` with owner = -1
+  for the sink, the group index at stage 1, the query index at stage 2.
+* KV tiles are cut every ``block_n`` tokens inside a segment (sink, each group,
+  each query's self tokens) from the segment's first token.
+* A KV tile is listed for a Q tile iff at least one (row, key) pair in it is
+  visible.  Its kind is FULL iff every pair is visible, else CAUSAL.  Self
+  tiles of the query stage carry the SELF bit.
+* Order: ascending ``kv_start`` at stage 1; at stage 2 the sink tiles, then the
+  selected groups in the caller's order, then the self tiles.
+* An entry is two int32 words: ``kv_start`` and ``kv_len | kind << 16``.
+* Decode: per query the pool part of the list (sink + selected groups); split s
+  of n covers entries ``[s*L // n, (s+1)*L // n)``.
+"""
+from __future__ import annotations
+
+from typing import List, Tuple
+
+import numpy as np
+
+from . import dbsa_oracle as orc
+
+KIND_FULL = 0
+KIND_CAUSAL = 1
+KIND_SELF_FULL = 2
+KIND_SELF_CAUSAL = 3
+
+
+def _segments(sink_len, demo_offsets, group_demo_offsets) -> List[Tuple[int, int]]:
+    """[(start, end)] of the sink segment and of every group, in token order."""
+    gb = np.asarray(demo_offsets)[np.asarray(group_demo_offsets)]
+    segs = [(0, int(sink_len))]
+    for g in range(len(gb) - 1):
+        segs.append((int(gb[g]), int(gb[g + 1])))
+    return segs
+
+
+def _cut(start: int, end: int, step: int) -> List[Tuple[int, int]]:
+    return [(a, min(step, end - a)) for a in range(start, end, step)]
+
+
+def _pack(entries) -> np.ndarray:
+    out = np.zeros((len(entries), 2), dtype=np.int32)
+    for n, (start, length, kind) in enumerate(entries):
+        out[n, 0] = start
+        out[n, 1] = length | (kind << 16)
+    return out
+
+
+def preencode_layout(sink_len, demo_offsets, group_demo_offsets, prev_window, block_m, block_n):
+    """-> (qtile_tab int32 [n,4], list_ptr int64 [n+1], list_ent int32 [E,2])."""
+    demo_of, group_of = orc.token_maps(sink_len, demo_offsets, group_demo_offsets)
+    segs = _segments(sink_len, demo_offsets, group_demo_offsets)
+    kv_tiles = [t for (a, b) in segs for t in _cut(a, b, block_n)]
+    qtab, ptr, ents = [], [0], []
+    for owner, (a, b) in enumerate(segs):
+        for (q0, qn) in _cut(a, b, block_m):
+            m = orc.mask_pre(np.arange(q0, q0 + qn), sink_len, demo_of, group_of, prev_window)
+            for (k0, kn) in kv_tiles:                      # ascending kv_start
+                sub = m[:, k0:k0 + kn]
+                if sub.any():
+                    ents.append((k0, kn, KIND_FULL if sub.all() else KIND_CAUSAL))
+            qtab.append((q0, qn, owner - 1, 0))
+            ptr.append(len(ents))
+    return (np.asarray(qtab, dtype=np.int32).reshape(-1, 4), np.asarray(ptr, dtype=np.int64), _pack(ents))
+
+
+def _pool_entries(u, sink_len, demo_offsets, group_demo_offsets, sel_ptr, sel_idx, block_n, group_of):
+    segs = _segments(sink_len, demo_offsets, group_demo_offsets)
+    sel = [int(g) for g in sel_idx[int(sel_ptr[u]):int(sel_ptr[u + 1])]]
+    vis = orc.mask_query_pool(sel, sink_len, group_of)
+    ents = []
+    for seg_id in [0] + [g + 1 for g in sel]:              # sink, then the caller's order
+        a, b = segs[seg_id]
+        for (k0, kn) in _cut(a, b, block_n):
+            sub = vis[k0:k0 + kn]
+            if sub.any():
+                assert sub.all()
+                ents.append((k0, kn, KIND_FULL))
+    return ents
+
+
+def query_layout(sink_len, demo_offsets, group_demo_offsets, cu_qlens, sel_ptr, sel_idx, block_m, block_n):
+    _, group_of = orc.token_maps(sink_len, demo_offsets, group_demo_offsets)
+    qtab, ptr, ents = [], [0], []
+    for u in range(len(cu_qlens) - 1):
+        t0, t1 = int(cu_qlens[u]), int(cu_qlens[u + 1])
+        pool = _pool_entries(u, sink_len, demo_offsets, group_demo_offsets, sel_ptr, sel_idx, block_n, group_of)
+        for (q0, qn) in _cut(t0, t1, block_m):
+            ents.extend(pool)
+            a = np.arange(q0, q0 + qn)[:, None]
+            for (k0, kn) in _cut(t0, t1, block_n):
+                b = np.arange(k0, k0 + kn)[None, :]
+                sub = b <= a
+                if sub.any():
+                    ents.append((k0, kn, KIND_SELF_FULL if sub.all() else KIND_SELF_CAUSAL))
+            qtab.append((q0, qn, u, 0))
+            ptr.append(len(ents))
+    return (np.asarray(qtab, dtype=np.int32).reshape(-1, 4), np.asarray(ptr, dtype=np.int64), _pack(ents))
+
+
+def decode_layout(sink_len, demo_offsets, group_demo_offsets, n_queries, sel_ptr, sel_idx, block_n, n_split):
+    """-> (dec_ptr int64 [B+1], dec_ent int32 [E,2], split_ptr int64 [B, n_split+1])."""
+    _, group_of = orc.token_maps(sink_len, demo_offsets, group_demo_offsets)
+    ptr, ents = [0], []
+    split = np.zeros((n_queries, n_split + 1), dtype=np.int64)
+    for u in range(n_queries):
+        pool = _pool_entries(u, sink_len, demo_offsets, group_demo_offsets, sel_ptr, sel_idx, block_n, group_of)
+        base = len(ents)
+        ents.extend(pool)
+        ptr.append(len(ents))
+        for s in range(n_split + 1):
+            split[u, s] = base + (s * len(pool)) // n_split
+    return np.asarray(ptr, dtype=np.int64), _pack(ents), split
