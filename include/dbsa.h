@@ -1,0 +1,216 @@
+/*
+ * dbsa.h -- C ABI of libdbsa: block-sparse causal attention over a demonstration
+ * KV cache (Dynamic Block-Sparse Attention), for AMD MI355X (gfx950).
+ *
+ * Vocabulary.  The paper calls the unit of encoding and retrieval a "block" of k
+ * demonstrations (Sec. 2.1).  Here that unit is a GROUP; "KV tile" / "Q tile" are
+ * kernel tiles of tokens.  Token order of a pool: the attention-sink prefix
+ * [0, S), then the demonstrations; groups are runs of whole demonstrations.
+ *
+ * All tensors are token-major [tokens, heads, D] with the D elements of one
+ * (token, head) contiguous; strides are given in ELEMENTS.  Q/K/V are post-RoPE:
+ * the library never applies positions, so the K handed to the query stage may be
+ * a re-positioned copy (Sec. 2.2) of the K used at pre-encoding.
+ *
+ * Every function returns DBSA_OK (0) or a negative error code; nothing throws
+ * across the boundary.  Functions are thread-safe on distinct layouts.  The
+ * attention entry points only enqueue work on the caller's stream and never
+ * synchronise it.  The caller owns every tensor and the workspace; the library
+ * owns only dbsa_layout objects (build / destroy).
+ */
+#ifndef DBSA_H_
+#define DBSA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  DBSA_OK = 0,
+  DBSA_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, misaligned tensor, layout of the wrong stage */
+  DBSA_ERR_BAD_BOUNDS = -2,    /* demo/group/query offsets not strictly increasing or not anchored as documented */
+  DBSA_ERR_BAD_SELECTION = -3, /* group index out of range, or a group listed twice by one query */
+  DBSA_ERR_UNSUPPORTED = -4,   /* head_dim, head ratio, dtype or tile size the kernels do not implement */
+  DBSA_ERR_WORKSPACE = -5,     /* workspace missing or smaller than dbsa_workspace_bytes() */
+  DBSA_ERR_HIP = -6            /* a HIP runtime call failed; hipGetLastError() holds the cause */
+};
+
+enum { DBSA_BF16 = 0, DBSA_F32 = 1 };
+
+/* dbsa_layout_build flag: build the host lists only and touch no GPU.  Such a
+ * layout can be exported and destroyed but not passed to an attention call. */
+enum { DBSA_LAYOUT_HOST_ONLY = 1 };
+
+/* KV-tile kinds stored in list entries. */
+enum {
+  DBSA_TILE_FULL = 0,        /* pool keys, every (row, key) pair visible                       */
+  DBSA_TILE_CAUSAL = 1,      /* pool keys, pair visible iff key token <= row token             */
+  DBSA_TILE_SELF_FULL = 2,   /* keys from the query's own K/V tensor, every pair visible       */
+  DBSA_TILE_SELF_CAUSAL = 3  /* own keys, pair visible iff key token <= row token              */
+};
+
+/* Static, NUL-terminated description of an error code; never freed. */
+const char* dbsa_strerror(int code);
+
+/*
+ * The demonstration pool (Sec. 2.1: D is partitioned into groups of whole
+ * demonstrations; the first unit is the anchor every group attends).  Host
+ * pointers, read during the call only.
+ */
+typedef struct {
+  int32_t sink_len;                  /* S >= 0: tokens [0, S) are the anchor / attention sink               */
+  int32_t n_demos;                   /* >= 1                                                                  */
+  const int32_t* demo_offsets;       /* [n_demos+1] token offsets; [0] == S; strictly increasing; last == N   */
+  int32_t n_groups;                  /* >= 1                                                                  */
+  const int32_t* group_demo_offsets; /* [n_groups+1] demo indices; [0] == 0; strictly increasing; last == n_demos */
+  int32_t prev_window;               /* number of preceding groups a group attends at pre-encoding (the paper's j);
+                                        0 = sink + own group only                                            */
+} dbsa_pool_desc;
+
+/*
+ * Per-query group selections (Sec. 2.2: a retriever picks a subset of groups for
+ * each test query; the anchor is always included and is NOT listed here).  Host
+ * pointers, read during the call only.  An empty selection is valid (sink + self).
+ */
+typedef struct {
+  int32_t n_queries;        /* B >= 1                                                                     */
+  const int32_t* cu_qlens;  /* [B+1] offsets of each query's prompt tokens in the packed query tensors;
+                               [0] == 0; strictly increasing                                              */
+  const int32_t* sel_ptr;   /* [B+1] CSR row pointers into sel_idx; [0] == 0; non-decreasing              */
+  const int32_t* sel_idx;   /* selected group indices; the caller's order is kept in the lists            */
+  int32_t n_split;          /* decode: KV splits per (query, KV head); 0 = let the library choose          */
+} dbsa_select_desc;
+
+typedef struct dbsa_layout dbsa_layout; /* opaque; owns host and device copies of its index lists */
+
+/*
+ * Block-layout builder.  Turns the pool structure (and, if `sel` is non-NULL, the
+ * per-query selections) into per-Q-tile lists of KV tiles so that the kernels walk
+ * only tiles holding visible keys (Sec. 2.1: masked blocks are skipped).
+ *
+ *   sel == NULL : pre-encode layout.  Q tiles: the sink segment, then each group,
+ *                 cut every block_m tokens from the segment's first token.  List of
+ *                 a tile: sink tiles, the tiles of the prev_window preceding groups,
+ *                 the own group's tiles up to the diagonal; ascending kv_start.
+ *   sel != NULL : query-stage layout.  Q tiles: each query's prompt cut every
+ *                 block_m tokens.  List: sink tiles, the tiles of the selected
+ *                 groups in the caller's order, then the query's own tiles up to
+ *                 the diagonal.  Also builds the decode lists: per query the pool
+ *                 part, cut into n_split runs of entries
+ *                 [s*L / n_split, (s+1)*L / n_split).
+ *
+ * KV tiles are cut every block_n tokens inside a segment (sink, group, a query's
+ * own tokens) and never straddle segments.  block_m, block_n > 0; the attention
+ * calls state which sizes their kernels accept.
+ *
+ * flags: 0 or DBSA_LAYOUT_HOST_ONLY.  Without HOST_ONLY the lists are copied to
+ * the current device with hipMemcpyAsync on `stream` (a hipStream_t, may be
+ * NULL) and the stream is synchronised before returning.
+ * On success *out receives a layout to be released with dbsa_layout_destroy.
+ * Errors: INVALID_ARG, BAD_BOUNDS, BAD_SELECTION, HIP; *out is untouched then.
+ */
+int dbsa_layout_build(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, int32_t block_m, int32_t block_n,
+                      int32_t flags, void* stream, dbsa_layout** out);
+
+/*
+ * Host views of the lists, valid until the layout is destroyed.
+ *   qtile_tab : int32 [n_qtiles][4] = (q_start, q_len, owner, 0); owner is -1 for
+ *               the sink segment, else the group (pre-encode) or query index.
+ *   list_ptr  : int64 [n_qtiles+1] entry offsets.
+ *   list_ent  : int32 [n_ent][2] = (kv_start, kv_len | kind << 16).
+ * Any output pointer may be NULL.
+ */
+int dbsa_layout_export(const dbsa_layout* layout, const int32_t** qtile_tab, int64_t* n_qtiles,
+                       const int64_t** list_ptr, const int32_t** list_ent, int64_t* n_ent);
+
+/*
+ * Decode lists of a query-stage layout (INVALID_ARG for a pre-encode layout).
+ *   dec_ptr   : int64 [B+1] offsets of each query's pool entries in dec_ent.
+ *   dec_ent   : int32 [n_dec_ent][2], same encoding as list_ent, kinds all FULL.
+ *   split_ptr : int64 [B][n_split+1] absolute offsets into dec_ent.
+ */
+int dbsa_layout_export_decode(const dbsa_layout* layout, const int64_t** dec_ptr, const int32_t** dec_ent,
+                              int64_t* n_dec_ent, const int64_t** split_ptr, int32_t* n_split);
+
+/* Launch order of Q tiles (a permutation of [0, n_qtiles), longest list first). */
+int dbsa_layout_export_order(const dbsa_layout* layout, const int32_t** order, int64_t* n_order);
+
+void dbsa_layout_destroy(dbsa_layout* layout); /* NULL is allowed */
+
+/*
+ * Bytes of device workspace dbsa_decode_attn needs for this layout (split-KV
+ * partial states: B * n_q_heads * n_split * (head_dim + 2) floats).  The
+ * pre-encode and query calls need none.  Returns 0 for a pre-encode layout.
+ */
+size_t dbsa_workspace_bytes(const dbsa_layout* layout, int32_t n_q_heads, int32_t head_dim);
+
+/* A device tensor [tokens, heads, D]: element strides between tokens and heads. */
+typedef struct {
+  const void* ptr;     /* device pointer, 16-byte aligned            */
+  int64_t stride_tok;  /* elements; multiple of 8 (bf16) / 4 (fp32) */
+  int64_t stride_head; /* elements; multiple of 8 (bf16) / 4 (fp32) */
+} dbsa_tensor;
+
+/*
+ * Stage 1, many-shot encoding (Sec. 2.1): for every token i of the pool and every
+ * query head h,  O[i,h,:] = sum_j softmax_j(scale * q[i,h,:].k[j,h/r,:]) v[j,h/r,:]
+ * over the keys j the layout lists for i: the sink, the prev_window preceding
+ * groups, and the own group up to and including i.  Sink rows attend the sink
+ * causally.  r = n_q_heads / n_kv_heads (grouped-query attention, Sec. 4).
+ *
+ *   layout : a pre-encode layout with device lists.
+ *   q, o   : [N, n_q_heads, D];  k, v : [N, n_kv_heads, D];  o is written.
+ *   lse    : optional device float [n_q_heads][N]: natural-log softmax denominator.
+ *   dtype  : DBSA_BF16 (MFMA kernel; fp32 accumulation, bf16 output; needs
+ *            block_n == 64 and block_m in {32,64,128,256}) or DBSA_F32 (plain fp32
+ *            kernel, any tile sizes).  head_dim in {64, 128}.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP.
+ */
+int dbsa_preencode_attn(const dbsa_layout* layout, dbsa_tensor q, dbsa_tensor k, dbsa_tensor v, dbsa_tensor o,
+                        float* lse, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                        float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Stage 2, query prefill (Sec. 2.2): token a of query u attends the sink, every
+ * key of u's selected groups (read in place from the pool, no concatenation
+ * copy), and its own tokens b <= a; one softmax over the union.
+ *
+ *   layout                 : a query-stage layout with device lists.
+ *   q_self, o              : [sum T, n_q_heads, D], queries packed by cu_qlens.
+ *   k_self, v_self         : [sum T, n_kv_heads, D].
+ *   k_pool, v_pool         : [N, n_kv_heads, D].
+ *   lse                    : optional device float [n_q_heads][sum T].
+ * Same dtype / tile-size rules and errors as dbsa_preencode_attn.
+ */
+int dbsa_query_attn(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_tensor k_self, dbsa_tensor v_self,
+                    dbsa_tensor k_pool, dbsa_tensor v_pool, dbsa_tensor o, float* lse, int32_t dtype,
+                    int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale, void* workspace,
+                    size_t workspace_bytes, void* stream);
+
+/*
+ * Stage 2, one autoregressive step (Sec. 2.2): the new token of query u attends
+ * the sink, u's selected groups and ALL of u's own cached keys [0, self_len[u]).
+ * The caller appends the new token's K/V to the cache before the call and counts
+ * it in self_len.  Runs a split-KV pass (one partial softmax state per split) and
+ * a merge pass  m* = max m_s,  l* = sum l_s e^(m_s-m*),  o = sum acc_s e^(m_s-m*) / l*.
+ *
+ *   q_step, o               : [B, n_q_heads, D]  (stride_tok = stride between queries).
+ *   k_selfcache, v_selfcache: [B, Tmax, n_kv_heads, D]; stride_tok/stride_head as
+ *                             usual, stride_query elements between queries.
+ *   self_len                : device int32 [B], 1 <= self_len[u] <= Tmax.
+ *   workspace               : device memory of >= dbsa_workspace_bytes() bytes,
+ *                             16-byte aligned; contents are overwritten.
+ * Same dtype rules; block_n == 64 for DBSA_BF16.  Errors add WORKSPACE.
+ */
+int dbsa_decode_attn(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
+                     const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool, dbsa_tensor v_pool,
+                     dbsa_tensor o, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                     float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DBSA_H_ */

@@ -1,0 +1,264 @@
+// C-ABI entry points of libdbsa (declared in include/dbsa.h): argument checks, the
+// device mirror of a layout's lists, and kernel launches.  No arithmetic of the
+// method lives here.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "kernels.hpp"
+#include "layout.hpp"
+
+namespace {
+
+template <typename T>
+hipError_t upload(const std::vector<T>& host, T** dev, hipStream_t stream) {
+  *dev = nullptr;
+  const size_t bytes = std::max<size_t>(host.size() * sizeof(T), sizeof(T));
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(dev), bytes);
+  if (e != hipSuccess) return e;
+  if (host.empty()) return hipSuccess;
+  return hipMemcpyAsync(*dev, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice, stream);
+}
+
+void free_device_lists(dbsa_device_lists& d) {
+  if (d.qtile_tab) (void)hipFree(d.qtile_tab);
+  if (d.list_ptr) (void)hipFree(d.list_ptr);
+  if (d.list_ent) (void)hipFree(d.list_ent);
+  if (d.order) (void)hipFree(d.order);
+  if (d.dec_ent) (void)hipFree(d.dec_ent);
+  if (d.split_ptr) (void)hipFree(d.split_ptr);
+  d = dbsa_device_lists{};
+}
+
+bool tensor_ok(const dbsa_tensor& t, int dtype) {
+  const int64_t align_elems = dtype == DBSA_BF16 ? 8 : 4;
+  return t.ptr != nullptr && (reinterpret_cast<uintptr_t>(t.ptr) % 16 == 0) && t.stride_tok > 0 &&
+         t.stride_head > 0 && t.stride_tok % align_elems == 0 && t.stride_head % align_elems == 0;
+}
+
+TensorView view(const dbsa_tensor& t) { return TensorView{t.ptr, t.stride_tok, t.stride_head}; }
+
+int check_shapes(int32_t dtype, int32_t hq, int32_t hkv, int32_t d, float scale) {
+  if (dtype != DBSA_BF16 && dtype != DBSA_F32) return DBSA_ERR_UNSUPPORTED;
+  if (hq <= 0 || hkv <= 0 || !(scale > 0.f) || !std::isfinite(scale)) return DBSA_ERR_INVALID_ARG;
+  if (hq % hkv != 0) return DBSA_ERR_UNSUPPORTED;
+  if (d != 64 && d != 128) return DBSA_ERR_UNSUPPORTED;
+  return DBSA_OK;
+}
+
+// Largest number of query heads one workgroup can take so that heads * (block_m/32)
+// wavefronts <= 8 and the heads share one KV head.
+int pick_heads_per_block(int r, int block_m) {
+  const int subs = block_m / 32;
+  int best = 1;
+  for (int h = 1; h <= r; ++h)
+    if (r % h == 0 && h * subs <= 8) {
+      const int nw = h * subs;
+      if (nw == 1 || nw == 2 || nw == 4 || nw == 8) best = h;
+    }
+  return best;
+}
+
+bool mfma_tile_sizes_ok(const dbsa_layout* L) {
+  const int bm = L->block_m;
+  return L->block_n == 64 && (bm == 32 || bm == 64 || bm == 128 || bm == 256);
+}
+
+void fill_lists(AttnParams& p, const dbsa_layout* L) {
+  p.qtile_tab = L->dev.qtile_tab;
+  p.list_ptr = L->dev.list_ptr;
+  p.list_ent = L->dev.list_ent;
+  p.order = L->dev.order;
+  p.dec_ent = L->dev.dec_ent;
+  p.split_ptr = L->dev.split_ptr;
+  p.n_qtiles = static_cast<int32_t>(L->n_qtiles());
+  p.n_split = L->n_split;
+  p.n_queries = L->n_queries;
+  p.block_m = L->block_m;
+  p.block_n = L->block_n;
+}
+
+int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, dbsa_tensor k_self, dbsa_tensor v_self,
+                   dbsa_tensor k_pool, dbsa_tensor v_pool, dbsa_tensor o, float* lse, int32_t dtype, int32_t hq,
+                   int32_t hkv, int32_t d, float scale, void* stream) {
+  if (!L || !L->on_device || L->query_stage != want_query_stage) return DBSA_ERR_INVALID_ARG;
+  if (int rc = check_shapes(dtype, hq, hkv, d, scale)) return rc;
+  if (!tensor_ok(q, dtype) || !tensor_ok(k_pool, dtype) || !tensor_ok(v_pool, dtype) || !tensor_ok(o, dtype))
+    return DBSA_ERR_INVALID_ARG;
+  if (want_query_stage && (!tensor_ok(k_self, dtype) || !tensor_ok(v_self, dtype))) return DBSA_ERR_INVALID_ARG;
+  AttnParams p{};
+  fill_lists(p, L);
+  p.q = view(q);
+  p.o = view(o);
+  p.k_pool = view(k_pool);
+  p.v_pool = view(v_pool);
+  p.k_self = want_query_stage ? view(k_self) : view(k_pool);
+  p.v_self = want_query_stage ? view(v_self) : view(v_pool);
+  p.lse = lse;
+  p.lse_stride = want_query_stage ? L->n_query_tokens : L->n_tokens;
+  p.n_q_heads = hq;
+  p.n_kv_heads = hkv;
+  p.scale = scale;
+  p.scale_log2e = scale * 1.4426950408889634f;
+  hipError_t e;
+  if (dtype == DBSA_BF16) {
+    if (!mfma_tile_sizes_ok(L)) return DBSA_ERR_UNSUPPORTED;
+    p.heads_per_block = pick_heads_per_block(hq / hkv, L->block_m);
+    e = launch_prefill_mfma(p, d, static_cast<hipStream_t>(stream));
+  } else {
+    e = launch_prefill_plain(p, d, /*bf16_storage=*/false, static_cast<hipStream_t>(stream));
+  }
+  return e == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dbsa_strerror(int code) {
+  switch (code) {
+    case DBSA_OK: return "ok";
+    case DBSA_ERR_INVALID_ARG: return "invalid argument";
+    case DBSA_ERR_BAD_BOUNDS: return "offsets are not strictly increasing or not anchored as documented";
+    case DBSA_ERR_BAD_SELECTION: return "selected group out of range or listed twice";
+    case DBSA_ERR_UNSUPPORTED: return "unsupported head_dim, head ratio, dtype or tile size";
+    case DBSA_ERR_WORKSPACE: return "workspace missing or too small";
+    case DBSA_ERR_HIP: return "HIP runtime error";
+    default: return "unknown dbsa error code";
+  }
+}
+
+int dbsa_layout_build(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, int32_t block_m, int32_t block_n,
+                      int32_t flags, void* stream, dbsa_layout** out) {
+  if (!out || (flags & ~DBSA_LAYOUT_HOST_ONLY)) return DBSA_ERR_INVALID_ARG;
+  dbsa_layout* L = new (std::nothrow) dbsa_layout();
+  if (!L) return DBSA_ERR_INVALID_ARG;
+  int rc = DBSA_OK;
+  try {
+    rc = dbsa_build_host_lists(pool, sel, block_m, block_n, L);
+  } catch (...) {
+    rc = DBSA_ERR_INVALID_ARG;
+  }
+  if (rc != DBSA_OK) {
+    delete L;
+    return rc;
+  }
+  if (!(flags & DBSA_LAYOUT_HOST_ONLY)) {
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = upload(L->qtile_tab, &L->dev.qtile_tab, s);
+    if (e == hipSuccess) e = upload(L->list_ptr, &L->dev.list_ptr, s);
+    if (e == hipSuccess) e = upload(L->list_ent, &L->dev.list_ent, s);
+    if (e == hipSuccess) e = upload(L->order, &L->dev.order, s);
+    if (e == hipSuccess) e = upload(L->dec_ent, &L->dev.dec_ent, s);
+    if (e == hipSuccess) e = upload(L->split_ptr, &L->dev.split_ptr, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) {
+      free_device_lists(L->dev);
+      delete L;
+      return DBSA_ERR_HIP;
+    }
+    L->on_device = true;
+  }
+  *out = L;
+  return DBSA_OK;
+}
+
+int dbsa_layout_export(const dbsa_layout* L, const int32_t** qtile_tab, int64_t* n_qtiles, const int64_t** list_ptr,
+                       const int32_t** list_ent, int64_t* n_ent) {
+  if (!L) return DBSA_ERR_INVALID_ARG;
+  if (qtile_tab) *qtile_tab = L->qtile_tab.data();
+  if (n_qtiles) *n_qtiles = L->n_qtiles();
+  if (list_ptr) *list_ptr = L->list_ptr.data();
+  if (list_ent) *list_ent = L->list_ent.data();
+  if (n_ent) *n_ent = L->n_ent();
+  return DBSA_OK;
+}
+
+int dbsa_layout_export_decode(const dbsa_layout* L, const int64_t** dec_ptr, const int32_t** dec_ent,
+                              int64_t* n_dec_ent, const int64_t** split_ptr, int32_t* n_split) {
+  if (!L || !L->query_stage) return DBSA_ERR_INVALID_ARG;
+  if (dec_ptr) *dec_ptr = L->dec_ptr.data();
+  if (dec_ent) *dec_ent = L->dec_ent.data();
+  if (n_dec_ent) *n_dec_ent = static_cast<int64_t>(L->dec_ent.size() / 2);
+  if (split_ptr) *split_ptr = L->split_ptr.data();
+  if (n_split) *n_split = L->n_split;
+  return DBSA_OK;
+}
+
+int dbsa_layout_export_order(const dbsa_layout* L, const int32_t** order, int64_t* n_order) {
+  if (!L) return DBSA_ERR_INVALID_ARG;
+  if (order) *order = L->order.data();
+  if (n_order) *n_order = static_cast<int64_t>(L->order.size());
+  return DBSA_OK;
+}
+
+void dbsa_layout_destroy(dbsa_layout* L) {
+  if (!L) return;
+  if (L->on_device) free_device_lists(L->dev);
+  delete L;
+}
+
+size_t dbsa_workspace_bytes(const dbsa_layout* L, int32_t n_q_heads, int32_t head_dim) {
+  if (!L || !L->query_stage || n_q_heads <= 0 || head_dim <= 0) return 0;
+  return static_cast<size_t>(L->n_queries) * n_q_heads * L->n_split * (head_dim + 2) * sizeof(float);
+}
+
+int dbsa_preencode_attn(const dbsa_layout* layout, dbsa_tensor q, dbsa_tensor k, dbsa_tensor v, dbsa_tensor o,
+                        float* lse, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                        float softmax_scale, void* /*workspace*/, size_t /*workspace_bytes*/, void* stream) {
+  return prefill_common(layout, false, q, k, v, k, v, o, lse, dtype, n_q_heads, n_kv_heads, head_dim, softmax_scale,
+                        stream);
+}
+
+int dbsa_query_attn(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_tensor k_self, dbsa_tensor v_self,
+                    dbsa_tensor k_pool, dbsa_tensor v_pool, dbsa_tensor o, float* lse, int32_t dtype,
+                    int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale, void* /*workspace*/,
+                    size_t /*workspace_bytes*/, void* stream) {
+  return prefill_common(layout, true, q_self, k_self, v_self, k_pool, v_pool, o, lse, dtype, n_q_heads, n_kv_heads,
+                        head_dim, softmax_scale, stream);
+}
+
+int dbsa_decode_attn(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
+                     const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool, dbsa_tensor v_pool,
+                     dbsa_tensor o, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                     float softmax_scale, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!L || !L->on_device || !L->query_stage || !self_len) return DBSA_ERR_INVALID_ARG;
+  if (int rc = check_shapes(dtype, n_q_heads, n_kv_heads, head_dim, softmax_scale)) return rc;
+  if (!tensor_ok(q_step, dtype) || !tensor_ok(k_selfcache, dtype) || !tensor_ok(v_selfcache, dtype) ||
+      !tensor_ok(k_pool, dtype) || !tensor_ok(v_pool, dtype) || !tensor_ok(o, dtype))
+    return DBSA_ERR_INVALID_ARG;
+  const int64_t align_elems = dtype == DBSA_BF16 ? 8 : 4;
+  if (stride_query <= 0 || stride_query % align_elems != 0) return DBSA_ERR_INVALID_ARG;
+  AttnParams p{};
+  fill_lists(p, L);
+  p.q = view(q_step);
+  p.o = view(o);
+  p.k_pool = view(k_pool);
+  p.v_pool = view(v_pool);
+  p.k_self = view(k_selfcache);
+  p.v_self = view(v_selfcache);
+  p.stride_query = stride_query;
+  p.self_len = self_len;
+  p.n_q_heads = n_q_heads;
+  p.n_kv_heads = n_kv_heads;
+  p.scale = softmax_scale;
+  p.scale_log2e = softmax_scale * 1.4426950408889634f;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  if (dtype == DBSA_BF16) {
+    if (L->block_n != 64 || n_q_heads / n_kv_heads > 32) return DBSA_ERR_UNSUPPORTED;
+    const size_t need = dbsa_workspace_bytes(L, n_q_heads, head_dim);
+    if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
+      return DBSA_ERR_WORKSPACE;
+    p.partial = static_cast<float*>(workspace);
+    e = launch_decode_mfma(p, head_dim, s);
+    if (e == hipSuccess) e = launch_decode_merge(p, head_dim, /*out_bf16=*/true, s);
+  } else {
+    e = launch_decode_plain(p, head_dim, /*bf16_storage=*/false, s);
+  }
+  return e == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+// Launch parameters shared by api.hip and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+struct TensorView {
+  const void* ptr;
+  int64_t stride_tok;   // elements
+  int64_t stride_head;  // elements
+};
+
+// One description covers the three attention calls.  Prefill-shaped calls
+// (pre-encode, query) walk list_ent through list_ptr per Q tile; the decode call
+// walks dec_ent through split_ptr per (query, split) and then the query's own cache.
+struct AttnParams {
+  // lists (device)
+  const int32_t* qtile_tab;  // [n_qtiles][4]
+  const int64_t* list_ptr;   // [n_qtiles+1]
+  const int32_t* list_ent;   // [n_ent][2]
+  const int32_t* order;      // [n_qtiles]
+  const int32_t* dec_ent;    // [n_dec_ent][2]
+  const int64_t* split_ptr;  // [B][n_split+1]
+  int32_t n_qtiles, n_split, n_queries;
+  // tensors
+  TensorView q, o;            // rows: tokens (prefill) or queries (decode)
+  TensorView k_pool, v_pool;  // [N, Hkv, D]
+  TensorView k_self, v_self;  // prefill: [sum T, Hkv, D]; decode: cache of one query, + stride_query per query
+  int64_t stride_query;       // decode only (elements)
+  const int32_t* self_len;    // decode only, device [B]
+  float* lse;                 // optional [Hq][n_rows]
+  int64_t lse_stride;         // rows per head in lse
+  float* partial;             // decode: [B][Hq][n_split][D+2]
+  // shapes
+  int32_t n_q_heads, n_kv_heads, block_m, block_n;
+  int32_t heads_per_block;    // query heads handled by one workgroup (divides Hq/Hkv)
+  float scale;                // softmax scale
+  float scale_log2e;          // scale * log2(e)
+};
+
+// bf16 MFMA kernels (attn_mfma.hip)
+hipError_t launch_prefill_mfma(const AttnParams& p, int head_dim, hipStream_t stream);
+hipError_t launch_decode_mfma(const AttnParams& p, int head_dim, hipStream_t stream);
+hipError_t launch_decode_merge(const AttnParams& p, int head_dim, bool out_bf16, hipStream_t stream);
+
+// plain fp32-arithmetic kernels for fp32 or bf16 storage (attn_plain.hip)
+hipError_t launch_prefill_plain(const AttnParams& p, int head_dim, bool bf16_storage, hipStream_t stream);
+hipError_t launch_decode_plain(const AttnParams& p, int head_dim, bool bf16_storage, hipStream_t stream);

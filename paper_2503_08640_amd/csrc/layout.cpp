@@ -1,0 +1,167 @@
+// Host block-layout builder: pool structure (+ per-query group selections) ->
+// per-Q-tile lists of KV tiles.  Integer work only, no GPU calls.
+//
+// Stage 1 (Sec. 2.1): a group attends the anchor, a fixed number of preceding
+// groups, and itself causally, so the list of a Q tile is: every sink tile, every
+// tile of the preceding groups in the window, and the own group's tiles that start
+// at or before the tile's last row.  Stage 2 (Sec. 2.2): the selected groups' KV is
+// used in place -- the list simply names their tiles behind the sink's -- followed
+// by the query's own tiles up to the diagonal.
+#include "layout.hpp"
+
+#include <algorithm>
+#include <numeric>
+
+namespace {
+
+struct Seg {
+  int32_t begin, end;
+};
+
+inline int32_t pack_len_kind(int32_t len, int32_t kind) { return len | (kind << 16); }
+
+// Append the tiles of [seg.begin, seg.end) cut every `bn` tokens, all with `kind`.
+void push_whole_segment(std::vector<int32_t>& ent, Seg seg, int32_t bn, int32_t kind) {
+  for (int64_t k0 = seg.begin; k0 < seg.end; k0 += bn) {
+    ent.push_back(static_cast<int32_t>(k0));
+    ent.push_back(pack_len_kind(static_cast<int32_t>(std::min<int64_t>(bn, seg.end - k0)), kind));
+  }
+}
+
+// Append the tiles of `seg` a Q tile [q0, q0+qn) sees under a causal rule inside the
+// segment: a tile is listed when its first key is not after the tile's last row; it
+// needs no mask when its last key is not after the tile's first row.
+void push_causal_segment(std::vector<int32_t>& ent, Seg seg, int32_t bn, int32_t q0, int32_t qn, int32_t kind_full,
+                         int32_t kind_causal) {
+  const int64_t q_last = static_cast<int64_t>(q0) + qn - 1;
+  for (int64_t k0 = seg.begin; k0 < seg.end && k0 <= q_last; k0 += bn) {
+    const int64_t kn = std::min<int64_t>(bn, seg.end - k0);
+    const bool full = (k0 + kn - 1) <= q0;
+    ent.push_back(static_cast<int32_t>(k0));
+    ent.push_back(pack_len_kind(static_cast<int32_t>(kn), full ? kind_full : kind_causal));
+  }
+}
+
+bool strictly_increasing(const int32_t* a, int64_t n) {
+  for (int64_t i = 1; i < n; ++i)
+    if (a[i] <= a[i - 1]) return false;
+  return true;
+}
+
+}  // namespace
+
+int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, int32_t block_m, int32_t block_n,
+                          dbsa_layout* L) {
+  if (!pool || !L || block_m <= 0 || block_n <= 0 || block_n >= (1 << 16)) return DBSA_ERR_INVALID_ARG;
+  if (!pool->demo_offsets || !pool->group_demo_offsets || pool->n_demos < 1 || pool->n_groups < 1 ||
+      pool->sink_len < 0 || pool->prev_window < 0)
+    return DBSA_ERR_INVALID_ARG;
+  const int32_t S = pool->sink_len;
+  const int32_t* doff = pool->demo_offsets;
+  const int32_t* gdo = pool->group_demo_offsets;
+  if (doff[0] != S || !strictly_increasing(doff, static_cast<int64_t>(pool->n_demos) + 1)) return DBSA_ERR_BAD_BOUNDS;
+  if (gdo[0] != 0 || gdo[pool->n_groups] != pool->n_demos ||
+      !strictly_increasing(gdo, static_cast<int64_t>(pool->n_groups) + 1))
+    return DBSA_ERR_BAD_BOUNDS;
+
+  const int32_t G = pool->n_groups;
+  std::vector<Seg> group(G);
+  for (int32_t g = 0; g < G; ++g) group[g] = Seg{doff[gdo[g]], doff[gdo[g + 1]]};
+  const Seg sink{0, S};
+
+  L->block_m = block_m;
+  L->block_n = block_n;
+  L->sink_len = S;
+  L->n_tokens = doff[pool->n_demos];
+  L->n_groups = G;
+  L->prev_window = pool->prev_window;
+  L->query_stage = (sel != nullptr);
+  L->list_ptr.assign(1, 0);
+
+  auto close_tile = [&](int32_t q0, int32_t qn, int32_t owner) {
+    L->qtile_tab.insert(L->qtile_tab.end(), {q0, qn, owner, 0});
+    L->list_ptr.push_back(static_cast<int64_t>(L->list_ent.size() / 2));
+  };
+
+  if (!sel) {
+    // ---- stage 1 ----
+    for (int64_t q0 = 0; q0 < S; q0 += block_m) {
+      const int32_t qn = static_cast<int32_t>(std::min<int64_t>(block_m, S - q0));
+      push_causal_segment(L->list_ent, sink, block_n, static_cast<int32_t>(q0), qn, DBSA_TILE_FULL, DBSA_TILE_CAUSAL);
+      close_tile(static_cast<int32_t>(q0), qn, -1);
+    }
+    for (int32_t g = 0; g < G; ++g) {
+      const int32_t first_prev = std::max<int64_t>(0, static_cast<int64_t>(g) - pool->prev_window);
+      for (int64_t q0 = group[g].begin; q0 < group[g].end; q0 += block_m) {
+        const int32_t qn = static_cast<int32_t>(std::min<int64_t>(block_m, group[g].end - q0));
+        push_whole_segment(L->list_ent, sink, block_n, DBSA_TILE_FULL);
+        for (int32_t p = first_prev; p < g; ++p) push_whole_segment(L->list_ent, group[p], block_n, DBSA_TILE_FULL);
+        push_causal_segment(L->list_ent, group[g], block_n, static_cast<int32_t>(q0), qn, DBSA_TILE_FULL,
+                            DBSA_TILE_CAUSAL);
+        close_tile(static_cast<int32_t>(q0), qn, g);
+      }
+    }
+  } else {
+    // ---- stage 2 ----
+    if (sel->n_queries < 1 || !sel->cu_qlens || !sel->sel_ptr || sel->n_split < 0) return DBSA_ERR_INVALID_ARG;
+    const int32_t B = sel->n_queries;
+    if (sel->cu_qlens[0] != 0 || !strictly_increasing(sel->cu_qlens, static_cast<int64_t>(B) + 1))
+      return DBSA_ERR_BAD_BOUNDS;
+    if (sel->sel_ptr[0] != 0) return DBSA_ERR_BAD_BOUNDS;
+    for (int32_t u = 0; u < B; ++u)
+      if (sel->sel_ptr[u + 1] < sel->sel_ptr[u]) return DBSA_ERR_BAD_BOUNDS;
+    if (sel->sel_ptr[B] > 0 && !sel->sel_idx) return DBSA_ERR_INVALID_ARG;
+    std::vector<int32_t> seen(G, -1);
+    for (int32_t u = 0; u < B; ++u)
+      for (int32_t e = sel->sel_ptr[u]; e < sel->sel_ptr[u + 1]; ++e) {
+        const int32_t g = sel->sel_idx[e];
+        if (g < 0 || g >= G || seen[g] == u) return DBSA_ERR_BAD_SELECTION;
+        seen[g] = u;
+      }
+
+    L->n_queries = B;
+    L->n_query_tokens = sel->cu_qlens[B];
+    L->dec_ptr.assign(1, 0);
+    size_t shortest = SIZE_MAX;
+    for (int32_t u = 0; u < B; ++u) {
+      // pool part, shared by all Q tiles of the query and by decode
+      const size_t dec_begin = L->dec_ent.size();
+      push_whole_segment(L->dec_ent, sink, block_n, DBSA_TILE_FULL);
+      for (int32_t e = sel->sel_ptr[u]; e < sel->sel_ptr[u + 1]; ++e)
+        push_whole_segment(L->dec_ent, group[sel->sel_idx[e]], block_n, DBSA_TILE_FULL);
+      L->dec_ptr.push_back(static_cast<int64_t>(L->dec_ent.size() / 2));
+      shortest = std::min(shortest, (L->dec_ent.size() - dec_begin) / 2);
+
+      const Seg self{sel->cu_qlens[u], sel->cu_qlens[u + 1]};
+      for (int64_t q0 = self.begin; q0 < self.end; q0 += block_m) {
+        const int32_t qn = static_cast<int32_t>(std::min<int64_t>(block_m, self.end - q0));
+        L->list_ent.insert(L->list_ent.end(), L->dec_ent.begin() + dec_begin, L->dec_ent.end());
+        push_causal_segment(L->list_ent, self, block_n, static_cast<int32_t>(q0), qn, DBSA_TILE_SELF_FULL,
+                            DBSA_TILE_SELF_CAUSAL);
+        close_tile(static_cast<int32_t>(q0), qn, u);
+      }
+    }
+    // split count: enough (query, split) pairs to cover the chip a few times over
+    // once multiplied by the KV heads, but never more splits than tiles.
+    int32_t ns = sel->n_split;
+    if (ns == 0) {
+      ns = std::max(1, std::min(32, (256 + B - 1) / B));
+      ns = static_cast<int32_t>(std::max<size_t>(1, std::min<size_t>(ns, shortest)));
+    }
+    L->n_split = ns;
+    L->split_ptr.resize(static_cast<size_t>(B) * (ns + 1));
+    for (int32_t u = 0; u < B; ++u) {
+      const int64_t base = L->dec_ptr[u], len = L->dec_ptr[u + 1] - base;
+      for (int32_t s = 0; s <= ns; ++s) L->split_ptr[static_cast<size_t>(u) * (ns + 1) + s] = base + (s * len) / ns;
+    }
+  }
+
+  // launch order: longest list first (stable), so the tail of the grid is short work
+  const int64_t nt = L->n_qtiles();
+  L->order.resize(nt);
+  std::iota(L->order.begin(), L->order.end(), 0);
+  std::stable_sort(L->order.begin(), L->order.end(), [&](int32_t a, int32_t b) {
+    return (L->list_ptr[a + 1] - L->list_ptr[a]) > (L->list_ptr[b + 1] - L->list_ptr[b]);
+  });
+  return DBSA_OK;
+}

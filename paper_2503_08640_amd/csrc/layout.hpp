@@ -1,0 +1,42 @@
+// Internal definition of the opaque dbsa_layout object: host index lists built by
+// layout.cpp and their device mirrors filled in by api.hip.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "../../include/dbsa.h"
+
+struct dbsa_device_lists {
+  int32_t* qtile_tab = nullptr;   // [n_qtiles][4]
+  int64_t* list_ptr = nullptr;    // [n_qtiles+1]
+  int32_t* list_ent = nullptr;    // [n_ent][2]
+  int32_t* order = nullptr;       // [n_qtiles]
+  int32_t* dec_ent = nullptr;     // [n_dec_ent][2]
+  int64_t* split_ptr = nullptr;   // [B][n_split+1]
+};
+
+struct dbsa_layout {
+  bool query_stage = false;
+  bool on_device = false;
+  int32_t block_m = 0, block_n = 0;
+  int32_t sink_len = 0, n_tokens = 0, n_groups = 0, prev_window = 0;
+  int32_t n_queries = 0, n_query_tokens = 0, n_split = 0;
+
+  std::vector<int32_t> qtile_tab;   // 4 per tile
+  std::vector<int64_t> list_ptr;
+  std::vector<int32_t> list_ent;    // 2 per entry
+  std::vector<int32_t> order;
+  std::vector<int64_t> dec_ptr;     // [B+1]
+  std::vector<int32_t> dec_ent;     // 2 per entry
+  std::vector<int64_t> split_ptr;   // [B][n_split+1]
+
+  dbsa_device_lists dev;
+
+  int64_t n_qtiles() const { return static_cast<int64_t>(qtile_tab.size() / 4); }
+  int64_t n_ent() const { return static_cast<int64_t>(list_ent.size() / 2); }
+};
+
+// Pure host integer work; returns a DBSA_* code and fills `L` on success.
+int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, int32_t block_m, int32_t block_n,
+                          dbsa_layout* L);

@@ -1,0 +1,184 @@
+"""Host block-layout builder vs the tile-list oracle (bit-exact), error codes, and
+that the C-ABI library exports what include/dbsa.h declares.  CPU only: layouts
+are built with DBSA_LAYOUT_HOST_ONLY, no GPU call is made."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import layout_oracle as lo
+from paper_2503_08640_amd import binding as B
+from paper_2503_08640_amd import synth
+
+
+def rand_pool(rng, sink_len, n_groups, demos_per_group=(1, 4), demo_len=(1, 9)):
+    lens, gdo = [], [0]
+    for _ in range(n_groups):
+        nd = int(rng.integers(demos_per_group[0], demos_per_group[1] + 1))
+        lens += [int(rng.integers(demo_len[0], demo_len[1] + 1)) for _ in range(nd)]
+        gdo.append(len(lens))
+    offs = sink_len + np.concatenate([[0], np.cumsum(lens)])
+    return synth.Pool(sink_len, offs.astype(np.int32), np.asarray(gdo, np.int32))
+
+
+def assert_same_lists(got, want):
+    for g, w, name in zip(got, want, ("qtile_tab", "list_ptr", "list_ent")):
+        assert g.dtype == w.dtype, name
+        assert g.shape == w.shape, (name, g.shape, w.shape)
+        assert np.array_equal(g, w), name
+
+
+def test_library_exports_every_declared_symbol():
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    header = open(os.path.join(root, "include", "dbsa.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(dbsa_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTED_SYMBOLS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert B.strerror(B.DBSA_OK) == "ok"
+    assert "workspace" in B.strerror(B.DBSA_ERR_WORKSPACE)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_preencode_lists_match_oracle_on_random_pools(seed):
+    rng = np.random.default_rng(seed)
+    pool = rand_pool(rng, sink_len=int(rng.integers(0, 12)), n_groups=int(rng.integers(1, 6)))
+    w = int(rng.integers(0, 3))
+    bm, bn = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+    lay = B.dbsa_layout_build(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, w, block_m=bm, block_n=bn,
+                              host_only=True)
+    assert_same_lists(lay.export(), lo.preencode_layout(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets,
+                                                        w, bm, bn))
+    order = lay.export_order()
+    tab, ptr, _ = lay.export()
+    assert sorted(order.tolist()) == list(range(len(tab)))
+    lens = np.diff(ptr)[order]
+    assert np.all(lens[:-1] >= lens[1:])
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_query_and_decode_lists_match_oracle_on_random_inputs(seed):
+    rng = np.random.default_rng(50 + seed)
+    pool = rand_pool(rng, sink_len=int(rng.integers(0, 7)), n_groups=int(rng.integers(1, 7)))
+    nq = int(rng.integers(1, 5))
+    qlens = rng.integers(1, 12, size=nq)
+    cu = np.concatenate([[0], np.cumsum(qlens)]).astype(np.int32)
+    sels = [rng.permutation(pool.n_groups)[:int(rng.integers(0, pool.n_groups + 1))] for _ in range(nq)]
+    sel_ptr = np.concatenate([[0], np.cumsum([len(s) for s in sels])]).astype(np.int32)
+    sel_idx = np.concatenate(sels).astype(np.int32) if sel_ptr[-1] else np.zeros(0, np.int32)
+    bm, bn, ns = int(rng.integers(1, 7)), int(rng.integers(1, 7)), int(rng.integers(1, 5))
+    lay = B.dbsa_layout_build(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, cu_qlens=cu,
+                              sel_ptr=sel_ptr, sel_idx=sel_idx, n_split=ns, block_m=bm, block_n=bn, host_only=True)
+    assert_same_lists(lay.export(), lo.query_layout(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, cu,
+                                                    sel_ptr, sel_idx, bm, bn))
+    dec_ptr, dec_ent, split = lay.export_decode(nq)
+    o_ptr, o_ent, o_split = lo.decode_layout(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, nq, sel_ptr,
+                                             sel_idx, bn, ns)
+    assert np.array_equal(dec_ptr, o_ptr) and np.array_equal(dec_ent, o_ent) and np.array_equal(split, o_split)
+
+
+def test_config0_lists_match_oracle_and_counts():
+    pc = synth.config0_pool()
+    p = pc.pool
+    lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, 0, block_m=64, block_n=64,
+                              host_only=True)
+    got = lay.export()
+    assert_same_lists(got, lo.preencode_layout(p.sink_len, p.demo_offsets, p.group_demo_offsets, 0, 64, 64))
+    tab, ptr, ent = got
+    # sink tile + 2 groups x 2 tiles; lists: [sink], then per group (sink, diag), (sink, full, diag)
+    assert tab.tolist() == [[0, 4, -1, 0], [4, 64, 0, 0], [68, 64, 0, 0], [132, 64, 1, 0], [196, 64, 1, 0]]
+    assert np.diff(ptr).tolist() == [1, 2, 3, 2, 3]
+    qc = synth.config0_query(pc)
+    layq = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, cu_qlens=qc.cu_qlens,
+                               sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, n_split=2, block_m=64, block_n=64,
+                               host_only=True)
+    assert_same_lists(layq.export(), lo.query_layout(p.sink_len, p.demo_offsets, p.group_demo_offsets, qc.cu_qlens,
+                                                     qc.sel_ptr, qc.sel_idx, 64, 64))
+    _, _, qent = layq.export()
+    # sink, the two tiles of group 1, then the query's own 16 tokens under the causal rule
+    assert qent.tolist() == [[0, 4], [132, 64], [196, 64], [0, 16 | (3 << 16)]]
+
+
+def test_ragged_bf16_shape_lists_match_oracle():
+    """A cut-down config-1 pool (ragged demo lengths, groups that are no tile multiple)."""
+    pc_pool = synth.pack_groups(64, synth.draw_demo_lengths(np.random.default_rng(3), 4096, 32, 128), 4)
+    for bm in (64, 256):
+        lay = B.dbsa_layout_build(pc_pool.sink_len, pc_pool.demo_offsets, pc_pool.group_demo_offsets, 0, block_m=bm,
+                                  block_n=64, host_only=True)
+        assert_same_lists(lay.export(), lo.preencode_layout(pc_pool.sink_len, pc_pool.demo_offsets,
+                                                            pc_pool.group_demo_offsets, 0, bm, 64))
+
+
+def test_permuted_selection_gives_permuted_lists():
+    pc = synth.config0_pool()
+    p = pc.pool
+    cu, sel_ptr = np.array([0, 5], np.int32), np.array([0, 2], np.int32)
+    ents = []
+    for sel in ([0, 1], [1, 0]):
+        lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, cu_qlens=cu, sel_ptr=sel_ptr,
+                                  sel_idx=np.array(sel, np.int32), n_split=1, block_m=64, block_n=64, host_only=True)
+        ents.append(lay.export()[2])
+    a, b = ents
+    assert a[0].tolist() == b[0].tolist()                      # sink first in both
+    assert a[1:3].tolist() == b[3:5].tolist() and a[3:5].tolist() == b[1:3].tolist()
+    assert a[5:].tolist() == b[5:].tolist()                    # self tiles last
+
+
+def _build(pool_kw=None, sel_kw=None, **kw):
+    pc = synth.config0_pool().pool
+    args = dict(sink_len=pc.sink_len, demo_offsets=pc.demo_offsets, group_demo_offsets=pc.group_demo_offsets)
+    args.update(pool_kw or {})
+    return B.dbsa_layout_build(args["sink_len"], args["demo_offsets"], args["group_demo_offsets"], 0,
+                               host_only=True, **(sel_kw or {}), **kw)
+
+
+@pytest.mark.parametrize("pool_kw,sel_kw,code", [
+    (dict(sink_len=3), None, B.DBSA_ERR_BAD_BOUNDS),                                   # demo_offsets[0] != S
+    (dict(demo_offsets=[4, 36, 36, 100]), None, B.DBSA_ERR_BAD_BOUNDS),                # not strictly increasing
+    (dict(group_demo_offsets=[0, 4, 9]), None, B.DBSA_ERR_BAD_BOUNDS),                 # last != n_demos
+    (dict(group_demo_offsets=[1, 4, 8]), None, B.DBSA_ERR_BAD_BOUNDS),                 # first != 0
+    (None, dict(cu_qlens=[0, 4], sel_ptr=[0, 2], sel_idx=[1, 1]), B.DBSA_ERR_BAD_SELECTION),   # duplicate
+    (None, dict(cu_qlens=[0, 4], sel_ptr=[0, 1], sel_idx=[2]), B.DBSA_ERR_BAD_SELECTION),      # out of range
+    (None, dict(cu_qlens=[0, 4], sel_ptr=[0, 1], sel_idx=[-1]), B.DBSA_ERR_BAD_SELECTION),
+    (None, dict(cu_qlens=[0, 4, 4], sel_ptr=[0, 0, 0], sel_idx=[]), B.DBSA_ERR_BAD_BOUNDS),    # empty query
+    (None, dict(cu_qlens=[1, 4], sel_ptr=[0, 0], sel_idx=[]), B.DBSA_ERR_BAD_BOUNDS),
+    (None, dict(cu_qlens=[0, 4], sel_ptr=[0, 0], sel_idx=[], n_split=-1), B.DBSA_ERR_INVALID_ARG),
+])
+def test_malformed_inputs_are_rejected(pool_kw, sel_kw, code):
+    with pytest.raises(B.DbsaError) as ei:
+        _build(pool_kw, sel_kw)
+    assert ei.value.code == code
+
+
+def test_bad_tile_sizes_and_flags_are_rejected():
+    for kw in (dict(block_m=0), dict(block_n=0), dict(block_n=1 << 16)):
+        with pytest.raises(B.DbsaError) as ei:
+            _build(**kw)
+        assert ei.value.code == B.DBSA_ERR_INVALID_ARG
+
+
+def test_empty_selection_and_same_group_in_two_queries_are_valid():
+    lay = _build(sel_kw=dict(cu_qlens=[0, 4, 9], sel_ptr=[0, 0, 1], sel_idx=[1]))
+    tab, ptr, ent = lay.export()
+    assert np.diff(ptr).tolist() == [2, 4]          # (sink, self) and (sink, 2 group tiles, self)
+    lay2 = _build(sel_kw=dict(cu_qlens=[0, 4, 9], sel_ptr=[0, 1, 2], sel_idx=[1, 1]))
+    assert lay2.export()[0].shape[0] == 2
+
+
+def test_host_only_layout_cannot_run_attention_and_workspace_size():
+    lay = _build(sel_kw=dict(cu_qlens=[0, 4, 9], sel_ptr=[0, 0, 1], sel_idx=[1], n_split=3))
+    assert lay.workspace_bytes(32, 128) == 2 * 32 * 3 * 130 * 4
+    pre = _build()
+    assert pre.workspace_bytes(32, 128) == 0
+    t = B.Tensor(16, 8, 8)
+    rc = B.lib().dbsa_preencode_attn(pre.handle, t, t, t, t, None, B.DBSA_BF16, 2, 2, 64, 0.125, None, 0, None)
+    assert rc == B.DBSA_ERR_INVALID_ARG
+
+
+def test_default_split_count_is_bounded_by_list_length():
+    lay = _build(sel_kw=dict(cu_qlens=[0, 4], sel_ptr=[0, 0], sel_idx=[]))   # one sink tile only
+    _, _, split = lay.export_decode(1)
+    assert split.shape == (1, 2)
