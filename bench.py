@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the DBSA attention hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of seeded synthetic input at
+the 90k-token / 30 %-retrieval workload: pre-encode layout build + block-sparse
+pre-encode attention over the 90k pool (Llama-3.1-8B shape, GQA 32/8 x 128), then
+query layout build + query prefill (16 queries x 64 tokens, 7 of 22 groups each)
++ 32 split-KV decode steps against the same selections.  Inputs are resident in
+HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+PRE_BLOCK_M = 64            # tokens per Q tile at pre-encode (x 4 query heads of one KV head per workgroup)
+QUERY_BLOCK_M = 64
+
+
+def visible_pairs_pre(pool) -> int:
+    """Closed-form count of visible (row, key) pairs of the stage-1 pattern with no
+    preceding-group window: sink triangle + per group L*S + L(L+1)/2."""
+    s = pool.sink_len
+    lens = np.diff(pool.group_token_bounds()).astype(np.int64)
+    return s * (s + 1) // 2 + int((lens * s + lens * (lens + 1) // 2).sum())
+
+
+def selected_keys(pool, qc) -> np.ndarray:
+    lens = np.diff(pool.group_token_bounds()).astype(np.int64)
+    return np.array([pool.sink_len + int(lens[qc.sel_idx[qc.sel_ptr[u]:qc.sel_ptr[u + 1]]].sum())
+                     for u in range(qc.n_queries)], dtype=np.int64)
+
+
+def load_traffic(kernel: str):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (profiles/hbm_traffic.json)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    try:
+        return json.load(open(path)).get(kernel, {}).get("bytes_per_launch")
+    except Exception:
+        return None
+
+
+def cpu_baseline(pc, n_rows: int = 512):
+    """The fp64 oracle, as it stands, on a bounded sample of pre-encode rows."""
+    from oracle import dbsa_oracle as orc
+    from paper_2503_08640_amd import synth
+    p = pc.pool
+    rng = np.random.default_rng(4242)
+    rows = np.sort(rng.choice(p.n_tokens, size=n_rows, replace=False))
+    q, k, v = synth.as_f64(pc.q), synth.as_f64(pc.k), synth.as_f64(pc.v)
+    t0 = time.perf_counter()
+    orc.preencode_attn(q, k, v, p.sink_len, p.demo_offsets, p.group_demo_offsets, pc.scale,
+                       pc.prev_window, rows=rows)
+    dt = time.perf_counter() - t0
+    gb = p.group_token_bounds()
+    g = np.searchsorted(gb, rows, side="right") - 1
+    vis = np.where(rows < p.sink_len, rows + 1, p.sink_len + rows - gb[np.maximum(g, 0)] + 1)
+    flops = 4.0 * pc.head_dim * float(vis.sum()) * pc.n_q_heads
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"pre-encode, {n_rows} seeded random rows x {pc.n_q_heads} heads, each scored densely in fp64 "
+                      f"against all {p.n_tokens} keys ({dt:.1f} s); useful (visible-pair) flops counted",
+            "rows_per_s": n_rows / dt}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2503_08640_amd import binding as B
+    from paper_2503_08640_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    B.lib()  # fail loudly if the HIP library is not built
+
+    # ---- seeded synthetic inputs, resident in HBM ----
+    pc = synth.config2_pool()
+    qc = synth.config3_query(pc)
+    p = pc.pool
+
+    def dev(x):
+        return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+
+    q, k, v = dev(pc.q), dev(pc.k), dev(pc.v)
+    o = torch.empty_like(q)
+    qs, ks, vs = dev(qc.q), dev(qc.k), dev(qc.v)
+    oq = torch.empty_like(qs)
+    shp = qc.k_cache.shape
+    kc, vc = dev(qc.k_cache.reshape(-1, shp[2], shp[3])).view(shp), dev(qc.v_cache.reshape(-1, shp[2], shp[3])).view(shp)
+    dq = dev(qc.dec_q.reshape(-1, pc.n_q_heads, pc.head_dim)).view(qc.dec_q.shape)
+    od = torch.empty_like(dq[0])
+    lens = np.diff(qc.cu_qlens)
+    self_lens = [torch.from_numpy((lens + s + 1).astype(np.int32)).cuda() for s in range(qc.n_decode)]
+    hq, hkv, d = pc.n_q_heads, pc.n_kv_heads, pc.head_dim
+
+    # ---- algorithmic work of one step ----
+    pairs_pre = visible_pairs_pre(p)
+    keys = selected_keys(p, qc)
+    t_q = int(lens[0])
+    flops_pre = 4.0 * d * pairs_pre * hq
+    flops_query = 4.0 * d * hq * float((lens * keys).sum() + (lens * (lens + 1) // 2).sum())
+    flops_decode = sum(4.0 * d * hq * float((keys + lens + s + 1).sum()) for s in range(qc.n_decode))
+    bytes_decode_step = float((keys + lens + (qc.n_decode + 1) / 2.0).sum()) * hkv * d * 2 * 2
+    flops_step = flops_pre + flops_query + flops_decode
+
+    ws_holder = {}
+
+    def step(ev=None):
+        t0 = time.perf_counter()
+        lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, 0, block_m=PRE_BLOCK_M,
+                                  block_n=64)
+        t1 = time.perf_counter()
+        if ev: ev[0].record()
+        B.dbsa_preencode_attn(lay, q, k, v, pc.scale, out=o)
+        if ev: ev[1].record()
+        t2 = time.perf_counter()
+        layq = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, cu_qlens=qc.cu_qlens,
+                                   sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, n_split=0, block_m=QUERY_BLOCK_M,
+                                   block_n=64)
+        t3 = time.perf_counter()
+        need = layq.workspace_bytes(hq, d)
+        if ws_holder.get("n", 0) < need:
+            ws_holder["t"] = torch.empty(need, dtype=torch.uint8, device="cuda")
+            ws_holder["n"] = need
+        if ev: ev[2].record()
+        B.dbsa_query_attn(layq, qs, ks, vs, k, v, pc.scale, out=oq)
+        if ev: ev[3].record()
+        for s in range(qc.n_decode):
+            B.dbsa_decode_attn(layq, dq[s], kc, vc, self_lens[s], k, v, pc.scale, out=od, workspace=ws_holder["t"])
+        if ev: ev[4].record()
+        return (t1 - t0) + (t3 - t2)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    layout_s = 0.0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        layout_s += step(evs[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_step = elapsed * 1e3 / args.steps
+    pre_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    query_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+    decode_ms = float(np.mean([e[3].elapsed_time(e[4]) for e in evs])) / qc.n_decode
+    pre_tflops = flops_pre / pre_ms / 1e9
+    dec_gbs = bytes_decode_step / decode_ms / 1e6
+
+    out = {
+        "metric": "useful attn TFLOP/s + query-stage ms @90k-token pool, 30% retrieval, 1 GPU",
+        "value": flops_step / (ms_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {
+            "workload": "config 2 pre-encode (90k pool, GQA 32/8 x 128, 22 groups, sink 64) + config 3 query stage "
+                        "(16 queries x 64 tokens, 7 of 22 groups each, 32 decode steps)",
+            "pool_tokens": int(p.n_tokens), "n_groups": int(p.n_groups), "n_queries": int(qc.n_queries),
+            "query_len": t_q, "groups_per_query": int(qc.sel_ptr[1]), "decode_steps": int(qc.n_decode),
+            "block_m_preencode": PRE_BLOCK_M, "block_m_query": QUERY_BLOCK_M, "block_n": 64,
+        },
+        "stages": {
+            "preencode_ms": pre_ms, "preencode_useful_tflops": pre_tflops,
+            "query_prefill_ms": query_ms, "query_prefill_useful_tflops": flops_query / query_ms / 1e9,
+            "decode_step_ms": decode_ms, "query_stage_ms": query_ms + decode_ms * qc.n_decode,
+            "layout_build_ms_per_step": layout_s * 1e3 / args.steps,
+            "useful_tflop_per_step": flops_step / 1e12,
+        },
+        "roofline": {
+            "kernel": "attn_mfma_kernel<128,8,prefill> (pre-encode)", "bound": "mfma", "achieved": pre_tflops,
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": pre_tflops / PEAK_BF16_TFLOPS,
+            "traffic": load_traffic("preencode"),
+        },
+        "roofline_decode": {
+            "kernel": "attn_mfma_kernel<128,1,decode> + decode_merge_kernel (one step)", "bound": "hbm",
+            "achieved": dec_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
+            "traffic": load_traffic("decode_step"),
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(pc)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -206,10 +206,11 @@ def query_attn(q_self: np.ndarray, k_self: np.ndarray, v_self: np.ndarray, k_poo
         a = np.arange(t)
         self_vis = a[None, :] <= a[:, None]                     # b <= a
         mask = np.concatenate([np.broadcast_to(pool_vis, (t, n)), self_vis], axis=1)
-        for h in range(hq):
-            kk = np.concatenate([k_pool[:, h // r, :], k_self[t0:t1, h // r, :]], axis=0)
-            vv = np.concatenate([v_pool[:, h // r, :], v_self[t0:t1, h // r, :]], axis=0)
-            out[t0:t1, h, :] = masked_softmax_attend(q_self[t0:t1, h, :], kk, vv, mask, scale)
+        for hk in range(hkv):                                   # candidate keys: [pool ; own tokens]
+            kk = np.concatenate([k_pool[:, hk, :], k_self[t0:t1, hk, :]], axis=0)
+            vv = np.concatenate([v_pool[:, hk, :], v_self[t0:t1, hk, :]], axis=0)
+            for h in range(hk * r, (hk + 1) * r):
+                out[t0:t1, h, :] = masked_softmax_attend(q_self[t0:t1, h, :], kk, vv, mask, scale)
     return out
 
 
@@ -231,10 +232,11 @@ def decode_attn(q_step: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, se
         pool_vis = mask_query_pool(_query_selected(sel_ptr, sel_idx, u), sink_len, group_of)
         self_vis = np.arange(t_max) < int(self_len[u])
         mask = np.concatenate([pool_vis, self_vis])[None, :]
-        for h in range(hq):
-            kk = np.concatenate([k_pool[:, h // r, :], k_cache[u, :, h // r, :]], axis=0)
-            vv = np.concatenate([v_pool[:, h // r, :], v_cache[u, :, h // r, :]], axis=0)
-            out[u, h, :] = masked_softmax_attend(q_step[u:u + 1, h, :], kk, vv, mask, scale)[0]
+        for hk in range(hkv):                                   # candidate keys: [pool ; own cache]
+            kk = np.concatenate([k_pool[:, hk, :], k_cache[u, :, hk, :]], axis=0)
+            vv = np.concatenate([v_pool[:, hk, :], v_cache[u, :, hk, :]], axis=0)
+            out[u, hk * r:(hk + 1) * r, :] = masked_softmax_attend(q_step[u, hk * r:(hk + 1) * r, :], kk, vv,
+                                                                   np.broadcast_to(mask, (r, mask.shape[1])), scale)
     return out
 
 

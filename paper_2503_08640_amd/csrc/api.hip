@@ -12,23 +12,47 @@
 
 namespace {
 
-template <typename T>
-hipError_t upload(const std::vector<T>& host, T** dev, hipStream_t stream) {
-  *dev = nullptr;
-  const size_t bytes = std::max<size_t>(host.size() * sizeof(T), sizeof(T));
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(dev), bytes);
+// Copy every list into ONE device allocation (a single hipMalloc and a single copy):
+// the lists are small and the allocation calls, not the bytes, dominate the cost.
+hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
+  auto pad = [](size_t n) { return (n + 255) / 256 * 256; };
+  const size_t b_tab = L->qtile_tab.size() * sizeof(int32_t), b_ptr = L->list_ptr.size() * sizeof(int64_t),
+               b_ent = L->list_ent.size() * sizeof(int32_t), b_ord = L->order.size() * sizeof(int32_t),
+               b_dec = L->dec_ent.size() * sizeof(int32_t), b_spl = L->split_ptr.size() * sizeof(int64_t);
+  const size_t o_tab = 0, o_ptr = o_tab + pad(b_tab), o_ent = o_ptr + pad(b_ptr), o_ord = o_ent + pad(b_ent),
+               o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), total = o_spl + pad(b_spl) + 256;
+  std::vector<unsigned char> staging(total, 0);
+  auto put = [&](size_t off, const void* src, size_t bytes) {
+    if (bytes) std::memcpy(staging.data() + off, src, bytes);
+  };
+  put(o_tab, L->qtile_tab.data(), b_tab);
+  put(o_ptr, L->list_ptr.data(), b_ptr);
+  put(o_ent, L->list_ent.data(), b_ent);
+  put(o_ord, L->order.data(), b_ord);
+  put(o_dec, L->dec_ent.data(), b_dec);
+  put(o_spl, L->split_ptr.data(), b_spl);
+  void* base = nullptr;
+  hipError_t e = hipMalloc(&base, total);
   if (e != hipSuccess) return e;
-  if (host.empty()) return hipSuccess;
-  return hipMemcpyAsync(*dev, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice, stream);
+  e = hipMemcpyAsync(base, staging.data(), total, hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);  // staging is freed on return
+  if (e != hipSuccess) {
+    (void)hipFree(base);
+    return e;
+  }
+  unsigned char* b = static_cast<unsigned char*>(base);
+  L->dev.base = base;
+  L->dev.qtile_tab = reinterpret_cast<int32_t*>(b + o_tab);
+  L->dev.list_ptr = reinterpret_cast<int64_t*>(b + o_ptr);
+  L->dev.list_ent = reinterpret_cast<int32_t*>(b + o_ent);
+  L->dev.order = reinterpret_cast<int32_t*>(b + o_ord);
+  L->dev.dec_ent = reinterpret_cast<int32_t*>(b + o_dec);
+  L->dev.split_ptr = reinterpret_cast<int64_t*>(b + o_spl);
+  return hipSuccess;
 }
 
 void free_device_lists(dbsa_device_lists& d) {
-  if (d.qtile_tab) (void)hipFree(d.qtile_tab);
-  if (d.list_ptr) (void)hipFree(d.list_ptr);
-  if (d.list_ent) (void)hipFree(d.list_ent);
-  if (d.order) (void)hipFree(d.order);
-  if (d.dec_ent) (void)hipFree(d.dec_ent);
-  if (d.split_ptr) (void)hipFree(d.split_ptr);
+  if (d.base) (void)hipFree(d.base);
   d = dbsa_device_lists{};
 }
 
@@ -146,16 +170,8 @@ int dbsa_layout_build(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, i
     return rc;
   }
   if (!(flags & DBSA_LAYOUT_HOST_ONLY)) {
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = upload(L->qtile_tab, &L->dev.qtile_tab, s);
-    if (e == hipSuccess) e = upload(L->list_ptr, &L->dev.list_ptr, s);
-    if (e == hipSuccess) e = upload(L->list_ent, &L->dev.list_ent, s);
-    if (e == hipSuccess) e = upload(L->order, &L->dev.order, s);
-    if (e == hipSuccess) e = upload(L->dec_ent, &L->dev.dec_ent, s);
-    if (e == hipSuccess) e = upload(L->split_ptr, &L->dev.split_ptr, s);
-    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    const hipError_t e = upload_lists(L, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) {
-      free_device_lists(L->dev);
       delete L;
       return DBSA_ERR_HIP;
     }

@@ -8,6 +8,7 @@
 #include "../../include/dbsa.h"
 
 struct dbsa_device_lists {
+  void* base = nullptr;           // one allocation holds every list below
   int32_t* qtile_tab = nullptr;   // [n_qtiles][4]
   int64_t* list_ptr = nullptr;    // [n_qtiles+1]
   int32_t* list_ent = nullptr;    // [n_ent][2]

@@ -1,0 +1,178 @@
+"""GPU parity at the full sizes of configs 1-4, in the launch configuration the
+benchmark times.  The fp64 oracle scores a seeded sample of rows (dense over all
+keys); rows outside the sample are covered by closed-form probes that need no
+oracle: the Q = 0 mask probe (exact visible-set size of EVERY row), constant V,
+and run-twice bitwise determinism."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dbsa_oracle as orc
+from paper_2503_08640_amd import binding as B
+from paper_2503_08640_amd import synth
+from gpu_util import assert_close, to_dev, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(pool, seed, n_random=96, edge=70):
+    """Random rows + the sink + first/last rows of the first, a middle and the last group
+    + the demo boundaries of one group."""
+    rng = np.random.default_rng(seed)
+    gb = pool.group_token_bounds()
+    rows = set(rng.choice(pool.n_tokens, size=n_random, replace=False).tolist())
+    rows |= set(range(pool.sink_len))
+    for g in (0, pool.n_groups // 2, pool.n_groups - 1):
+        rows |= set(range(int(gb[g]), int(gb[g]) + edge)) | set(range(int(gb[g + 1]) - edge, int(gb[g + 1])))
+    g = min(1, pool.n_groups - 1)
+    d0, d1 = pool.group_demo_offsets[g], pool.group_demo_offsets[g + 1]
+    for b in pool.demo_offsets[d0:d1 + 1][:24]:
+        rows |= {int(b) - 1, int(b)} & set(range(pool.n_tokens))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+def preencode_fullsize(pc, block_m, what):
+    p = pc.pool
+    print(f"[case] {what}: N={p.n_tokens} Hq={pc.n_q_heads} Hkv={pc.n_kv_heads} bm={block_m}", flush=True)
+    lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, 0, block_m=block_m, block_n=64)
+    q, k, v = to_dev(pc.q), to_dev(pc.k), to_dev(pc.v)
+    o = B.dbsa_preencode_attn(lay, q, k, v, pc.scale)
+    o2 = B.dbsa_preencode_attn(lay, q, k, v, pc.scale)
+    torch.cuda.synchronize()
+    assert torch.equal(o.view(torch.int16), o2.view(torch.int16)), "two runs differ bitwise"
+    rows = sample_rows(p, pc.seed)
+    ref = orc.preencode_attn(synth.as_f64(pc.q), synth.as_f64(pc.k), synth.as_f64(pc.v), p.sink_len, p.demo_offsets,
+                             p.group_demo_offsets, pc.scale, rows=rows)
+    assert_close(to_f64(o[torch.from_numpy(rows).cuda()]), ref, f"{what}, {len(rows)} sampled rows")
+
+    # closed-form probes over every row: Q = 0 gives uniform weights over the visible set
+    gb = p.group_token_bounds().astype(np.int64)
+    tok = np.arange(p.n_tokens, dtype=np.int64)
+    grp = np.searchsorted(gb, tok, side="right") - 1
+    n_vis = np.where(tok < p.sink_len, tok + 1, p.sink_len + tok - gb[np.maximum(grp, 0)] + 1)
+    vprobe = torch.zeros_like(v)
+    vprobe[:, :, 0] = 1.0                                    # every visible key counts 1
+    vprobe[: p.sink_len, :, 1] = 1.0                         # sink keys
+    vprobe[:, :, 2] = torch.from_numpy((tok % 2).astype(np.float32)).cuda()[:, None].to(v.dtype)  # odd tokens
+    vprobe[:, :, 3] = 0.5                                    # a constant channel
+    oz = to_f64(B.dbsa_preencode_attn(lay, torch.zeros_like(q), k, vprobe, pc.scale))
+    assert np.abs(oz[:, :, 0] - 1.0).max() <= 2 ** -8
+    assert np.abs(oz[:, :, 3] - 0.5).max() <= 2 ** -9
+    sink_seen = np.minimum(tok + 1, p.sink_len)
+    # bf16 output rounding is at most 2^-8 relative, so the recovered count is off by <= S * 2^-8 < 1/2
+    assert np.abs(oz[:, :, 1] * n_vis[:, None] - sink_seen[:, None]).max() <= max(1, p.sink_len) * 2.0 ** -8 + 1e-6
+    lo_tok = np.where(tok < p.sink_len, 0, gb[np.maximum(grp, 0)])
+    odd_own = (tok + 1) // 2 - lo_tok // 2                   # odd tokens in [lo_tok, tok]
+    odd_sink = np.where(tok < p.sink_len, 0, p.sink_len // 2)
+    want = (odd_own + odd_sink) / n_vis
+    assert np.abs(oz[:, :, 2] - want[:, None]).max() <= 2 ** -8
+
+
+def test_config1_preencode_full_size():
+    preencode_fullsize(synth.config1_pool(), 256, "cfg1 pre-encode")
+
+
+def test_config2_preencode_full_size():
+    preencode_fullsize(synth.config2_pool(), 64, "cfg2 pre-encode")
+
+
+def _query_fullsize(pc, qc, block_m, oracle_queries, decode_steps, what):
+    p = pc.pool
+    print(f"[case] {what}: B={qc.n_queries} T={int(qc.cu_qlens[1])} m={int(qc.sel_ptr[1])} bm={block_m}", flush=True)
+    lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, cu_qlens=qc.cu_qlens,
+                              sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, n_split=0, block_m=block_m, block_n=64)
+    kp, vp = to_dev(pc.k), to_dev(pc.v)
+    kp64, vp64 = synth.as_f64(pc.k), synth.as_f64(pc.v)
+    oq = B.dbsa_query_attn(lay, to_dev(qc.q), to_dev(qc.k), to_dev(qc.v), kp, vp, pc.scale)
+    ref = orc.query_attn(synth.as_f64(qc.q), synth.as_f64(qc.k), synth.as_f64(qc.v), kp64, vp64, p.sink_len,
+                         p.demo_offsets, p.group_demo_offsets, qc.cu_qlens, qc.sel_ptr, qc.sel_idx, pc.scale,
+                         queries=oracle_queries)
+    rows = np.concatenate([np.arange(qc.cu_qlens[u], qc.cu_qlens[u + 1]) for u in oracle_queries])
+    assert_close(to_f64(oq)[rows], ref[rows], f"{what} prefill, queries {list(oracle_queries)}")
+    shp = qc.k_cache.shape
+    kc = to_dev(qc.k_cache.reshape(-1, shp[2], shp[3])).view(shp)
+    vc = to_dev(qc.v_cache.reshape(-1, shp[2], shp[3])).view(shp)
+    kc64, vc64 = synth.as_f64(qc.k_cache), synth.as_f64(qc.v_cache)
+    lens = np.diff(qc.cu_qlens)
+    for s in decode_steps:
+        self_len = (lens + s + 1).astype(np.int32)
+        od = B.dbsa_decode_attn(lay, to_dev(qc.dec_q[s]), kc, vc, torch.from_numpy(self_len).cuda(), kp, vp, pc.scale)
+        refd = orc.decode_attn(synth.as_f64(qc.dec_q[s]), kc64, vc64, self_len, kp64, vp64, p.sink_len,
+                               p.demo_offsets, p.group_demo_offsets, qc.sel_ptr, qc.sel_idx, pc.scale,
+                               queries=oracle_queries)
+        assert_close(to_f64(od)[list(oracle_queries)], refd[list(oracle_queries)], f"{what} decode step {s}")
+    return lay, kp, vp
+
+
+@pytest.fixture(scope="module")
+def cfg2():
+    return synth.config2_pool()
+
+
+def test_config3_query_stage_full_size(cfg2):
+    qc = synth.config3_query(cfg2)
+    assert int(qc.sel_ptr[1]) == 7
+    _query_fullsize(cfg2, qc, 64, oracle_queries=(0, 7, 15), decode_steps=(0, 31), what="cfg3")
+
+
+@pytest.mark.parametrize("ratio", synth.RETRIEVAL_RATIOS)
+def test_config4_sweep_full_size(cfg2, ratio):
+    qc = synth.config4_query(cfg2, ratio)
+    assert int(qc.sel_ptr[1]) == {0.10: 2, 0.30: 7, 0.50: 11, 1.00: 22}[ratio]
+    _query_fullsize(cfg2, qc, 32, oracle_queries=(0, 127), decode_steps=(0,), what=f"cfg4 ratio {ratio}")
+
+
+def test_config4_full_retrieval_equals_dense_causal(cfg2):
+    """At 100 % retrieval the query rows are rows of dense causal attention over
+    [pool ; query] (cached many-shot ICL over the whole pool, Sec. 3 Baselines); checked
+    against a textbook fp64 routine instead of the oracle."""
+    qc = synth.config4_query(cfg2, 1.00)
+    p = cfg2.pool
+    lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, cu_qlens=qc.cu_qlens,
+                              sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, n_split=0, block_m=32, block_n=64)
+    oq = to_f64(B.dbsa_query_attn(lay, to_dev(qc.q), to_dev(qc.k), to_dev(qc.v), to_dev(cfg2.k), to_dev(cfg2.v),
+                                  cfg2.scale))
+    u = 3
+    t0, t1 = int(qc.cu_qlens[u]), int(qc.cu_qlens[u + 1])
+    n = p.n_tokens
+    r = cfg2.n_q_heads // cfg2.n_kv_heads
+    kk = torch.from_numpy(np.concatenate([synth.as_f64(cfg2.k), synth.as_f64(qc.k[t0:t1])])).permute(1, 0, 2)
+    vv = torch.from_numpy(np.concatenate([synth.as_f64(cfg2.v), synth.as_f64(qc.v[t0:t1])])).permute(1, 0, 2)
+    qq = torch.from_numpy(synth.as_f64(qc.q[t0:t1])).permute(1, 0, 2)             # [Hq, T, D]
+    s = torch.einsum("htd,hnd->htn", qq, kk.repeat_interleave(r, dim=0)) * cfg2.scale
+    causal = torch.arange(n + t1 - t0)[None, :] <= (n + torch.arange(t1 - t0))[:, None]
+    s = s.masked_fill(~causal[None], float("-inf"))
+    ref = torch.einsum("htn,hnd->thd", torch.softmax(s, dim=-1), vv.repeat_interleave(r, dim=0)).numpy()
+    assert_close(oq[t0:t1], ref, "cfg4 100 % vs dense causal")
+
+
+def test_query_stage_time_grows_with_the_retrieval_ratio(cfg2):
+    """Decode and prefill cost is linear in the selected KV (Sec. 4, inference latency)."""
+    p = cfg2.pool
+    kp, vp = to_dev(cfg2.k), to_dev(cfg2.v)
+    times, keys = [], []
+    for ratio in synth.RETRIEVAL_RATIOS:
+        qc = synth.config4_query(cfg2, ratio)
+        lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, cu_qlens=qc.cu_qlens,
+                                  sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, n_split=0, block_m=32, block_n=64)
+        qs, ks, vs = to_dev(qc.q), to_dev(qc.k), to_dev(qc.v)
+        out = torch.empty_like(qs)
+        for _ in range(2):
+            B.dbsa_query_attn(lay, qs, ks, vs, kp, vp, cfg2.scale, out=out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            B.dbsa_query_attn(lay, qs, ks, vs, kp, vp, cfg2.scale, out=out)
+        torch.cuda.synchronize()
+        times.append((time.perf_counter() - t0) / 5)
+        lens = np.diff(p.group_token_bounds())
+        keys.append(p.sink_len + np.mean([lens[qc.sel_idx[qc.sel_ptr[u]:qc.sel_ptr[u + 1]]].sum()
+                                          for u in range(qc.n_queries)]))
+    times, keys = np.array(times), np.array(keys)
+    a, b = np.polyfit(keys, times, 1)
+    r2 = 1 - ((times - (a * keys + b)) ** 2).sum() / ((times - times.mean()) ** 2).sum()
+    print(f"[scaling] ms at 10/30/50/100 %: {np.round(times * 1e3, 3).tolist()}  R^2={r2:.5f}", flush=True)
+    assert r2 >= 0.99
+    assert abs((times[0] / times[-1]) / (keys[0] / keys[-1]) - 1.0) <= 0.25
