@@ -13,8 +13,11 @@
 //     operand of the second product without any cross-lane movement.
 //   * the output is accumulated transposed too, O^T = V^T P^T, so that rescaling by
 //     the running-max correction is a per-lane scalar multiply.
-// K tiles sit in LDS row-major (padded rows); V tiles sit in LDS transposed so that a
-// lane can fetch 4 consecutive keys of one channel with one 64-bit read.
+// K and V tiles sit in LDS row-major with padded rows.  The second product needs, per
+// lane, 4 consecutive keys of one channel: that transposed fragment comes from the
+// gfx950 LDS transpose read (ds_read_b64_tr_b16), in which lane i of a 16-lane group
+// supplies the address of key k0 + i/4, channels c0 + 4*(i%4).. and receives keys
+// k0..k0+3 of channel c0 + i.
 #include "kernels.hpp"
 
 namespace {
@@ -24,15 +27,18 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBN = 64;            // keys per KV tile
 constexpr float kNegBig = -1.0e30f;  // "no key seen yet" running max (finite on purpose)
 
 template <int D>
 struct Lds {
-  static constexpr int kKStride = D + 8;    // elements per K row: 16 B of padding
-  static constexpr int kVStride = kBN + 4;  // elements per V^T row: 8 B of padding
-  static constexpr int kBytes = (kBN * kKStride + D * kVStride) * 2;
+  static constexpr int kKStride = D + 8;   // elements per K row: 16 B of padding (rows shift by 4 banks)
+  static constexpr int kVStride = D + 32;  // elements per V row: 64 B of padding (rows shift by 16 banks):
+                                           // measured conflict-free for the transpose reads
+  static constexpr int kBytes = (kBN * kKStride + kBN * kVStride) * 2;
 };
 
 __device__ inline bf16x8 pack8(const floatx16& s, int first) {
@@ -45,6 +51,26 @@ __device__ inline bf16x8 pack8(const floatx16& s, int first) {
     u.p[i] = __builtin_convertvector(floatx2{s[first + 2 * i], s[first + 2 * i + 1]}, bf16x2);
   return u.v;
 }
+
+// LDS transpose read of 4 keys x 16 channels per 16-lane group (see the file header).
+__device__ inline bf16x4 lds_read_tr(const __bf16* p) {
+  typedef __attribute__((address_space(3))) shortx4* lds_ptr;
+  const shortx4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  return __builtin_bit_cast(bf16x4, t);
+}
+
+// Exchange a value between lane l and lane l^32 (the two half-waves hold the two key
+// halves of the same row) and combine it.
+__device__ inline float half_swap_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float half_swap_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+constexpr float kRescaleSlack = 8.f;  // log2 units the running max may lag before accumulators are rescaled
 
 struct TileDesc {
   const __bf16* k;  // row 0 of the tile for this KV head
@@ -63,13 +89,14 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnParams p) {
   constexpr int PPT = kBN * kPiecesPerRow / NT;   // pieces each thread moves per tile
   static_assert(PPT >= 1 && PPT * NT == kBN * kPiecesPerRow, "tile must split evenly over the workgroup");
   __bf16* lds_k = reinterpret_cast<__bf16*>(smem);
-  __bf16* lds_vt = lds_k + kBN * L::kKStride;
+  __bf16* lds_v = lds_k + kBN * L::kKStride;
 
   const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, l32 = lane % 32, half = lane / 32;
   const int r = p.n_q_heads / p.n_kv_heads;
 
   // ---- which rows does this wave own, and which tiles does the workgroup walk ----
   int head, hk, row_tok, q_pos;  // q_pos: token index used by the causal compare
+  int wave_q_hi = 0;             // largest q_pos over the wave's rows
   bool row_valid, wave_active;
   int64_t e0, e1;
   int n_self_tiles = 0, self_len = 0, u = 0, split = 0;
@@ -86,6 +113,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnParams p) {
     wave_active = sub * 32 < q_len;
     row_tok = q_start + min(row_local, q_len - 1);
     q_pos = q_start + row_local;
+    wave_q_hi = q_start + sub * 32 + 31;
     e0 = p.list_ptr[tile];
     e1 = p.list_ptr[tile + 1];
     ent = p.list_ent;
@@ -159,57 +187,63 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnParams p) {
   float m_run = kNegBig, l_run = 0.f;  // running max (log2 domain, scaled) and this lane's share of the sum
   const float c2 = p.scale_log2e;
 
-  // ---- global -> register prefetch of one K/V tile ----
-  uint4 kreg[PPT], vreg[PPT];
-  auto prefetch = [&](const TileDesc& t) {
-#pragma unroll
-    for (int j = 0; j < PPT; ++j) {
-      const int piece = tid + j * NT;
-      const int row = min(piece / kPiecesPerRow, t.kv_len - 1);  // rows past the tail repeat the last key
-      const int col = (piece % kPiecesPerRow) * 8;
-      kreg[j] = *reinterpret_cast<const uint4*>(t.k + static_cast<int64_t>(t.kv_start + row) * t.k_stride + col);
-      vreg[j] = *reinterpret_cast<const uint4*>(t.v + static_cast<int64_t>(t.kv_start + row) * t.v_stride + col);
-    }
-  };
-  auto stage = [&]() {
-#pragma unroll
-    for (int j = 0; j < PPT; ++j) {
-      const int piece = tid + j * NT;
-      const int row = piece / kPiecesPerRow, col = (piece % kPiecesPerRow) * 8;
-      *reinterpret_cast<uint4*>(lds_k + row * L::kKStride + col) = kreg[j];
-      const __bf16* ve = reinterpret_cast<const __bf16*>(&vreg[j]);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) lds_vt[(col + i) * L::kVStride + row] = ve[i];
-    }
-  };
+  // ---- global -> register prefetch of one K/V tile, then registers -> LDS ----
+  uintx4 kreg[PPT], vreg[PPT];
+#define DBSA_PREFETCH(t)                                                                                       \
+  _Pragma("unroll") for (int j = 0; j < PPT; ++j) {                                                            \
+    const int piece = tid + j * NT;                                                                            \
+    const int row = min(piece / kPiecesPerRow, (t).kv_len - 1); /* rows past the tail repeat the last key */   \
+    const int col = (piece % kPiecesPerRow) * 8;                                                               \
+    kreg[j] = *reinterpret_cast<const uintx4*>((t).k + static_cast<int64_t>((t).kv_start + row) * (t).k_stride + col); \
+    vreg[j] = *reinterpret_cast<const uintx4*>((t).v + static_cast<int64_t>((t).kv_start + row) * (t).v_stride + col); \
+  }
+#define DBSA_STAGE()                                                                   \
+  _Pragma("unroll") for (int j = 0; j < PPT; ++j) {                                    \
+    const int piece = tid + j * NT;                                                    \
+    const int row = piece / kPiecesPerRow, col = (piece % kPiecesPerRow) * 8;          \
+    *reinterpret_cast<uintx4*>(lds_k + row * L::kKStride + col) = kreg[j];              \
+    *reinterpret_cast<uintx4*>(lds_v + row * L::kVStride + col) = vreg[j];              \
+  }
+
+  // this lane's address inside a V tile for the transpose reads: key 4*half + (i/4),
+  // channel 16*(l32/16) + 4*(i%4), i = lane%16
+  const __bf16* v_lane = lds_v + (4 * half + (lane % 16) / 4) * L::kVStride + 16 * (l32 / 16) + 4 * (lane % 4);
 
   TileDesc cur{}, nxt{};
   if (n_tiles > 0) {
     nxt = tile_desc(0);
-    prefetch(nxt);
+    DBSA_PREFETCH(nxt)
   }
   for (int it = 0; it < n_tiles; ++it) {
     cur = nxt;
     __syncthreads();  // every wave has finished reading the previous tile
-    stage();
+    DBSA_STAGE()
     __syncthreads();
     if (it + 1 < n_tiles) {
       nxt = tile_desc(it + 1);
-      prefetch(nxt);
+      DBSA_PREFETCH(nxt)
     }
     if (!wave_active) continue;
 
-    // S^T = K Q^T for the two 32-key blocks of the tile
+    // 32-key blocks of this tile that hold a key visible to some row of the wave
+    int nkb = (cur.kv_len + 31) / 32;
+    if (cur.causal) nkb = max(0, min(nkb, (wave_q_hi - cur.kv_start) / 32 + 1));
+    if (wave_q_hi < cur.kv_start && cur.causal) nkb = 0;
+    if (nkb == 0) continue;
+
+    // S^T = K Q^T
     floatx16 s[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
-      const __bf16* kp = lds_k + (kb * 32 + l32) * L::kKStride + 8 * half;
+      if (kb < nkb) {
+        const __bf16* kp = lds_k + (kb * 32 + l32) * L::kKStride + 8 * half;
 #pragma unroll
-      for (int c = 0; c < D / 16; ++c) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kp + 16 * c);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[c], s[kb], 0, 0, 0);
+        for (int c = 0; c < D / 16; ++c) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(kp + 16 * c);
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[c], s[kb], 0, 0, 0);
+        }
       }
     }
     if (cur.causal || cur.kv_len < kBN) {
@@ -227,42 +261,57 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnParams p) {
     float mx = s[0][0];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
+      if (kb < nkb) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx * c2);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+      }
+    mx = half_swap_max(mx) * c2;
+    // The running max may lag the true max by kRescaleSlack (the weights then reach
+    // 2^slack at most, harmless in fp32/bf16): accumulators are rescaled only when some
+    // row of the wave outgrows it, which is rare once a few tiles have been seen.
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int ob = 0; ob < D / 32; ++ob) o[ob] *= alpha;
+    }
     float psum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
+      if (kb < nkb) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        s[kb][i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], c2, -m_new));
-        psum += s[kb][i];
+        for (int i = 0; i < 16; ++i) {
+          s[kb][i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], c2, -m_run));
+          psum += s[kb][i];
+        }
       }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int ob = 0; ob < D / 32; ++ob) o[ob] *= alpha;
+    l_run += psum;
     // O^T += V^T P^T
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
+      if (kb < nkb) {
 #pragma unroll
-      for (int ch = 0; ch < 2; ++ch) {
-        const bf16x8 pf = pack8(s[kb], 8 * ch);
+        for (int ch = 0; ch < 2; ++ch) {
+          const bf16x8 pf = pack8(s[kb], 8 * ch);
 #pragma unroll
-        for (int ob = 0; ob < D / 32; ++ob) {
-          const __bf16* vp = lds_vt + (32 * ob + l32) * L::kVStride + kb * 32 + 16 * ch + 4 * half;
-          const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vp);
-          const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vp + 8);
-          const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, o[ob], 0, 0, 0);
+          for (int ob = 0; ob < D / 32; ++ob) {
+            const __bf16* vp = v_lane + (kb * 32 + 16 * ch) * L::kVStride + 32 * ob;
+            const bf16x4 lo = lds_read_tr(vp);
+            const bf16x4 hi = lds_read_tr(vp + 8 * L::kVStride);
+            const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, o[ob], 0, 0, 0);
+          }
         }
       }
   }
 
+#undef DBSA_PREFETCH
+#undef DBSA_STAGE
+
   // ---- epilogue ----
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = half_swap_sum(l_run);
   if (!row_valid) return;
   if constexpr (!DECODE) {
     const float inv = 1.f / l_tot;
