@@ -130,7 +130,8 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
   if (dtype == DBSA_BF16) {
     if (!mfma_tile_sizes_ok(L)) return DBSA_ERR_UNSUPPORTED;
     p.heads_per_block = pick_heads_per_block(hq / hkv, L->block_m);
-    e = launch_prefill_mfma(p, d, static_cast<hipStream_t>(stream));
+    e = d == 128 ? launch_prefill_pipelined(p, static_cast<hipStream_t>(stream))
+                 : launch_prefill_mfma(p, d, static_cast<hipStream_t>(stream));
   } else {
     e = launch_prefill_plain(p, d, /*bf16_storage=*/false, static_cast<hipStream_t>(stream));
   }

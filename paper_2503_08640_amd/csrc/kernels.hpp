@@ -41,6 +41,8 @@ struct AttnParams {
 
 // bf16 MFMA kernels (attn_mfma.hip)
 hipError_t launch_prefill_mfma(const AttnParams& p, int head_dim, hipStream_t stream);
+// software-pipelined variant for head_dim 128 (attn_prefill.hip)
+hipError_t launch_prefill_pipelined(const AttnParams& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const AttnParams& p, int head_dim, hipStream_t stream);
 hipError_t launch_decode_merge(const AttnParams& p, int head_dim, bool out_bf16, hipStream_t stream);
 
