@@ -3,6 +3,7 @@
 // method lives here.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -130,8 +131,12 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
   if (dtype == DBSA_BF16) {
     if (!mfma_tile_sizes_ok(L)) return DBSA_ERR_UNSUPPORTED;
     p.heads_per_block = pick_heads_per_block(hq / hkv, L->block_m);
-    e = d == 128 ? launch_prefill_pipelined(p, static_cast<hipStream_t>(stream))
-                 : launch_prefill_mfma(p, d, static_cast<hipStream_t>(stream));
+    // the pipelined kernel addresses a tile's rows with 32-bit byte offsets
+    const int64_t max_stride = std::max(std::max(p.k_pool.stride_tok, p.v_pool.stride_tok),
+                                        std::max(p.k_self.stride_tok, p.v_self.stride_tok));
+    e = (d == 128 && max_stride < (int64_t{1} << 24))
+            ? launch_prefill_pipelined(p, static_cast<hipStream_t>(stream))
+            : launch_prefill_mfma(p, d, static_cast<hipStream_t>(stream));
   } else {
     e = launch_prefill_plain(p, d, /*bf16_storage=*/false, static_cast<hipStream_t>(stream));
   }

@@ -1,7 +1,9 @@
 // Software-pipelined bf16 MFMA attention for prefill-shaped calls (pre-encode, Sec. 2.1;
 // query prefill, Sec. 2.2) at head_dim 128 on gfx950.  Same mathematics and register
 // plan as attn_mfma.hip (transposed scores S^T = K Q^T, per-lane softmax statistics,
-// O^T = V^T P^T); what differs is how the tiles move and how the work is ordered:
+// O^T = V^T P^T).  Measured on MI355X, one wavefront issues at most one instruction every
+// ~8 cycles and two wavefronts per SIMD fit the register budget, so the kernel is built
+// around a small instruction count per MFMA:
 //
 //   * K and V tiles go from global memory straight into LDS with
 //     global_load_lds_dwordx4 (no staging registers, no ds_write).  A wave-level load
@@ -12,11 +14,16 @@
 //     4*(row % 4) for the 64-bit transpose reads (4 rows x 4 slots per half-wave).
 //   * two LDS stages per operand and ONE workgroup barrier per KV tile: while tile j is
 //     being consumed, K of tile j+2 and V of tile j+1 are in flight.
-//   * the scores of tile j+1 are issued in the same straight-line region as the
-//     exponentials of tile j, so the matrix pipe and the vector ALU overlap inside one
-//     wave; the second product of tile j follows.
-//   * a wave may own two 32-row blocks (64 rows): every K/V fragment read from LDS then
-//     feeds two MFMAs, at one wave per SIMD with the full 512-register budget.
+//   * Q is pre-multiplied by scale*log2(e) when its fragments are loaded, and the score
+//     accumulators start at minus the running row maximum, so that a probability is one
+//     v_exp_f32 of the MFMA result; the row sum comes from a packed bf16 dot product of
+//     the rounded probabilities with ones.
+//   * the scores of tile j+1 are issued in the same straight-line steps as the
+//     exponentials of tile j, and the row maxima of tile j+1 in the same steps as the
+//     second product of tile j, with K/V fragments fetched two steps ahead.
+//   * the running maximum may lag the true maximum by kRescaleSlack (weights then reach
+//     2^slack at most, harmless in fp32/bf16): accumulators are rescaled only when some
+//     row of the wave outgrows it, which is rare once a few tiles have been seen.
 #include <cstdint>
 
 #include "kernels.hpp"
@@ -35,21 +42,9 @@ constexpr int kBN = 64;                       // keys per KV tile
 constexpr int kRowBytes = kD * 2;             // 256
 constexpr int kTileBytes = kBN * kRowBytes;   // 16 KiB per K or V tile
 constexpr int kLdsBytes = 4 * kTileBytes;     // K stage 0/1, V stage 0/1
-constexpr float kNegBig = -1.0e30f;
-constexpr float kRescaleSlack = 8.f;
+constexpr float kRescaleSlack = 8.f;          // log2 units
 
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
-
-__device__ inline bf16x8 pack8(const floatx16& s, int first) {
-  union {
-    bf16x8 v;
-    bf16x2 p[4];
-  } u;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-    u.p[i] = __builtin_convertvector(floatx2{s[first + 2 * i], s[first + 2 * i + 1]}, bf16x2);
-  return u.v;
-}
 
 __device__ inline bf16x4 lds_read_tr(const lds_byte* p) {
   typedef __attribute__((address_space(3))) shortx4* tr_ptr;
@@ -57,6 +52,8 @@ __device__ inline bf16x4 lds_read_tr(const lds_byte* p) {
   return __builtin_bit_cast(bf16x4, t);
 }
 
+// Combine a value held by lanes l and l^32 (the two half-waves hold the two key halves of
+// the same row).
 __device__ inline float half_swap_max(float x) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
@@ -70,20 +67,25 @@ __device__ inline float half_swap_sum(float x) {
 // dst + 16*l.  Issued through inline assembly so that the transfer stays asynchronous:
 // the kernel waits for it explicitly (vmcnt) right before the workgroup barrier that
 // publishes the stage, instead of before the next LDS read of any stage.
-__device__ inline void dma16(const void* gbase, unsigned byte_off, lds_byte* dst) {
-  const unsigned m0v = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst));  // wave-uniform LDS address
+__device__ inline void dma16(const void* gbase_in, unsigned byte_off, lds_byte* dst) {
+  // both addresses are wave-uniform by construction; say so to the compiler, which must
+  // place them in scalar registers
+  const uint64_t g = reinterpret_cast<uint64_t>(gbase_in);
+  // (readfirstlane returns a signed int: widen through unsigned, or the low word would be sign-extended)
+  const unsigned g_hi = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(g >> 32)));
+  const unsigned g_lo = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(g & 0xFFFFFFFFu)));
+  const void* gbase = reinterpret_cast<const void*>((static_cast<uint64_t>(g_hi) << 32) | static_cast<uint64_t>(g_lo));
+  const unsigned m0v = static_cast<unsigned>(
+      __builtin_amdgcn_readfirstlane(static_cast<int>(reinterpret_cast<uintptr_t>(dst) & 0xFFFFFFFFu)));
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(m0v), "v"(byte_off), "s"(gbase)
                : "memory");
 }
 
-struct Tile {
-  const __bf16* k;
-  const __bf16* v;
-  int64_t k_stride, v_stride;
-  int kv_start, kv_len;
-  bool causal;
+struct TileRef {
+  int start, len;
+  bool causal, self;
 };
 
 // NW wavefronts per workgroup, RB 32-row blocks per wavefront.  Row block g = wave*RB + rb
@@ -104,10 +106,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   const int tile = p.order[blockIdx.x];
   const int q_start = p.qtile_tab[tile * 4 + 0], q_len = p.qtile_tab[tile * 4 + 1];
   const int spb = p.block_m / 32;
-  int head[RB], row_tok[RB], q_pos[RB], blk_q_hi[RB];
+  int head[RB], row_tok[RB], q_pos[RB];
   bool row_valid[RB];
-  bool wave_active = false;
-  int wave_q_hi = 0;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     const int g = wave * RB + rb;
@@ -115,63 +115,69 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
     head[rb] = blockIdx.y * p.heads_per_block + g / spb;
     const int row_local = sub * 32 + l32;
     row_valid[rb] = row_local < q_len;
-    wave_active = wave_active || (sub * 32 < q_len);
     row_tok[rb] = q_start + min(row_local, q_len - 1);
     q_pos[rb] = q_start + row_local;
-    blk_q_hi[rb] = q_start + sub * 32 + 31;
-    wave_q_hi = max(wave_q_hi, blk_q_hi[rb]);
   }
   const int hk = (blockIdx.y * p.heads_per_block) / r;
   const int64_t e0 = p.list_ptr[tile];
   const int n_tiles = static_cast<int>(p.list_ptr[tile + 1] - e0);
   const int32_t* ent = p.list_ent + 2 * e0;
+  if (n_tiles == 0) return;  // cannot happen for a well-formed layout: every row sees itself
 
   const __bf16* kpool = static_cast<const __bf16*>(p.k_pool.ptr) + hk * p.k_pool.stride_head;
   const __bf16* vpool = static_cast<const __bf16*>(p.v_pool.ptr) + hk * p.v_pool.stride_head;
   const __bf16* kself = static_cast<const __bf16*>(p.k_self.ptr) + hk * p.k_self.stride_head;
   const __bf16* vself = static_cast<const __bf16*>(p.v_self.ptr) + hk * p.v_self.stride_head;
+  const int kp_stride = static_cast<int>(p.k_pool.stride_tok), vp_stride = static_cast<int>(p.v_pool.stride_tok);
+  const int ks_stride = static_cast<int>(p.k_self.stride_tok), vs_stride = static_cast<int>(p.v_self.stride_tok);
 
-  auto tile_desc = [&](int it) {
-    Tile t;
+  auto tile_ref = [&](int it) {
     const int w0 = ent[2 * it], w1 = ent[2 * it + 1];
-    const int kind = w1 >> 16;
-    const bool self = kind & 2;
-    t.k = self ? kself : kpool;
-    t.v = self ? vself : vpool;
-    t.k_stride = self ? p.k_self.stride_tok : p.k_pool.stride_tok;
-    t.v_stride = self ? p.v_self.stride_tok : p.v_pool.stride_tok;
-    t.kv_start = w0;
-    t.kv_len = w1 & 0xFFFF;
-    t.causal = kind & 1;
-    return t;
+    return TileRef{w0, w1 & 0xFFFF, ((w1 >> 16) & 1) != 0, ((w1 >> 17) & 1) != 0};
   };
 
   // ---- global -> LDS loads: this wave fills blocks wave*kBlocksPerWave .. of each operand ----
   // lane -> (row, slot) inside block b: row = 4*b + lane/16, slot = lane%16; the piece
-  // fetched into that slot is column (slot ^ swizzle(row)).  4*b is a multiple of 4 and,
-  // per wave, the blocks are consecutive, so the swizzles only depend on lane and j.
-  auto issue_k = [&](const Tile& t, int stage) {
-    const __bf16* base = t.k + static_cast<int64_t>(t.kv_start) * t.k_stride;  // uniform
+  // fetched into that slot is column (slot ^ swizzle(row)).  The byte offsets of a full
+  // pool tile only depend on the lane, so they are computed once.
+  unsigned k_lane_off[kBlocksPerWave], v_lane_off[kBlocksPerWave];
 #pragma unroll
-    for (int j = 0; j < kBlocksPerWave; ++j) {
-      const int b = wave * kBlocksPerWave + j;
-      const int row_in = 4 * b + lane / 16;
-      const int row = min(row_in, t.kv_len - 1);  // rows past the tail repeat the last key
-      const int col = ((lane % 16) ^ (row_in % 16)) * 8;
-      const unsigned off = static_cast<unsigned>(__mul24(row, static_cast<int>(t.k_stride)) + col) * 2u;
-      dma16(base, off, lds + stage * kTileBytes + b * 1024);
+  for (int j = 0; j < kBlocksPerWave; ++j) {
+    const int row_in = 4 * (wave * kBlocksPerWave + j) + lane / 16;
+    k_lane_off[j] = static_cast<unsigned>(row_in * kp_stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u;
+    v_lane_off[j] = static_cast<unsigned>(row_in * vp_stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u;
+  }
+  auto issue_k = [&](const TileRef& t, int stage) {
+    const __bf16* base = (t.self ? kself : kpool) + static_cast<int64_t>(t.start) * (t.self ? ks_stride : kp_stride);
+    lds_byte* dst = lds + stage * kTileBytes + wave * kBlocksPerWave * 1024;
+    if (!t.self && t.len == kBN) {
+#pragma unroll
+      for (int j = 0; j < kBlocksPerWave; ++j) dma16(base, k_lane_off[j], dst + j * 1024);
+    } else {
+      const int stride = t.self ? ks_stride : kp_stride;
+#pragma unroll
+      for (int j = 0; j < kBlocksPerWave; ++j) {
+        const int row_in = 4 * (wave * kBlocksPerWave + j) + lane / 16;
+        const int row = min(row_in, t.len - 1);  // rows past the tail repeat the last key
+        dma16(base, static_cast<unsigned>(row * stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u, dst + j * 1024);
+      }
     }
   };
-  auto issue_v = [&](const Tile& t, int stage) {
-    const __bf16* base = t.v + static_cast<int64_t>(t.kv_start) * t.v_stride;
+  auto issue_v = [&](const TileRef& t, int stage) {
+    const __bf16* base = (t.self ? vself : vpool) + static_cast<int64_t>(t.start) * (t.self ? vs_stride : vp_stride);
+    lds_byte* dst = lds + (2 + stage) * kTileBytes + wave * kBlocksPerWave * 1024;
+    if (!t.self && t.len == kBN) {
 #pragma unroll
-    for (int j = 0; j < kBlocksPerWave; ++j) {
-      const int b = wave * kBlocksPerWave + j;
-      const int row_in = 4 * b + lane / 16;
-      const int row = min(row_in, t.kv_len - 1);
-      const int col = ((lane % 16) ^ (4 * (row_in % 4))) * 8;
-      const unsigned off = static_cast<unsigned>(__mul24(row, static_cast<int>(t.v_stride)) + col) * 2u;
-      dma16(base, off, lds + (2 + stage) * kTileBytes + b * 1024);
+      for (int j = 0; j < kBlocksPerWave; ++j) dma16(base, v_lane_off[j], dst + j * 1024);
+    } else {
+      const int stride = t.self ? vs_stride : vp_stride;
+#pragma unroll
+      for (int j = 0; j < kBlocksPerWave; ++j) {
+        const int row_in = 4 * (wave * kBlocksPerWave + j) + lane / 16;
+        const int row = min(row_in, t.len - 1);
+        dma16(base, static_cast<unsigned>(row * stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u,
+              dst + j * 1024);
+      }
     }
   };
 
@@ -185,28 +191,39 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   const int v_base = (4 * half + (lane % 16) / 4) * kRowBytes +
                      (((2 * (l32 / 16) + (lane % 4) / 2) ^ (4 * ((lane % 16) / 4))) * 16) + (lane % 2) * 8;
 
-  // ---- Q^T fragments ----
+  // ---- Q^T fragments, pre-multiplied by scale*log2(e) ----
+  const float c2 = p.scale_log2e;
   bf16x8 qf[RB][kD / 16];
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(row_tok[rb]) * p.q.stride_tok +
                        static_cast<int64_t>(head[rb]) * p.q.stride_head + 8 * half;
 #pragma unroll
-    for (int c = 0; c < kD / 16; ++c) qf[rb][c] = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
+    for (int c = 0; c < kD / 16; ++c) {
+      const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
+      union {
+        bf16x8 v;
+        bf16x2 p2[4];
+      } sc;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        sc.p2[e] = __builtin_convertvector(
+            floatx2{static_cast<float>(raw[2 * e]) * c2, static_cast<float>(raw[2 * e + 1]) * c2}, bf16x2);
+      qf[rb][c] = sc.v;
+    }
   }
 
   floatx16 o[RB][kD / 32];
-  float m_run[RB], l_run[RB];
+  float m_run[RB], l_run[RB];  // running max (log2 domain), this lane's share of the row sum
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    m_run[rb] = kNegBig;
+    m_run[rb] = 0.f;
     l_run[rb] = 0.f;
 #pragma unroll
     for (int ob = 0; ob < kD / 32; ++ob)
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[rb][ob][i] = 0.f;
   }
-  const float c2 = p.scale_log2e;
 
   // ---- building blocks of one tile step -------------------------------------------------
   // K fragment t (t = kb*8 + c) of K stage `stage`; V fragment t (t = kb*8 + ch*4 + ob).
@@ -221,104 +238,107 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
     const bf16x4 hi = lds_read_tr(vp + 8 * kRowBytes);
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   };
-  // masks of a causal or short tile, applied to raw scores
-  auto apply_mask = [&](floatx16 (&s)[RB][2], const Tile& t) {
+  // masks of a causal or short tile, applied to the scores
+  auto apply_mask = [&](floatx16 (&s)[RB][2], const TileRef& t) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      const int limit = t.causal ? (q_pos[rb] - t.kv_start) : kBN;  // visible iff key_local <= limit
+      const int limit = t.causal ? (q_pos[rb] - t.start) : kBN;  // visible iff key_local <= limit
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int key_local = kb * 32 + 8 * (i / 4) + 4 * half + (i % 4);
-          const bool vis = key_local < t.kv_len && key_local <= limit;
+          const bool vis = key_local < t.len && key_local <= limit;
           s[rb][kb][i] = vis ? s[rb][kb][i] : -INFINITY;
         }
     }
   };
-
-  // ---- prologue: K(0), V(0), K(1) in flight; scores and row maxima of tile 0 ----
-  Tile cur{}, nxt{};
-  floatx16 s_a[RB][2], s_b[RB][2];  // scores of the tile being consumed / of the next tile, swapping roles
-  float mx_cur[RB];                 // scaled row maxima of the tile being consumed
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) mx_cur[rb] = -INFINITY;
-  if (n_tiles > 0) {
-    cur = tile_desc(0);
-    issue_k(cur, 0);
-    issue_v(cur, 0);
-    if (n_tiles > 1) {
-      nxt = tile_desc(1);
-      issue_k(nxt, 1);
-    }
-    __builtin_amdgcn_s_waitcnt(0);  // all counters: own loads have landed
-    __syncthreads();
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s_a[rb][kb][i] = 0.f;
-#pragma unroll
-    for (int t = 0; t < 16; ++t) {
-      const bf16x8 kf = ld_k(0, t);
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-        s_a[rb][t / 8] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][t % 8], s_a[rb][t / 8], 0, 0, 0);
-    }
-    if (cur.causal || cur.kv_len < kBN) apply_mask(s_a, cur);
+  auto row_max = [&](const floatx16 (&s)[RB][2], float (&mx)[RB]) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      float m = s_a[rb][0][0];
+      float m = s[rb][0][0];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) m = fmaxf(m, s_a[rb][kb][i]);
-      mx_cur[rb] = half_swap_max(m) * c2;
+        for (int i = 0; i < 16; ++i) m = fmaxf(m, s[rb][kb][i]);
+      mx[rb] = half_swap_max(m);
     }
+  };
+
+  // ---- prologue: K(0), V(0), K(1) in flight; scores of tile 0 fix the first running max ----
+  TileRef cur = tile_ref(0), nxt{};
+  floatx16 s_a[RB][2], s_b[RB][2];  // scores (minus running max) of the tile being consumed / of the next tile
+  float mx_cur[RB];                 // row maxima of the tile being consumed, relative to the running max
+  issue_k(cur, 0);
+  issue_v(cur, 0);
+  if (n_tiles > 1) {
+    nxt = tile_ref(1);
+    issue_k(nxt, 1);
+  }
+  __builtin_amdgcn_s_waitcnt(0);  // all counters: own loads have landed
+  __syncthreads();
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s_a[rb][kb][i] = 0.f;
+#pragma unroll
+  for (int t = 0; t < 16; ++t) {
+    const bf16x8 kf = ld_k(0, t);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+      s_a[rb][t / 8] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][t % 8], s_a[rb][t / 8], 0, 0, 0);
+  }
+  if (cur.causal || cur.len < kBN) apply_mask(s_a, cur);
+  row_max(s_a, mx_cur);
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    // every row sees at least one key of its first listed tile, so the maximum is finite
+    m_run[rb] = fmaxf(mx_cur[rb], -1.0e30f);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s_a[rb][kb][i] -= m_run[rb];
+    mx_cur[rb] = 0.f;
   }
 
-  // One tile step.  On entry s_cur / mx_cur hold the (masked) raw scores and scaled row
-  // maxima of tile `it`; K(it+1) -> K stage 1-STAGE and V(it) -> V stage STAGE have been
-  // issued.  The step issues the next loads, turns s_cur into probabilities while the
-  // matrix pipe produces s_nxt, and accumulates O while the row maxima of s_nxt are
-  // taken.  The last tile computes an s_nxt nobody uses (stale but finite-or-ignored LDS
-  // contents) so that every tile runs the same straight-line code.
+  // One tile step.  On entry s_cur holds the (masked) scores of tile `it` minus m_run and
+  // mx_cur their row maxima; K(it+1) -> K stage 1-STAGE and V(it) -> V stage STAGE have
+  // been issued.  The last tile computes an s_nxt nobody uses (stale LDS contents) so that
+  // every tile runs the same straight-line code.
 #define DBSA_TILE_STEP(STAGE, s_cur, s_nxt)                                                                      \
   {                                                                                                              \
     __builtin_amdgcn_s_waitcnt(0);                                                                               \
     __syncthreads();                                                                                             \
-    Tile nn{};                                                                                                   \
+    TileRef nn{};                                                                                                \
     if (it + 2 < n_tiles) {                                                                                      \
-      nn = tile_desc(it + 2);                                                                                    \
+      nn = tile_ref(it + 2);                                                                                     \
       issue_k(nn, STAGE);                                                                                        \
     }                                                                                                            \
     const bool has_next = it + 1 < n_tiles;                                                                      \
     if (has_next) issue_v(nxt, 1 - STAGE);                                                                       \
-    /* The running max may lag the true max by kRescaleSlack (weights then reach 2^slack at most, */           \
-    /* harmless in fp32/bf16): accumulators are rescaled only when some row of the wave outgrows it. */         \
     {                                                                                                            \
       bool grow = false;                                                                                         \
-      _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) grow = grow || (mx_cur[rb] > m_run[rb] + kRescaleSlack); \
+      _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) grow = grow || (mx_cur[rb] > kRescaleSlack);             \
       if (__builtin_amdgcn_ballot_w64(grow) != 0) {                                                              \
         _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) {                                                      \
-          const float m_new = fmaxf(m_run[rb], mx_cur[rb]);                                                      \
-          const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_new);                                         \
-          m_run[rb] = m_new;                                                                                     \
+          const float delta = fmaxf(mx_cur[rb], 0.f);                                                            \
+          const float alpha = __builtin_amdgcn_exp2f(-delta);                                                    \
+          m_run[rb] += delta;                                                                                    \
           l_run[rb] *= alpha;                                                                                    \
           _Pragma("unroll") for (int ob = 0; ob < kD / 32; ++ob) o[rb][ob] *= alpha;                             \
+          _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int i = 0; i < 16; ++i)        \
+              s_cur[rb][kb][i] -= delta;                                                                         \
         }                                                                                                        \
       }                                                                                                          \
     }                                                                                                            \
     /* -- scores of the next tile (matrix pipe) || probabilities of this tile (vector ALU) -- */                \
     bf16x2 pk[RB][2][8];                                                                                         \
-    float psum[RB];                                                                                              \
-    _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) {                                                          \
-      psum[rb] = 0.f;                                                                                            \
-      _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int i = 0; i < 16; ++i)            \
-          s_nxt[rb][kb][i] = 0.f;                                                                                \
-    }                                                                                                            \
+    _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) _Pragma("unroll") for (int kb = 0; kb < 2; ++kb)           \
+        _Pragma("unroll") for (int i = 0; i < 16; ++i) s_nxt[rb][kb][i] = -m_run[rb];                            \
     {                                                                                                            \
+      const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};                                \
       bf16x8 kf[3];                                                                                              \
       kf[0] = ld_k(1 - STAGE, 0);                                                                                \
       kf[1] = ld_k(1 - STAGE, 1);                                                                                \
@@ -329,16 +349,18 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
             __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t % 3], qf[rb][t % 8], s_nxt[rb][t / 8], 0, 0, 0);        \
         _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) {                                                      \
           const int kb = t / 8, i = 2 * (t % 8);                                                                 \
-          const float p0 = __builtin_amdgcn_exp2f(fmaf(s_cur[rb][kb][i], c2, -m_run[rb]));                       \
-          const float p1 = __builtin_amdgcn_exp2f(fmaf(s_cur[rb][kb][i + 1], c2, -m_run[rb]));                   \
-          psum[rb] += p0 + p1;                                                                                   \
+          const float p0 = __builtin_amdgcn_exp2f(s_cur[rb][kb][i]);                                             \
+          const float p1 = __builtin_amdgcn_exp2f(s_cur[rb][kb][i + 1]);                                         \
           pk[rb][kb][t % 8] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);                                  \
+          /* row sum of the ROUNDED probabilities: the same values the second product uses */                   \
+          l_run[rb] = __builtin_amdgcn_fdot2_f32_bf16(pk[rb][kb][t % 8], ones, l_run[rb], false);                \
+          /* keep the exponentials in this step, next to the MFMA they overlap with */                          \
+          asm volatile("" : "+v"(pk[rb][kb][t % 8]), "+v"(l_run[rb]));                                           \
         }                                                                                                        \
         __builtin_amdgcn_sched_barrier(0);                                                                       \
       }                                                                                                          \
     }                                                                                                            \
-    _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) l_run[rb] += psum[rb];                                     \
-    if (has_next && (nxt.causal || nxt.kv_len < kBN)) apply_mask(s_nxt, nxt);                                    \
+    if (has_next && (nxt.causal || nxt.len < kBN)) apply_mask(s_nxt, nxt);                                       \
     /* -- O^T += V^T P^T (matrix pipe) || row maxima of the next tile (vector ALU) -- */                        \
     {                                                                                                            \
       float mt[RB];                                                                                              \
@@ -357,10 +379,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
           _Pragma("unroll") for (int e = 0; e < 4; ++e) pf.p2[e] = pk[rb][t / 8][4 * ((t / 4) % 2) + e];         \
           o[rb][t % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t % 3], pf.v, o[rb][t % 4], 0, 0, 0);        \
           mt[rb] = fmaxf(mt[rb], fmaxf(s_nxt[rb][t / 8][2 * (t % 8)], s_nxt[rb][t / 8][2 * (t % 8) + 1]));       \
+          asm volatile("" : "+v"(mt[rb]));                                                                       \
         }                                                                                                        \
         __builtin_amdgcn_sched_barrier(0);                                                                       \
       }                                                                                                          \
-      _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) mx_cur[rb] = half_swap_max(mt[rb]) * c2;                 \
+      _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) mx_cur[rb] = half_swap_max(mt[rb]);                      \
     }                                                                                                            \
     cur = nxt;                                                                                                   \
     nxt = nn;                                                                                                    \
@@ -374,8 +397,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
     --it;
   }
 #undef DBSA_TILE_STEP
-  (void)wave_active;
-  (void)wave_q_hi;
 
   // ---- epilogue ----
 #pragma unroll
@@ -421,8 +442,6 @@ hipError_t launch_cfg(const AttnParams& p, hipStream_t stream) {
 }  // namespace
 
 // One workgroup takes heads_per_block * (block_m / 32) row blocks of 32 rows, one per wave.
-// (Measured on MI355X: one wave per SIMD issues MFMA and VALU work at only half the peak
-// rate, so two row blocks per wave at one wave per SIMD is not used.)
 hipError_t launch_prefill_pipelined(const AttnParams& p, hipStream_t stream) {
   if (p.n_qtiles == 0) return hipSuccess;
   const int row_blocks = p.heads_per_block * (p.block_m / 32);
