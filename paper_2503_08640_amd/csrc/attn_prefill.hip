@@ -103,8 +103,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   const int r = p.n_q_heads / p.n_kv_heads;
 
   // ---- rows of this wave, tiles of this workgroup ----
-  const int tile = p.order[blockIdx.x];
-  const int q_start = p.qtile_tab[tile * 4 + 0], q_len = p.qtile_tab[tile * 4 + 1];
+  // (loaded through vector memory; readfirstlane moves the wave-uniform values to scalar registers)
+  const int tile = __builtin_amdgcn_readfirstlane(p.order[blockIdx.x]);
+  const int q_start = __builtin_amdgcn_readfirstlane(p.qtile_tab[tile * 4 + 0]);
+  const int q_len = __builtin_amdgcn_readfirstlane(p.qtile_tab[tile * 4 + 1]);
   const int spb = p.block_m / 32;
   int head[RB], row_tok[RB], q_pos[RB];
   bool row_valid[RB];
@@ -119,9 +121,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
     q_pos[rb] = q_start + row_local;
   }
   const int hk = (blockIdx.y * p.heads_per_block) / r;
-  const int64_t e0 = p.list_ptr[tile];
-  const int n_tiles = static_cast<int>(p.list_ptr[tile + 1] - e0);
-  const int32_t* ent = p.list_ent + 2 * e0;
+  const int e0 = __builtin_amdgcn_readfirstlane(static_cast<int>(p.list_ptr[tile]));
+  const int n_tiles = __builtin_amdgcn_readfirstlane(static_cast<int>(p.list_ptr[tile + 1])) - e0;
+  const int32_t* ent = p.list_ent + 2 * static_cast<int64_t>(e0);
   if (n_tiles == 0) return;  // cannot happen for a well-formed layout: every row sees itself
 
   const __bf16* kpool = static_cast<const __bf16*>(p.k_pool.ptr) + hk * p.k_pool.stride_head;
@@ -132,7 +134,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   const int ks_stride = static_cast<int>(p.k_self.stride_tok), vs_stride = static_cast<int>(p.v_self.stride_tok);
 
   auto tile_ref = [&](int it) {
-    const int w0 = ent[2 * it], w1 = ent[2 * it + 1];
+    const int w0 = __builtin_amdgcn_readfirstlane(ent[2 * it]), w1 = __builtin_amdgcn_readfirstlane(ent[2 * it + 1]);
     return TileRef{w0, w1 & 0xFFFF, ((w1 >> 16) & 1) != 0, ((w1 >> 17) & 1) != 0};
   };
 
@@ -311,6 +313,13 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   {                                                                                                              \
     __builtin_amdgcn_s_waitcnt(0);                                                                               \
     __syncthreads();                                                                                             \
+    /* first fragments of both products right away: their LDS latency hides behind the bookkeeping below */     \
+    bf16x8 kf[3], vf[3];                                                                                         \
+    kf[0] = ld_k(1 - STAGE, 0);                                                                                  \
+    kf[1] = ld_k(1 - STAGE, 1);                                                                                  \
+    vf[0] = ld_v(STAGE, 0);                                                                                      \
+    vf[1] = ld_v(STAGE, 1);                                                                                      \
+    __builtin_amdgcn_sched_barrier(0);                                                                           \
     TileRef nn{};                                                                                                \
     if (it + 2 < n_tiles) {                                                                                      \
       nn = tile_ref(it + 2);                                                                                     \
@@ -339,9 +348,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
         _Pragma("unroll") for (int i = 0; i < 16; ++i) s_nxt[rb][kb][i] = -m_run[rb];                            \
     {                                                                                                            \
       const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};                                \
-      bf16x8 kf[3];                                                                                              \
-      kf[0] = ld_k(1 - STAGE, 0);                                                                                \
-      kf[1] = ld_k(1 - STAGE, 1);                                                                                \
       __builtin_amdgcn_sched_barrier(0);                                                                         \
       _Pragma("unroll") for (int t = 0; t < 16; ++t) {                                                           \
         if (t + 2 < 16) kf[(t + 2) % 3] = ld_k(1 - STAGE, t + 2);                                                \
@@ -365,9 +371,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
     {                                                                                                            \
       float mt[RB];                                                                                              \
       _Pragma("unroll") for (int rb = 0; rb < RB; ++rb) mt[rb] = s_nxt[rb][0][0];                                \
-      bf16x8 vf[3];                                                                                              \
-      vf[0] = ld_v(STAGE, 0);                                                                                    \
-      vf[1] = ld_v(STAGE, 1);                                                                                    \
       __builtin_amdgcn_sched_barrier(0);                                                                         \
       _Pragma("unroll") for (int t = 0; t < 16; ++t) {                                                           \
         if (t + 2 < 16) vf[(t + 2) % 3] = ld_v(STAGE, t + 2);                                                    \
