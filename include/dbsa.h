@@ -135,15 +135,40 @@ int dbsa_layout_export(const dbsa_layout* layout, const int32_t** qtile_tab, int
 int dbsa_layout_export_decode(const dbsa_layout* layout, const int64_t** dec_ptr, const int32_t** dec_ent,
                               int64_t* n_dec_ent, const int64_t** split_ptr, int32_t* n_split);
 
+/*
+ * Group-major decode schedule of a query-stage layout (INVALID_ARG for a pre-encode
+ * layout).  Queries that selected the same group read the same KV (Sec. 2.2: the caches
+ * of the selected groups are reused in place), so one work item covers a run of KV tiles
+ * of one segment for up to 32 of the queries that use it; each (item, query) pair owns one
+ * partial-softmax slot and the last slot of a query is for its own cached keys.
+ *   seg_ptr   : int64 [n_groups+2]: tile offsets of the sink (segment 0) and of group g
+ *               (segment g+1) in seg_ent.
+ *   seg_ent   : int32 [n_seg_ent][2], same encoding as list_ent, kinds all FULL.
+ *   items     : int32 [n_items][4] = (ent_begin, ent_count, qref_begin, n_q).  Order:
+ *               segments ascending (those with a user), runs of chunk_tiles tiles
+ *               ascending, users in ascending query order in batches of 32.  The sink's
+ *               users are all queries.
+ *   qrefs     : int32 [n_qrefs][2] = (query, slot).
+ *   slot_ptr  : int64 [B+1]: slots of query u are slot_ptr[u] .. slot_ptr[u+1]-1, numbered
+ *               in item order; the last one is the own-cache slot.
+ *   chunk_tiles: tiles per run: ceil(longest segment with a user / n_split) when the
+ *               caller gave n_split > 0, else chosen by the library.
+ */
+int dbsa_layout_export_decode_groups(const dbsa_layout* layout, const int64_t** seg_ptr, const int32_t** seg_ent,
+                                     int64_t* n_seg_ent, const int32_t** items, int64_t* n_items,
+                                     const int32_t** qrefs, int64_t* n_qrefs, const int64_t** slot_ptr,
+                                     int32_t* chunk_tiles);
+
 /* Launch order of Q tiles (a permutation of [0, n_qtiles), longest list first). */
 int dbsa_layout_export_order(const dbsa_layout* layout, const int32_t** order, int64_t* n_order);
 
 void dbsa_layout_destroy(dbsa_layout* layout); /* NULL is allowed */
 
 /*
- * Bytes of device workspace dbsa_decode_attn needs for this layout (split-KV
- * partial states: B * n_q_heads * n_split * (head_dim + 2) floats).  The
- * pre-encode and query calls need none.  Returns 0 for a pre-encode layout.
+ * Bytes of device workspace dbsa_decode_attn needs for this layout: one partial softmax
+ * state of (head_dim + 2) floats per query head and slot, for the larger of the two
+ * decode schedules (B * n_split slots, or slot_ptr[B] slots).  The pre-encode and query
+ * calls need none.  Returns 0 for a pre-encode layout.
  */
 size_t dbsa_workspace_bytes(const dbsa_layout* layout, int32_t n_q_heads, int32_t head_dim);
 

@@ -122,3 +122,42 @@ def decode_layout(sink_len, demo_offsets, group_demo_offsets, n_queries, sel_ptr
         for s in range(n_split + 1):
             split[u, s] = base + (s * len(pool)) // n_split
     return np.asarray(ptr, dtype=np.int64), _pack(ents), split
+
+
+def decode_group_schedule(sink_len, demo_offsets, group_demo_offsets, n_queries, sel_ptr, sel_idx, block_n,
+                          chunk_tiles, item_queries=32):
+    """Group-major decode schedule derived from the visibility predicate: a segment (the
+    sink, a group) is used by the queries that see its keys; every run of ``chunk_tiles`` KV
+    tiles of a used segment is one item per batch of ``item_queries`` users (ascending query
+    order); every (item, user) pair takes the user's next slot; a query's last slot is for
+    its own cached keys.  -> dict like the library's export."""
+    _, group_of = orc.token_maps(sink_len, demo_offsets, group_demo_offsets)
+    segs = _segments(sink_len, demo_offsets, group_demo_offsets)
+    vis = [orc.mask_query_pool([int(g) for g in sel_idx[int(sel_ptr[u]):int(sel_ptr[u + 1])]], sink_len, group_of)
+           for u in range(n_queries)]
+    seg_ptr, seg_ent = [0], []
+    for (a, b) in segs:
+        seg_ent.extend((k0, kn, KIND_FULL) for (k0, kn) in _cut(a, b, block_n))
+        seg_ptr.append(len(seg_ent))
+    uses, counts = [], np.zeros(n_queries, dtype=np.int64)
+    for s, (a, b) in enumerate(segs):
+        users = [u for u in range(n_queries) if b > a and vis[u][a:b].any()]
+        for u in users:
+            assert vis[u][a:b].all()
+        for c0 in range(seg_ptr[s], seg_ptr[s + 1], chunk_tiles):
+            cn = min(chunk_tiles, seg_ptr[s + 1] - c0)
+            for b0 in range(0, len(users), item_queries):
+                uses.append((c0, cn, users[b0:b0 + item_queries]))
+                for u in users[b0:b0 + item_queries]:
+                    counts[u] += 1
+    slot_ptr = np.concatenate([[0], np.cumsum(counts + 1)]).astype(np.int64)
+    nxt = np.zeros(n_queries, dtype=np.int64)
+    items, qrefs = [], []
+    for (c0, cn, users) in uses:
+        items.append((c0, cn, len(qrefs), len(users)))
+        for u in users:
+            qrefs.append((u, int(slot_ptr[u] + nxt[u])))
+            nxt[u] += 1
+    return dict(seg_ptr=np.asarray(seg_ptr, np.int64), seg_ent=_pack(seg_ent),
+                items=np.asarray(items, np.int32).reshape(-1, 4), qrefs=np.asarray(qrefs, np.int32).reshape(-1, 2),
+                slot_ptr=slot_ptr)

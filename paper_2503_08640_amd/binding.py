@@ -29,7 +29,7 @@ DBSA_LAYOUT_HOST_ONLY = 1
 
 EXPORTED_SYMBOLS = (
     "dbsa_strerror", "dbsa_layout_build", "dbsa_layout_export", "dbsa_layout_export_decode",
-    "dbsa_layout_export_order", "dbsa_layout_destroy", "dbsa_workspace_bytes", "dbsa_preencode_attn",
+    "dbsa_layout_export_decode_groups", "dbsa_layout_export_order", "dbsa_layout_destroy", "dbsa_workspace_bytes", "dbsa_preencode_attn",
     "dbsa_query_attn", "dbsa_decode_attn",
 )
 
@@ -78,6 +78,11 @@ def lib() -> C.CDLL:
     L.dbsa_layout_export_decode.argtypes = [C.c_void_p, C.POINTER(C.POINTER(C.c_int64)),
                                             C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int64),
                                             C.POINTER(C.POINTER(C.c_int64)), C.POINTER(C.c_int32)]
+    L.dbsa_layout_export_decode_groups.restype = C.c_int
+    L.dbsa_layout_export_decode_groups.argtypes = [
+        C.c_void_p, C.POINTER(C.POINTER(C.c_int64)), C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int64),
+        C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int64), C.POINTER(C.POINTER(C.c_int32)),
+        C.POINTER(C.c_int64), C.POINTER(C.POINTER(C.c_int64)), C.POINTER(C.c_int32)]
     L.dbsa_layout_export_order.restype = C.c_int
     L.dbsa_layout_export_order.argtypes = [C.c_void_p, C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int64)]
     L.dbsa_layout_destroy.restype = None
@@ -154,6 +159,22 @@ class Layout:
         dec_ent = np.ctypeslib.as_array(de, shape=(ne.value, 2)).copy() if ne.value else np.zeros((0, 2), np.int32)
         split = np.ctypeslib.as_array(sp, shape=(n_queries, ns.value + 1)).copy()
         return dec_ptr, dec_ent, split
+
+    def export_decode_groups(self, n_groups: int, n_queries: int):
+        """-> dict(seg_ptr [G+2], seg_ent [E,2], items [I,4], qrefs [R,2], slot_ptr [B+1], chunk_tiles) copies."""
+        sp, se, it, qr, sl = (C.POINTER(C.c_int64)(), C.POINTER(C.c_int32)(), C.POINTER(C.c_int32)(),
+                              C.POINTER(C.c_int32)(), C.POINTER(C.c_int64)())
+        ne, ni, nr, ct = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int32()
+        _check(lib().dbsa_layout_export_decode_groups(self.handle, C.byref(sp), C.byref(se), C.byref(ne),
+                                                      C.byref(it), C.byref(ni), C.byref(qr), C.byref(nr),
+                                                      C.byref(sl), C.byref(ct)), "dbsa_layout_export_decode_groups")
+
+        def arr(ptr, shape, dt):
+            return np.ctypeslib.as_array(ptr, shape=shape).copy() if shape[0] else np.zeros(shape, dt)
+
+        return dict(seg_ptr=arr(sp, (n_groups + 2,), np.int64), seg_ent=arr(se, (ne.value, 2), np.int32),
+                    items=arr(it, (ni.value, 4), np.int32), qrefs=arr(qr, (nr.value, 2), np.int32),
+                    slot_ptr=arr(sl, (n_queries + 1,), np.int64), chunk_tiles=int(ct.value))
 
     def export_order(self) -> np.ndarray:
         op, n = C.POINTER(C.c_int32)(), C.c_int64()

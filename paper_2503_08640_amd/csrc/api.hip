@@ -19,9 +19,13 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   auto pad = [](size_t n) { return (n + 255) / 256 * 256; };
   const size_t b_tab = L->qtile_tab.size() * sizeof(int32_t), b_ptr = L->list_ptr.size() * sizeof(int64_t),
                b_ent = L->list_ent.size() * sizeof(int32_t), b_ord = L->order.size() * sizeof(int32_t),
-               b_dec = L->dec_ent.size() * sizeof(int32_t), b_spl = L->split_ptr.size() * sizeof(int64_t);
+               b_dec = L->dec_ent.size() * sizeof(int32_t), b_spl = L->split_ptr.size() * sizeof(int64_t),
+               b_gse = L->gm_seg_ent.size() * sizeof(int32_t), b_git = L->gm_items.size() * sizeof(int32_t),
+               b_gqr = L->gm_qrefs.size() * sizeof(int32_t), b_gsp = L->gm_slot_ptr.size() * sizeof(int64_t);
   const size_t o_tab = 0, o_ptr = o_tab + pad(b_tab), o_ent = o_ptr + pad(b_ptr), o_ord = o_ent + pad(b_ent),
-               o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), total = o_spl + pad(b_spl) + 256;
+               o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), o_gse = o_spl + pad(b_spl),
+               o_git = o_gse + pad(b_gse), o_gqr = o_git + pad(b_git), o_gsp = o_gqr + pad(b_gqr),
+               total = o_gsp + pad(b_gsp) + 256;
   std::vector<unsigned char> staging(total, 0);
   auto put = [&](size_t off, const void* src, size_t bytes) {
     if (bytes) std::memcpy(staging.data() + off, src, bytes);
@@ -32,6 +36,10 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   put(o_ord, L->order.data(), b_ord);
   put(o_dec, L->dec_ent.data(), b_dec);
   put(o_spl, L->split_ptr.data(), b_spl);
+  put(o_gse, L->gm_seg_ent.data(), b_gse);
+  put(o_git, L->gm_items.data(), b_git);
+  put(o_gqr, L->gm_qrefs.data(), b_gqr);
+  put(o_gsp, L->gm_slot_ptr.data(), b_gsp);
   void* base = nullptr;
   hipError_t e = hipMalloc(&base, total);
   if (e != hipSuccess) return e;
@@ -49,6 +57,10 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   L->dev.order = reinterpret_cast<int32_t*>(b + o_ord);
   L->dev.dec_ent = reinterpret_cast<int32_t*>(b + o_dec);
   L->dev.split_ptr = reinterpret_cast<int64_t*>(b + o_spl);
+  L->dev.gm_seg_ent = reinterpret_cast<int32_t*>(b + o_gse);
+  L->dev.gm_items = reinterpret_cast<int32_t*>(b + o_git);
+  L->dev.gm_qrefs = reinterpret_cast<int32_t*>(b + o_gqr);
+  L->dev.gm_slot_ptr = reinterpret_cast<int64_t*>(b + o_gsp);
   return hipSuccess;
 }
 
@@ -209,6 +221,23 @@ int dbsa_layout_export_decode(const dbsa_layout* L, const int64_t** dec_ptr, con
   return DBSA_OK;
 }
 
+int dbsa_layout_export_decode_groups(const dbsa_layout* L, const int64_t** seg_ptr, const int32_t** seg_ent,
+                                     int64_t* n_seg_ent, const int32_t** items, int64_t* n_items,
+                                     const int32_t** qrefs, int64_t* n_qrefs, const int64_t** slot_ptr,
+                                     int32_t* chunk_tiles) {
+  if (!L || !L->query_stage) return DBSA_ERR_INVALID_ARG;
+  if (seg_ptr) *seg_ptr = L->gm_seg_ptr.data();
+  if (seg_ent) *seg_ent = L->gm_seg_ent.data();
+  if (n_seg_ent) *n_seg_ent = static_cast<int64_t>(L->gm_seg_ent.size() / 2);
+  if (items) *items = L->gm_items.data();
+  if (n_items) *n_items = static_cast<int64_t>(L->gm_items.size() / 4);
+  if (qrefs) *qrefs = L->gm_qrefs.data();
+  if (n_qrefs) *n_qrefs = static_cast<int64_t>(L->gm_qrefs.size() / 2);
+  if (slot_ptr) *slot_ptr = L->gm_slot_ptr.data();
+  if (chunk_tiles) *chunk_tiles = L->gm_chunk_tiles;
+  return DBSA_OK;
+}
+
 int dbsa_layout_export_order(const dbsa_layout* L, const int32_t** order, int64_t* n_order) {
   if (!L) return DBSA_ERR_INVALID_ARG;
   if (order) *order = L->order.data();
@@ -224,7 +253,9 @@ void dbsa_layout_destroy(dbsa_layout* L) {
 
 size_t dbsa_workspace_bytes(const dbsa_layout* L, int32_t n_q_heads, int32_t head_dim) {
   if (!L || !L->query_stage || n_q_heads <= 0 || head_dim <= 0) return 0;
-  return static_cast<size_t>(L->n_queries) * n_q_heads * L->n_split * (head_dim + 2) * sizeof(float);
+  const size_t slots = std::max<size_t>(static_cast<size_t>(L->n_queries) * L->n_split,
+                                        L->gm_slot_ptr.empty() ? 0 : static_cast<size_t>(L->gm_slot_ptr.back()));
+  return slots * n_q_heads * (head_dim + 2) * sizeof(float);
 }
 
 int dbsa_preencode_attn(const dbsa_layout* layout, dbsa_tensor q, dbsa_tensor k, dbsa_tensor v, dbsa_tensor o,

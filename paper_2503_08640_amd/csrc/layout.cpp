@@ -156,6 +156,70 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
     }
   }
 
+  if (sel) {
+    // ---- group-major decode schedule ----
+    // Queries that selected the same group read the same KV, so at decode a chunk of a
+    // segment (the sink, a group) is one work item for up to kItemQueries of its users:
+    // its keys are fetched once and scored against all of them.  Every (item, user) pair
+    // owns one partial-softmax slot; a query's last slot is for its own cached keys.
+    constexpr int32_t kItemQueries = 32;
+    const int32_t B = sel->n_queries;
+    std::vector<std::vector<int32_t>> users(static_cast<size_t>(G) + 1);
+    if (S > 0)
+      for (int32_t u = 0; u < B; ++u) users[0].push_back(u);
+    for (int32_t u = 0; u < B; ++u)
+      for (int32_t e = sel->sel_ptr[u]; e < sel->sel_ptr[u + 1]; ++e) users[sel->sel_idx[e] + 1].push_back(u);
+    for (auto& v : users) std::sort(v.begin(), v.end());
+    L->gm_seg_ptr.assign(1, 0);
+    push_whole_segment(L->gm_seg_ent, sink, block_n, DBSA_TILE_FULL);
+    L->gm_seg_ptr.push_back(static_cast<int64_t>(L->gm_seg_ent.size() / 2));
+    for (int32_t g = 0; g < G; ++g) {
+      push_whole_segment(L->gm_seg_ent, group[g], block_n, DBSA_TILE_FULL);
+      L->gm_seg_ptr.push_back(static_cast<int64_t>(L->gm_seg_ent.size() / 2));
+    }
+    int64_t max_tiles = 1, tile_batches = 0;
+    for (int32_t s = 0; s <= G; ++s) {
+      const int64_t t = L->gm_seg_ptr[s + 1] - L->gm_seg_ptr[s];
+      if (users[s].empty() || t == 0) continue;
+      max_tiles = std::max(max_tiles, t);
+      tile_batches += t * ((static_cast<int64_t>(users[s].size()) + kItemQueries - 1) / kItemQueries);
+    }
+    int64_t chunk = sel->n_split > 0 ? (max_tiles + sel->n_split - 1) / sel->n_split
+                                     : std::min<int64_t>(16, (tile_batches + 191) / 192);
+    chunk = std::max<int64_t>(1, chunk);
+    L->gm_chunk_tiles = static_cast<int32_t>(chunk);
+    std::vector<int64_t> n_slots(B, 0);
+    // first pass: count slots per query; second pass: emit items with absolute slot numbers
+    for (int pass = 0; pass < 2; ++pass) {
+      std::vector<int64_t> next(B, 0);
+      if (pass == 1) {
+        L->gm_slot_ptr.assign(static_cast<size_t>(B) + 1, 0);
+        for (int32_t u = 0; u < B; ++u) L->gm_slot_ptr[u + 1] = L->gm_slot_ptr[u] + n_slots[u] + 1;  // + own cache
+      }
+      for (int32_t s = 0; s <= G; ++s) {
+        const int64_t t0 = L->gm_seg_ptr[s], t1 = L->gm_seg_ptr[s + 1];
+        if (users[s].empty()) continue;
+        for (int64_t c0 = t0; c0 < t1; c0 += chunk)
+          for (size_t b0 = 0; b0 < users[s].size(); b0 += kItemQueries) {
+            const size_t b1 = std::min(users[s].size(), b0 + kItemQueries);
+            if (pass == 1)
+              L->gm_items.insert(L->gm_items.end(),
+                                 {static_cast<int32_t>(c0), static_cast<int32_t>(std::min(chunk, t1 - c0)),
+                                  static_cast<int32_t>(L->gm_qrefs.size() / 2), static_cast<int32_t>(b1 - b0)});
+            for (size_t k = b0; k < b1; ++k) {
+              const int32_t u = users[s][k];
+              if (pass == 0)
+                ++n_slots[u];
+              else {
+                L->gm_qrefs.push_back(u);
+                L->gm_qrefs.push_back(static_cast<int32_t>(L->gm_slot_ptr[u] + next[u]++));
+              }
+            }
+          }
+      }
+    }
+  }
+
   // launch order: longest list first (stable), so the tail of the grid is short work
   const int64_t nt = L->n_qtiles();
   L->order.resize(nt);

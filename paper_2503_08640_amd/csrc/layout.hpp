@@ -15,6 +15,10 @@ struct dbsa_device_lists {
   int32_t* order = nullptr;       // [n_qtiles]
   int32_t* dec_ent = nullptr;     // [n_dec_ent][2]
   int64_t* split_ptr = nullptr;   // [B][n_split+1]
+  int32_t* gm_seg_ent = nullptr;  // [n_seg_ent][2]
+  int32_t* gm_items = nullptr;    // [n_items][4]
+  int32_t* gm_qrefs = nullptr;    // [n_qrefs][2]
+  int64_t* gm_slot_ptr = nullptr; // [B+1]
 };
 
 struct dbsa_layout {
@@ -31,6 +35,13 @@ struct dbsa_layout {
   std::vector<int64_t> dec_ptr;     // [B+1]
   std::vector<int32_t> dec_ent;     // 2 per entry
   std::vector<int64_t> split_ptr;   // [B][n_split+1]
+  // group-major decode schedule: every KV chunk is walked once for all queries that use it
+  int32_t gm_chunk_tiles = 0;
+  std::vector<int64_t> gm_seg_ptr;  // [n_groups+2] offsets of the sink's and each group's tiles in gm_seg_ent
+  std::vector<int32_t> gm_seg_ent;  // 2 per tile
+  std::vector<int32_t> gm_items;    // 4 per item: (ent_begin, ent_count, qref_begin, n_q)
+  std::vector<int32_t> gm_qrefs;    // 2 per reference: (query, slot)
+  std::vector<int64_t> gm_slot_ptr; // [B+1]; the last slot of a query is its own-cache partial
 
   dbsa_device_lists dev;
 

@@ -78,6 +78,15 @@ def test_query_and_decode_lists_match_oracle_on_random_inputs(seed):
     o_ptr, o_ent, o_split = lo.decode_layout(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, nq, sel_ptr,
                                              sel_idx, bn, ns)
     assert np.array_equal(dec_ptr, o_ptr) and np.array_equal(dec_ent, o_ent) and np.array_equal(split, o_split)
+    got = lay.export_decode_groups(pool.n_groups, nq)
+    segs = np.diff(got["seg_ptr"])
+    used = [0] * (pool.sink_len > 0) + [int(g) + 1 for g in set(sel_idx.tolist())]
+    longest = max([int(segs[s]) for s in used] + [1])
+    assert got["chunk_tiles"] == max(1, -(-longest // ns))               # ceil(longest used segment / n_split)
+    want = lo.decode_group_schedule(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, nq, sel_ptr, sel_idx,
+                                    bn, got["chunk_tiles"])
+    for key in ("seg_ptr", "seg_ent", "items", "qrefs", "slot_ptr"):
+        assert got[key].dtype == want[key].dtype and np.array_equal(got[key], want[key]), key
 
 
 def test_config0_lists_match_oracle_and_counts():
@@ -182,3 +191,25 @@ def test_default_split_count_is_bounded_by_list_length():
     lay = _build(sel_kw=dict(cu_qlens=[0, 4], sel_ptr=[0, 0], sel_idx=[]))   # one sink tile only
     _, _, split = lay.export_decode(1)
     assert split.shape == (1, 2)
+
+
+def test_group_major_schedule_batches_users_and_defaults_to_a_bounded_chunk():
+    """40 queries on one group: two items per run (32 + 8 users); every slot is used once."""
+    pc = synth.config0_pool().pool
+    nq = 40
+    cu = np.arange(nq + 1, dtype=np.int32)
+    sel_ptr = np.arange(nq + 1, dtype=np.int32)
+    sel_idx = np.ones(nq, np.int32)
+    lay = B.dbsa_layout_build(pc.sink_len, pc.demo_offsets, pc.group_demo_offsets, cu_qlens=cu, sel_ptr=sel_ptr,
+                              sel_idx=sel_idx, n_split=0, block_m=64, block_n=64, host_only=True)
+    got = lay.export_decode_groups(pc.n_groups, nq)
+    want = lo.decode_group_schedule(pc.sink_len, pc.demo_offsets, pc.group_demo_offsets, nq, sel_ptr, sel_idx, 64,
+                                    got["chunk_tiles"])
+    for key in ("seg_ptr", "seg_ent", "items", "qrefs", "slot_ptr"):
+        assert np.array_equal(got[key], want[key]), key
+    assert 1 <= got["chunk_tiles"] <= 16
+    assert sorted(got["items"][:, 3].tolist()) == [8, 8, 8, 32, 32, 32]  # the sink tile and the two tiles of group 1
+    slots = np.sort(got["qrefs"][:, 1])
+    own = got["slot_ptr"][1:] - 1
+    assert np.array_equal(np.sort(np.concatenate([slots, own])), np.arange(got["slot_ptr"][-1]))
+    assert lay.workspace_bytes(4, 64) == int(got["slot_ptr"][-1]) * 4 * 66 * 4
