@@ -166,7 +166,7 @@ void dbsa_layout_destroy(dbsa_layout* layout); /* NULL is allowed */
 
 /*
  * Bytes of device workspace dbsa_decode_attn needs for this layout: one partial softmax
- * state of (head_dim + 2) floats per query head and slot, for the larger of the two
+ * state of (head_dim + 4) floats per query head and slot, for the larger of the two
  * decode schedules (B * n_split slots, or slot_ptr[B] slots).  The pre-encode and query
  * calls need none.  Returns 0 for a pre-encode layout.
  */

@@ -110,6 +110,11 @@ void fill_lists(AttnParams& p, const dbsa_layout* L) {
   p.order = L->dev.order;
   p.dec_ent = L->dev.dec_ent;
   p.split_ptr = L->dev.split_ptr;
+  p.gm_seg_ent = L->dev.gm_seg_ent;
+  p.gm_items = L->dev.gm_items;
+  p.gm_qrefs = L->dev.gm_qrefs;
+  p.gm_slot_ptr = L->dev.gm_slot_ptr;
+  p.n_gm_items = static_cast<int32_t>(L->gm_items.size() / 4);
   p.n_qtiles = static_cast<int32_t>(L->n_qtiles());
   p.n_split = L->n_split;
   p.n_queries = L->n_queries;
@@ -255,7 +260,7 @@ size_t dbsa_workspace_bytes(const dbsa_layout* L, int32_t n_q_heads, int32_t hea
   if (!L || !L->query_stage || n_q_heads <= 0 || head_dim <= 0) return 0;
   const size_t slots = std::max<size_t>(static_cast<size_t>(L->n_queries) * L->n_split,
                                         L->gm_slot_ptr.empty() ? 0 : static_cast<size_t>(L->gm_slot_ptr.back()));
-  return slots * n_q_heads * (head_dim + 2) * sizeof(float);
+  return slots * n_q_heads * (head_dim + kPartialPad) * sizeof(float);
 }
 
 int dbsa_preencode_attn(const dbsa_layout* layout, dbsa_tensor q, dbsa_tensor k, dbsa_tensor v, dbsa_tensor o,
@@ -306,8 +311,16 @@ int dbsa_decode_attn(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_sel
     if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
       return DBSA_ERR_WORKSPACE;
     p.partial = static_cast<float*>(workspace);
-    e = launch_decode_mfma(p, head_dim, s);
-    if (e == hipSuccess) e = launch_decode_merge(p, head_dim, /*out_bf16=*/true, s);
+    const int r = n_q_heads / n_kv_heads;
+    const int64_t max_stride = std::max(std::max(p.k_pool.stride_tok, p.v_pool.stride_tok),
+                                        std::max(p.k_self.stride_tok, p.v_self.stride_tok));
+    if (head_dim == 128 && 32 % r == 0 && max_stride < (int64_t{1} << 24)) {
+      // every KV run is walked once for all the queries that selected it
+      e = launch_decode_group(p, s);
+    } else {
+      e = launch_decode_mfma(p, head_dim, s);
+      if (e == hipSuccess) e = launch_decode_merge(p, head_dim, /*out_bf16=*/true, s);
+    }
   } else {
     e = launch_decode_plain(p, head_dim, /*bf16_storage=*/false, s);
   }

@@ -1,0 +1,369 @@
+// Group-major split-KV decode for bf16, head_dim 128 on gfx950 (Sec. 2.2: one new token per
+// query attends the sink, the query's selected groups and its own cached keys).
+//
+// Queries that selected the same group read the same keys, and a decode step is bound by
+// HBM traffic, so the unit of work is not (query, split) but (run of KV tiles of one
+// segment, up to 32 queries that use it): the run is fetched ONCE and scored against all of
+// them on the matrix cores.  A workgroup is ONE wave that owns 32 score columns =
+// (32 / r) queries x the r query heads of one KV head, and walks the run once per batch of
+// 32 / r queries.  Every (item, query) pair writes one partial softmax state (m, l,
+// unnormalised O) into its slot; a second kernel merges the slots of a query
+// (m* = max m_s, l* = sum l_s 2^(m_s - m*), o = sum O_s 2^(m_s - m*) / l*).
+//
+// Tiles move as in the prefill kernel (global_load_lds_dwordx4 into XOR-swizzled LDS), in
+// half tiles of 32 keys through a wave-private 2-stage ring: no workgroup barrier, one
+// half tile (16 KiB) in flight per wave while it computes on the other, and five waves per
+// CU (32 KiB of LDS each), which keeps enough bytes outstanding to cover HBM latency while
+// every resident wave computes.
+#include <cstdint>
+
+#include "kernels.hpp"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kD = 128;
+constexpr int kHalf = 32;                      // keys per half tile
+constexpr int kRowBytes = kD * 2;              // 256
+constexpr int kHalfBytes = kHalf * kRowBytes;  // 8 KiB per K or V half tile
+constexpr int kStages = 2;
+constexpr int kAhead = 1;                      // half tiles in flight
+constexpr int kLdsBytes = kStages * 2 * kHalfBytes;
+constexpr int kLoadsPerHalf = 2 * (kHalfBytes / 1024);  // LDS-DMA instructions per half tile
+constexpr float kRescaleSlack = 8.f;
+
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+
+__device__ inline bf16x4 lds_read_tr(const lds_byte* p) {
+  typedef __attribute__((address_space(3))) shortx4* tr_ptr;
+  const shortx4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(p));
+  return __builtin_bit_cast(bf16x4, t);
+}
+__device__ inline float half_swap_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float half_swap_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// 16 bytes per lane from global memory straight into LDS (lane l lands at dst + 16*l),
+// asynchronous: completion is awaited with an explicit vmcnt wait.
+__device__ inline void dma16(const void* gbase_in, unsigned byte_off, lds_byte* dst) {
+  const uint64_t g = reinterpret_cast<uint64_t>(gbase_in);
+  // (readfirstlane returns a signed int: widen through unsigned, or the low word would be sign-extended)
+  const unsigned g_hi = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(g >> 32)));
+  const unsigned g_lo = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(g & 0xFFFFFFFFu)));
+  const void* gbase = reinterpret_cast<const void*>((static_cast<uint64_t>(g_hi) << 32) | static_cast<uint64_t>(g_lo));
+  const unsigned m0v = static_cast<unsigned>(
+      __builtin_amdgcn_readfirstlane(static_cast<int>(reinterpret_cast<uintptr_t>(dst) & 0xFFFFFFFFu)));
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(m0v), "v"(byte_off), "s"(gbase)
+               : "memory");
+}
+
+// Wait until at most N vector-memory operations of this wave are outstanding.  The memory
+// clobber keeps the LDS reads of the awaited stage below the wait.
+template <int N>
+__device__ inline void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+__global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  lds_byte* lds = (lds_byte*)smem;
+  const int lane = threadIdx.x, l32 = lane % 32, half = lane / 32;
+  const int r = p.n_q_heads / p.n_kv_heads;
+  const int qpw = 32 / r;  // queries per wave
+  const int hk = blockIdx.y;
+
+  // ---- the item: a run of pool tiles for several queries, or one query's own cache ----
+  const int item = blockIdx.x;
+  const bool self_item = item >= p.n_gm_items;
+  int ent_begin = 0, n_q = 1, qref_begin = 0, n_half = 0, self_len = 0, self_u = 0;
+  if (!self_item) {
+    ent_begin = __builtin_amdgcn_readfirstlane(p.gm_items[4 * item + 0]);
+    const int ent_count = __builtin_amdgcn_readfirstlane(p.gm_items[4 * item + 1]);
+    qref_begin = __builtin_amdgcn_readfirstlane(p.gm_items[4 * item + 2]);
+    n_q = __builtin_amdgcn_readfirstlane(p.gm_items[4 * item + 3]);
+    const int last_len = __builtin_amdgcn_readfirstlane(p.gm_seg_ent[2 * (ent_begin + ent_count - 1) + 1]) & 0xFFFF;
+    n_half = 2 * (ent_count - 1) + (last_len + kHalf - 1) / kHalf;
+  } else {
+    self_u = item - p.n_gm_items;
+    self_len = __builtin_amdgcn_readfirstlane(p.self_len[self_u]);
+    n_half = (self_len + kHalf - 1) / kHalf;
+  }
+  const __bf16* kbase = self_item ? static_cast<const __bf16*>(p.k_self.ptr) + self_u * p.stride_query +
+                                        hk * p.k_self.stride_head
+                                  : static_cast<const __bf16*>(p.k_pool.ptr) + hk * p.k_pool.stride_head;
+  const __bf16* vbase = self_item ? static_cast<const __bf16*>(p.v_self.ptr) + self_u * p.stride_query +
+                                        hk * p.v_self.stride_head
+                                  : static_cast<const __bf16*>(p.v_pool.ptr) + hk * p.v_pool.stride_head;
+  const int k_stride = static_cast<int>(self_item ? p.k_self.stride_tok : p.k_pool.stride_tok);
+  const int v_stride = static_cast<int>(self_item ? p.v_self.stride_tok : p.v_pool.stride_tok);
+
+  // half tile hh -> (first token, number of valid keys)
+  auto half_ref = [&](int hh, int& start, int& len) {
+    if (self_item) {
+      start = hh * kHalf;
+      len = min(kHalf, self_len - start);
+    } else {
+      const int e = ent_begin + hh / 2;
+      const int w0 = __builtin_amdgcn_readfirstlane(p.gm_seg_ent[2 * e]);
+      const int w1 = __builtin_amdgcn_readfirstlane(p.gm_seg_ent[2 * e + 1]) & 0xFFFF;
+      start = w0 + (hh % 2) * kHalf;
+      len = min(kHalf, w1 - (hh % 2) * kHalf);
+    }
+  };
+
+  // ---- loads: 8 K blocks and 8 V blocks of 1 KiB per half tile ----
+  // block b holds rows 4b .. 4b+3; lane -> row 4b + lane/16, slot lane%16 (swizzled).  For a
+  // full half tile the per-lane byte offset only depends on b % 4 (K) or not on b at all (V);
+  // the 4b rows go into the uniform base pointer.
+  unsigned k_lane_off[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    k_lane_off[j] = static_cast<unsigned>((lane / 16) * k_stride + (((lane % 16) ^ (4 * j + lane / 16)) * 8)) * 2u;
+  const unsigned v_lane_off =
+      static_cast<unsigned>((lane / 16) * v_stride + (((lane % 16) ^ (4 * ((lane / 16) % 4))) * 8)) * 2u;
+  auto issue = [&](int hh) {
+    int start, len;
+    half_ref(hh, start, len);
+    lds_byte* stage = lds + (hh % kStages) * 2 * kHalfBytes;
+    const __bf16* kb = kbase + static_cast<int64_t>(start) * k_stride;
+    const __bf16* vb = vbase + static_cast<int64_t>(start) * v_stride;
+    if (len == kHalf) {
+#pragma unroll
+      for (int b = 0; b < kHalfBytes / 1024; ++b) {
+        dma16(kb + static_cast<int64_t>(4 * b) * k_stride, k_lane_off[b % 4], stage + b * 1024);
+        dma16(vb + static_cast<int64_t>(4 * b) * v_stride, v_lane_off, stage + kHalfBytes + b * 1024);
+      }
+    } else {
+#pragma unroll
+      for (int b = 0; b < kHalfBytes / 1024; ++b) {
+        const int row_in = 4 * b + lane / 16;
+        const int row = min(row_in, len - 1);  // rows past the tail repeat the last key
+        dma16(kb, static_cast<unsigned>(row * k_stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u,
+              stage + b * 1024);
+        dma16(vb, static_cast<unsigned>(row * v_stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u,
+              stage + kHalfBytes + b * 1024);
+      }
+    }
+  };
+
+  const int k_base = l32 * kRowBytes + ((half ^ (l32 % 16)) * 16);
+  const int v_base = (4 * half + (lane % 16) / 4) * kRowBytes +
+                     (((2 * (l32 / 16) + (lane % 4) / 2) ^ (4 * ((lane % 16) / 4))) * 16) + (lane % 2) * 8;
+  const float c2 = p.scale_log2e;
+  const int n_pass = (n_q + qpw - 1) / qpw;
+
+  for (int pass = 0; pass < n_pass; ++pass) {
+    // ---- this lane's column: query and head ----
+    const int q_local = pass * qpw + l32 / r;  // index into the item's query list
+    const bool col_valid = q_local < n_q;
+    int u = self_u, slot;
+    if (self_item) {
+      slot = static_cast<int>(p.gm_slot_ptr[self_u + 1]) - 1;
+    } else {
+      const int qi = qref_begin + min(q_local, n_q - 1);
+      u = p.gm_qrefs[2 * qi];
+      slot = p.gm_qrefs[2 * qi + 1];
+    }
+    const int head = hk * r + l32 % r;
+
+    bf16x8 qf[kD / 16];
+    {
+      const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
+                         static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
+#pragma unroll
+      for (int c = 0; c < kD / 16; ++c) {
+        const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
+        union {
+          bf16x8 v;
+          bf16x2 p2[4];
+        } sc;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          sc.p2[e] = __builtin_convertvector(
+              floatx2{static_cast<float>(raw[2 * e]) * c2, static_cast<float>(raw[2 * e + 1]) * c2}, bf16x2);
+        qf[c] = sc.v;
+      }
+    }
+    floatx16 o[kD / 32];
+#pragma unroll
+    for (int ob = 0; ob < kD / 32; ++ob)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[ob][i] = 0.f;
+    float m_run = -1.0e30f, l_run = 0.f;
+
+    // ---- wave-private ring of half tiles ----
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a)
+      if (a < n_half) issue(a);
+    for (int hh = 0; hh < n_half; ++hh) {
+      // refill the stage half tile hh-1 used (its LDS reads were consumed by MFMAs already),
+      // then wait until only the loads issued after those of hh are still outstanding
+      if (hh + kAhead < n_half) issue(hh + kAhead);
+      if (hh + kAhead < n_half) wait_vmcnt<kLoadsPerHalf>();
+      else wait_vmcnt<0>();
+      int start, len;
+      half_ref(hh, start, len);
+      const lds_byte* ks = lds + (hh % kStages) * 2 * kHalfBytes;
+      const lds_byte* vs = ks + kHalfBytes;
+
+      // two accumulator chains of four MFMAs instead of one of eight: half the latency
+      floatx16 s, s2;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] = 0.f, s2[i] = 0.f;
+#pragma unroll
+      for (int c = 0; c < kD / 16; c += 2) {
+        const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * c)));
+        const bf16x8 a2 =
+            *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * (c + 1))));
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[c], s, 0, 0, 0);
+        s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, qf[c + 1], s2, 0, 0, 0);
+      }
+      s += s2;
+      if (len < kHalf) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key_local = 8 * (i / 4) + 4 * half + (i % 4);
+          s[i] = key_local < len ? s[i] : -INFINITY;
+        }
+      }
+      float mx = s[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+      mx = half_swap_max(mx);
+      if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int ob = 0; ob < kD / 32; ++ob) o[ob] *= alpha;
+      }
+      union {
+        bf16x8 v[2];
+        bf16x2 p2[8];
+      } pf;
+      const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float p0 = __builtin_amdgcn_exp2f(s[2 * i] - m_run);
+        const float p1 = __builtin_amdgcn_exp2f(s[2 * i + 1] - m_run);
+        pf.p2[i] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(pf.p2[i], ones, l_run, false);
+      }
+#pragma unroll
+      for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+        for (int ob = 0; ob < kD / 32; ++ob) {
+          const lds_byte* vp = vs + (v_base ^ (64 * ob)) + 16 * ch * kRowBytes;
+          const bf16x4 lo = lds_read_tr(vp);
+          const bf16x4 hi = lds_read_tr(vp + 8 * kRowBytes);
+          const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf.v[ch], o[ob], 0, 0, 0);
+        }
+    }
+
+    // ---- partial state of every valid column ----
+    const float l_tot = half_swap_sum(l_run);
+    if (col_valid) {
+      float* part = p.partial + (static_cast<int64_t>(slot) * p.n_q_heads + head) * (kD + kPartialPad);
+#pragma unroll
+      for (int ob = 0; ob < kD / 32; ++ob)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<floatx4*>(part + 32 * ob + 8 * g + 4 * half) =
+              floatx4{o[ob][4 * g], o[ob][4 * g + 1], o[ob][4 * g + 2], o[ob][4 * g + 3]};
+      if (half == 0) {
+        part[kD] = m_run;
+        part[kD + 1] = l_tot;
+      }
+    }
+  }
+}
+
+// Merge the partial states of one (query, head): slots [slot_ptr[u], slot_ptr[u+1]).
+// Thread d owns output channel d.  The per-slot maxima and sums are read with one slot per
+// thread (not one after the other by everyone), the weights 2^(m_s - m*) go through LDS, and
+// the weighted sum of the accumulators runs with independent loads in flight.
+__global__ __launch_bounds__(kD) void decode_group_merge_kernel(AttnParams p) {
+  constexpr int kRow = kD + kPartialPad, kCap = 256;
+  __shared__ float w_sh[kCap];
+  __shared__ float red[2][kD / 64];
+  const int u = blockIdx.x / p.n_q_heads, head = blockIdx.x % p.n_q_heads, d = threadIdx.x;
+  const int s0 = static_cast<int>(p.gm_slot_ptr[u]), s1 = static_cast<int>(p.gm_slot_ptr[u + 1]);
+  const float* part = p.partial + static_cast<int64_t>(head) * kRow;
+  const int64_t slot_stride = static_cast<int64_t>(p.n_q_heads) * kRow;
+
+  auto block_reduce = [&](float x, bool is_max, int which) {
+    for (int o = 32; o > 0; o >>= 1) {
+      const float y = __shfl_xor(x, o, 64);
+      x = is_max ? fmaxf(x, y) : x + y;
+    }
+    if (d % 64 == 0) red[which][d / 64] = x;
+    __syncthreads();
+    float r = red[which][0];
+    for (int w = 1; w < kD / 64; ++w) r = is_max ? fmaxf(r, red[which][w]) : r + red[which][w];
+    return r;
+  };
+
+  float m = -1.0e30f;
+  for (int s = s0 + d; s < s1; s += kD) m = fmaxf(m, part[s * slot_stride + kD]);
+  const float m_star = block_reduce(m, true, 0);
+
+  float l = 0.f, acc = 0.f;
+  for (int base = s0; base < s1; base += kCap) {
+    const int n = min(kCap, s1 - base);
+    __syncthreads();  // previous round's weights are consumed
+    for (int i = d; i < n; i += kD) {
+      const float w = __builtin_amdgcn_exp2f(part[(base + i) * slot_stride + kD] - m_star);
+      w_sh[i] = w;
+      l = fmaf(part[(base + i) * slot_stride + kD + 1], w, l);
+    }
+    __syncthreads();
+    const float* col = part + static_cast<int64_t>(base) * slot_stride + d;
+    int i = 0;
+    for (; i + 8 <= n; i += 8) {
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = col[(i + j) * slot_stride];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc = fmaf(v[j], w_sh[i + j], acc);
+    }
+    for (; i < n; ++i) acc = fmaf(col[i * slot_stride], w_sh[i], acc);
+  }
+  const float l_star = block_reduce(l, false, 1);
+  __bf16* o = static_cast<__bf16*>(const_cast<void*>(p.o.ptr));
+  o[static_cast<int64_t>(u) * p.o.stride_tok + static_cast<int64_t>(head) * p.o.stride_head + d] =
+      static_cast<__bf16>(acc / l_star);
+}
+
+}  // namespace
+
+hipError_t launch_decode_group(const AttnParams& p, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  dim3 grid(p.n_gm_items + p.n_queries, p.n_kv_heads), block(64);
+  decode_group_kernel<<<grid, block, kLdsBytes, stream>>>(p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  decode_group_merge_kernel<<<dim3(p.n_queries * p.n_q_heads), dim3(kD), 0, stream>>>(p);
+  return hipGetLastError();
+}

@@ -332,7 +332,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnParams p) {
     if (p.lse && half == 0)
       p.lse[static_cast<int64_t>(head) * p.lse_stride + row_tok] = (m_run + __log2f(l_tot)) * 0.69314718055994531f;
   } else {
-    float* part = p.partial + ((static_cast<int64_t>(u) * p.n_q_heads + head) * p.n_split + split) * (D + 2);
+    float* part = p.partial + ((static_cast<int64_t>(u) * p.n_split + split) * p.n_q_heads + head) * (D + kPartialPad);
 #pragma unroll
     for (int ob = 0; ob < D / 32; ++ob)
 #pragma unroll
@@ -350,14 +350,16 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnParams p) {
 template <int D, bool OUT_BF16>
 __global__ __launch_bounds__(D) void decode_merge_kernel(AttnParams p) {
   const int u = blockIdx.x / p.n_q_heads, head = blockIdx.x % p.n_q_heads, d = threadIdx.x;
-  const float* part = p.partial + (static_cast<int64_t>(u) * p.n_q_heads + head) * p.n_split * (D + 2);
+  constexpr int kRow = D + kPartialPad;
+  const int64_t slot_stride = static_cast<int64_t>(p.n_q_heads) * kRow;
+  const float* part = p.partial + static_cast<int64_t>(u) * p.n_split * slot_stride + static_cast<int64_t>(head) * kRow;
   float m_star = kNegBig;
-  for (int s = 0; s < p.n_split; ++s) m_star = fmaxf(m_star, part[s * (D + 2) + D]);
+  for (int s = 0; s < p.n_split; ++s) m_star = fmaxf(m_star, part[s * slot_stride + D]);
   float l_star = 0.f, acc = 0.f;
   for (int s = 0; s < p.n_split; ++s) {
-    const float w = __builtin_amdgcn_exp2f(part[s * (D + 2) + D] - m_star);
-    l_star = fmaf(part[s * (D + 2) + D + 1], w, l_star);
-    acc = fmaf(part[s * (D + 2) + d], w, acc);
+    const float w = __builtin_amdgcn_exp2f(part[s * slot_stride + D] - m_star);
+    l_star = fmaf(part[s * slot_stride + D + 1], w, l_star);
+    acc = fmaf(part[s * slot_stride + d], w, acc);
   }
   const float out = acc / l_star;
   void* obase = const_cast<void*>(p.o.ptr);

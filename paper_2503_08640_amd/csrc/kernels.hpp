@@ -5,6 +5,10 @@
 
 #include <cstdint>
 
+// A partial softmax state of one (slot, query head) is head_dim accumulator floats, the
+// running max, the row sum and two floats of padding (rows stay 16-byte aligned).
+constexpr int kPartialPad = 4;
+
 struct TensorView {
   const void* ptr;
   int64_t stride_tok;   // elements
@@ -22,6 +26,11 @@ struct AttnParams {
   const int32_t* order;      // [n_qtiles]
   const int32_t* dec_ent;    // [n_dec_ent][2]
   const int64_t* split_ptr;  // [B][n_split+1]
+  const int32_t* gm_seg_ent;   // group-major decode: tiles of the sink and of every group
+  const int32_t* gm_items;     // [n_gm_items][4]
+  const int32_t* gm_qrefs;     // [..][2]
+  const int64_t* gm_slot_ptr;  // [B+1]
+  int32_t n_gm_items;
   int32_t n_qtiles, n_split, n_queries;
   // tensors
   TensorView q, o;            // rows: tokens (prefill) or queries (decode)
@@ -31,7 +40,7 @@ struct AttnParams {
   const int32_t* self_len;    // decode only, device [B]
   float* lse;                 // optional [Hq][n_rows]
   int64_t lse_stride;         // rows per head in lse
-  float* partial;             // decode: [B][Hq][n_split][D+2]
+  float* partial;             // decode: [slot][Hq][D + kPartialPad]; per-query splits use slot = u*n_split + s
   // shapes
   int32_t n_q_heads, n_kv_heads, block_m, block_n;
   int32_t heads_per_block;    // query heads handled by one workgroup (divides Hq/Hkv)
@@ -43,6 +52,8 @@ struct AttnParams {
 hipError_t launch_prefill_mfma(const AttnParams& p, int head_dim, hipStream_t stream);
 // software-pipelined variant for head_dim 128 (attn_prefill.hip)
 hipError_t launch_prefill_pipelined(const AttnParams& p, hipStream_t stream);
+// group-major split-KV decode + merge for head_dim 128 (attn_decode.hip)
+hipError_t launch_decode_group(const AttnParams& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const AttnParams& p, int head_dim, hipStream_t stream);
 hipError_t launch_decode_merge(const AttnParams& p, int head_dim, bool out_bf16, hipStream_t stream);
 
