@@ -108,7 +108,9 @@ typedef struct dbsa_layout dbsa_layout; /* opaque; owns host and device copies o
  *
  * flags: 0 or DBSA_LAYOUT_HOST_ONLY.  Without HOST_ONLY the lists are copied to
  * the current device with hipMemcpyAsync on `stream` (a hipStream_t, may be
- * NULL) and the stream is synchronised before returning.
+ * NULL) and the stream is synchronised before returning.  The device block and its
+ * pinned staging twin come from a process-wide free list that dbsa_layout_destroy
+ * refills (blocks are kept until the process ends).
  * On success *out receives a layout to be released with dbsa_layout_destroy.
  * Errors: INVALID_ARG, BAD_BOUNDS, BAD_SELECTION, HIP; *out is untouched then.
  */
@@ -159,10 +161,12 @@ int dbsa_layout_export_decode_groups(const dbsa_layout* layout, const int64_t** 
                                      const int32_t** qrefs, int64_t* n_qrefs, const int64_t** slot_ptr,
                                      int32_t* chunk_tiles);
 
-/* Launch order of Q tiles (a permutation of [0, n_qtiles), longest list first). */
+/* Launch order of Q tiles: a permutation of [0, n_qtiles), owner by owner, the longest list
+ * of an owner first. */
 int dbsa_layout_export_order(const dbsa_layout* layout, const int32_t** order, int64_t* n_order);
 
-void dbsa_layout_destroy(dbsa_layout* layout); /* NULL is allowed */
+/* NULL is allowed.  Synchronises the device first (kernels may still be reading the lists). */
+void dbsa_layout_destroy(dbsa_layout* layout);
 
 /*
  * Bytes of device workspace dbsa_decode_attn needs for this layout: one partial softmax

@@ -6,15 +6,59 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <vector>
 
 #include "kernels.hpp"
 #include "layout.hpp"
 
 namespace {
 
-// Copy every list into ONE device allocation (a single hipMalloc and a single copy):
-// the lists are small and the allocation calls, not the bytes, dominate the cost.
+// Device blocks (with a pinned staging twin) are recycled between layouts: allocation
+// calls, not the copied bytes, dominate the cost of a layout build.  A block goes back to
+// the free list when its layout is destroyed, after a device synchronisation, so that no
+// kernel can still be reading the lists when the next layout overwrites them.
+struct ListBlock {
+  void* dev;
+  void* pinned;
+  size_t capacity;
+  int device;
+};
+std::mutex g_pool_mutex;
+std::vector<ListBlock> g_free_blocks;
+
+hipError_t acquire_block(size_t bytes, ListBlock* out) {
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return e;
+  {
+    std::lock_guard<std::mutex> lock(g_pool_mutex);
+    for (size_t i = 0; i < g_free_blocks.size(); ++i)
+      if (g_free_blocks[i].device == device && g_free_blocks[i].capacity >= bytes) {
+        *out = g_free_blocks[i];
+        g_free_blocks.erase(g_free_blocks.begin() + static_cast<std::ptrdiff_t>(i));
+        return hipSuccess;
+      }
+  }
+  ListBlock blk{nullptr, nullptr, (bytes + bytes / 2 + 65535) / 65536 * 65536, device};
+  e = hipMalloc(&blk.dev, blk.capacity);
+  if (e != hipSuccess) return e;
+  e = hipHostMalloc(&blk.pinned, blk.capacity, hipHostMallocDefault);
+  if (e != hipSuccess) {
+    (void)hipFree(blk.dev);
+    return e;
+  }
+  *out = blk;
+  return hipSuccess;
+}
+
+void release_block(const ListBlock& blk) {
+  std::lock_guard<std::mutex> lock(g_pool_mutex);
+  g_free_blocks.push_back(blk);
+}
+
+// Copy every list into ONE device block with a single asynchronous copy from pinned memory.
 hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   auto pad = [](size_t n) { return (n + 255) / 256 * 256; };
   const size_t b_tab = L->qtile_tab.size() * sizeof(int32_t), b_ptr = L->list_ptr.size() * sizeof(int64_t),
@@ -26,9 +70,12 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
                o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), o_gse = o_spl + pad(b_spl),
                o_git = o_gse + pad(b_gse), o_gqr = o_git + pad(b_git), o_gsp = o_gqr + pad(b_gqr),
                total = o_gsp + pad(b_gsp) + 256;
-  std::vector<unsigned char> staging(total, 0);
+  ListBlock blk{};
+  hipError_t e = acquire_block(total, &blk);
+  if (e != hipSuccess) return e;
+  unsigned char* h = static_cast<unsigned char*>(blk.pinned);
   auto put = [&](size_t off, const void* src, size_t bytes) {
-    if (bytes) std::memcpy(staging.data() + off, src, bytes);
+    if (bytes) std::memcpy(h + off, src, bytes);
   };
   put(o_tab, L->qtile_tab.data(), b_tab);
   put(o_ptr, L->list_ptr.data(), b_ptr);
@@ -40,17 +87,17 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   put(o_git, L->gm_items.data(), b_git);
   put(o_gqr, L->gm_qrefs.data(), b_gqr);
   put(o_gsp, L->gm_slot_ptr.data(), b_gsp);
-  void* base = nullptr;
-  hipError_t e = hipMalloc(&base, total);
-  if (e != hipSuccess) return e;
-  e = hipMemcpyAsync(base, staging.data(), total, hipMemcpyHostToDevice, stream);
-  if (e == hipSuccess) e = hipStreamSynchronize(stream);  // staging is freed on return
+  e = hipMemcpyAsync(blk.dev, blk.pinned, total, hipMemcpyHostToDevice, stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);  // the staging twin may be reused after return
   if (e != hipSuccess) {
-    (void)hipFree(base);
+    release_block(blk);
     return e;
   }
-  unsigned char* b = static_cast<unsigned char*>(base);
-  L->dev.base = base;
+  unsigned char* b = static_cast<unsigned char*>(blk.dev);
+  L->dev.base = blk.dev;
+  L->dev.staging = blk.pinned;
+  L->dev.capacity = blk.capacity;
+  L->dev.device = blk.device;
   L->dev.qtile_tab = reinterpret_cast<int32_t*>(b + o_tab);
   L->dev.list_ptr = reinterpret_cast<int64_t*>(b + o_ptr);
   L->dev.list_ent = reinterpret_cast<int32_t*>(b + o_ent);
@@ -65,7 +112,10 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
 }
 
 void free_device_lists(dbsa_device_lists& d) {
-  if (d.base) (void)hipFree(d.base);
+  if (d.base) {
+    (void)hipDeviceSynchronize();  // nothing may still be reading the lists
+    release_block(ListBlock{d.base, d.staging, d.capacity, d.device});
+  }
   d = dbsa_device_lists{};
 }
 

@@ -89,7 +89,7 @@ struct TileRef {
 };
 
 // NW wavefronts per workgroup, RB 32-row blocks per wavefront.  Row block g = wave*RB + rb
-// covers query head (blockIdx.y * heads_per_block + g / spb) and tokens
+// covers query head (blockIdx.x * heads_per_block + g / spb) and tokens
 // q_start + (g % spb)*32 .. +31, spb = block_m / 32.
 template <int NW, int RB>
 __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) {
@@ -104,7 +104,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
 
   // ---- rows of this wave, tiles of this workgroup ----
   // (loaded through vector memory; readfirstlane moves the wave-uniform values to scalar registers)
-  const int tile = __builtin_amdgcn_readfirstlane(p.order[blockIdx.x]);
+  // blockIdx.x = head block, blockIdx.y = position in the launch order: workgroups are handed
+  // to the 8 XCDs round-robin by linear id, so with a multiple of 8 head blocks an XCD keeps
+  // the same KV heads and meets the Q tiles of one owner back to back (their KV stays in its L2)
+  const int tile = __builtin_amdgcn_readfirstlane(p.order[blockIdx.y]);
   const int q_start = __builtin_amdgcn_readfirstlane(p.qtile_tab[tile * 4 + 0]);
   const int q_len = __builtin_amdgcn_readfirstlane(p.qtile_tab[tile * 4 + 1]);
   const int spb = p.block_m / 32;
@@ -114,13 +117,13 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   for (int rb = 0; rb < RB; ++rb) {
     const int g = wave * RB + rb;
     const int sub = g % spb;
-    head[rb] = blockIdx.y * p.heads_per_block + g / spb;
+    head[rb] = blockIdx.x * p.heads_per_block + g / spb;
     const int row_local = sub * 32 + l32;
     row_valid[rb] = row_local < q_len;
     row_tok[rb] = q_start + min(row_local, q_len - 1);
     q_pos[rb] = q_start + row_local;
   }
-  const int hk = (blockIdx.y * p.heads_per_block) / r;
+  const int hk = (blockIdx.x * p.heads_per_block) / r;
   const int e0 = __builtin_amdgcn_readfirstlane(static_cast<int>(p.list_ptr[tile]));
   const int n_tiles = __builtin_amdgcn_readfirstlane(static_cast<int>(p.list_ptr[tile + 1])) - e0;
   const int32_t* ent = p.list_ent + 2 * static_cast<int64_t>(e0);
@@ -437,7 +440,7 @@ hipError_t launch_cfg(const AttnParams& p, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid(p.n_qtiles, p.n_q_heads / p.heads_per_block), block(NW * 64);
+  dim3 grid(p.n_q_heads / p.heads_per_block, p.n_qtiles), block(NW * 64);
   attn_prefill_kernel<NW, RB><<<grid, block, kLdsBytes, stream>>>(p);
   return hipGetLastError();
 }

@@ -220,11 +220,15 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
     }
   }
 
-  // launch order: longest list first (stable), so the tail of the grid is short work
+  // launch order: owner by owner (a group at pre-encoding, a query at the query stage), the
+  // longest list of an owner first.  Q tiles of one owner walk the same KV, so keeping them
+  // adjacent keeps that KV in the L2 of the XCD that runs them.
   const int64_t nt = L->n_qtiles();
   L->order.resize(nt);
   std::iota(L->order.begin(), L->order.end(), 0);
   std::stable_sort(L->order.begin(), L->order.end(), [&](int32_t a, int32_t b) {
+    const int32_t oa = L->qtile_tab[4 * a + 2], ob = L->qtile_tab[4 * b + 2];
+    if (oa != ob) return oa < ob;
     return (L->list_ptr[a + 1] - L->list_ptr[a]) > (L->list_ptr[b + 1] - L->list_ptr[b]);
   });
   return DBSA_OK;

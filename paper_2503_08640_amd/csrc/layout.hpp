@@ -9,6 +9,9 @@
 
 struct dbsa_device_lists {
   void* base = nullptr;           // one allocation holds every list below
+  void* staging = nullptr;        // pinned host buffer the lists were copied from
+  size_t capacity = 0;            // bytes of base / staging
+  int device = -1;
   int32_t* qtile_tab = nullptr;   // [n_qtiles][4]
   int64_t* list_ptr = nullptr;    // [n_qtiles+1]
   int32_t* list_ent = nullptr;    // [n_ent][2]

@@ -55,8 +55,10 @@ def test_preencode_lists_match_oracle_on_random_pools(seed):
     order = lay.export_order()
     tab, ptr, _ = lay.export()
     assert sorted(order.tolist()) == list(range(len(tab)))
-    lens = np.diff(ptr)[order]
-    assert np.all(lens[:-1] >= lens[1:])
+    owners, lens = tab[order, 2], np.diff(ptr)[order]
+    assert np.all(np.diff(owners) >= 0)                      # owner by owner
+    same = owners[:-1] == owners[1:]
+    assert np.all(lens[:-1][same] >= lens[1:][same])         # longest list of an owner first
 
 
 @pytest.mark.parametrize("seed", range(8))
