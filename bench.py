@@ -127,6 +127,10 @@ def main() -> int:
     flops_decode = sum(4.0 * d * hq * float((keys + lens + s + 1).sum()) for s in range(qc.n_decode))
     bytes_decode_step = float((keys + lens + (qc.n_decode + 1) / 2.0).sum()) * hkv * d * 2 * 2
     flops_step = flops_pre + flops_query + flops_decode
+    # bytes a decode step must move when a group selected by several queries is fetched once
+    glens = np.diff(p.group_token_bounds()).astype(np.int64)
+    union_keys = p.sink_len + int(glens[np.unique(qc.sel_idx)].sum())
+    bytes_decode_unique = (union_keys + float((lens + (qc.n_decode + 1) / 2.0).sum())) * hkv * d * 2 * 2
 
     ws_holder = {}
 
@@ -201,7 +205,7 @@ def main() -> int:
             "useful_tflop_per_step": flops_step / 1e12,
         },
         "roofline": {
-            "kernel": "attn_prefill_kernel<8,1> (pre-encode launch; the same kernel serves the query prefill)",
+            "kernel": "attn_prefill_kernel<8,1,false> (pre-encode launch; the <8,1,true> instance serves the query prefill)",
             "bound": "mfma", "achieved": pre_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": pre_tflops / PEAK_BF16_TFLOPS, "traffic": load_traffic("attn_prefill_kernel_preencode"),
             "algorithmic": {"useful_tflop_per_launch": flops_pre / 1e12, "launch_ms": pre_ms},
@@ -210,7 +214,10 @@ def main() -> int:
             "kernel": "decode_group_kernel + decode_group_merge_kernel (one decode step)", "bound": "hbm",
             "achieved": dec_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
             "traffic": load_traffic("decode_step"),
-            "algorithmic": {"per_query_gb_per_step": bytes_decode_step / 1e9, "step_ms": decode_ms,
+            "achieved_unique_bytes": bytes_decode_unique / decode_ms / 1e6,
+            "frac_unique_bytes": bytes_decode_unique / decode_ms / 1e6 / PEAK_HBM_GBS,
+            "algorithmic": {"per_query_gb_per_step": bytes_decode_step / 1e9,
+                            "unique_gb_per_step": bytes_decode_unique / 1e9, "step_ms": decode_ms,
                             "note": "bytes are counted per query (every query re-reads the KV of its groups); the "
                                     "group-major schedule fetches a group once for all queries that selected it, so "
                                     "achieved can exceed the HBM peak; see traffic for the bytes actually moved"},

@@ -188,6 +188,7 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
   p.v_pool = view(v_pool);
   p.k_self = want_query_stage ? view(k_self) : view(k_pool);
   p.v_self = want_query_stage ? view(v_self) : view(v_pool);
+  p.query_stage = want_query_stage ? 1 : 0;
   p.lse = lse;
   p.lse_stride = want_query_stage ? L->n_query_tokens : L->n_tokens;
   p.n_q_heads = hq;

@@ -88,10 +88,12 @@ struct TileRef {
   bool causal, self;
 };
 
-// NW wavefronts per workgroup, RB 32-row blocks per wavefront.  Row block g = wave*RB + rb
+// NW wavefronts per workgroup, RB 32-row blocks per wavefront; SELF: the lists may name tiles of
+// the call's own K/V (query prefill) besides pool tiles (pre-encode lists name pool tiles only).
+// Row block g = wave*RB + rb
 // covers query head (blockIdx.x * heads_per_block + g / spb) and tokens
 // q_start + (g % spb)*32 .. +31, spb = block_m / 32.
-template <int NW, int RB>
+template <int NW, int RB, bool SELF>
 __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   constexpr int kBlocksPerWave = 16 / NW;  // 1-KiB load blocks of one operand per wave (NW <= 8 < 16)
@@ -138,7 +140,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
 
   auto tile_ref = [&](int it) {
     const int w0 = __builtin_amdgcn_readfirstlane(ent[2 * it]), w1 = __builtin_amdgcn_readfirstlane(ent[2 * it + 1]);
-    return TileRef{w0, w1 & 0xFFFF, ((w1 >> 16) & 1) != 0, ((w1 >> 17) & 1) != 0};
+    return TileRef{w0, w1 & 0xFFFF, ((w1 >> 16) & 1) != 0, SELF && ((w1 >> 17) & 1) != 0};
   };
 
   // ---- global -> LDS loads: this wave fills blocks wave*kBlocksPerWave .. of each operand ----
@@ -431,17 +433,17 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   }
 }
 
-template <int NW, int RB>
+template <int NW, int RB, bool SELF>
 hipError_t launch_cfg(const AttnParams& p, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_kernel<NW, RB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_kernel<NW, RB, SELF>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   dim3 grid(p.n_q_heads / p.heads_per_block, p.n_qtiles), block(NW * 64);
-  attn_prefill_kernel<NW, RB><<<grid, block, kLdsBytes, stream>>>(p);
+  attn_prefill_kernel<NW, RB, SELF><<<grid, block, kLdsBytes, stream>>>(p);
   return hipGetLastError();
 }
 
@@ -452,10 +454,10 @@ hipError_t launch_prefill_pipelined(const AttnParams& p, hipStream_t stream) {
   if (p.n_qtiles == 0) return hipSuccess;
   const int row_blocks = p.heads_per_block * (p.block_m / 32);
   switch (row_blocks) {
-    case 1: return launch_cfg<1, 1>(p, stream);
-    case 2: return launch_cfg<2, 1>(p, stream);
-    case 4: return launch_cfg<4, 1>(p, stream);
-    case 8: return launch_cfg<8, 1>(p, stream);
+    case 1: return p.query_stage ? launch_cfg<1, 1, true>(p, stream) : launch_cfg<1, 1, false>(p, stream);
+    case 2: return p.query_stage ? launch_cfg<2, 1, true>(p, stream) : launch_cfg<2, 1, false>(p, stream);
+    case 4: return p.query_stage ? launch_cfg<4, 1, true>(p, stream) : launch_cfg<4, 1, false>(p, stream);
+    case 8: return p.query_stage ? launch_cfg<8, 1, true>(p, stream) : launch_cfg<8, 1, false>(p, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -44,6 +44,7 @@ struct AttnParams {
   // shapes
   int32_t n_q_heads, n_kv_heads, block_m, block_n;
   int32_t heads_per_block;    // query heads handled by one workgroup (divides Hq/Hkv)
+  int32_t query_stage;        // prefill-shaped calls: 1 = query prefill (lists may name self tiles), 0 = pre-encode
   float scale;                // softmax scale
   float scale_log2e;          // scale * log2(e)
 };
