@@ -11,10 +11,11 @@
 // (m* = max m_s, l* = sum l_s 2^(m_s - m*), o = sum O_s 2^(m_s - m*) / l*).
 //
 // Tiles move as in the prefill kernel (global_load_lds_dwordx4 into XOR-swizzled LDS), in
-// half tiles of 32 keys through a wave-private 2-stage ring: no workgroup barrier, one
-// half tile (16 KiB) in flight per wave while it computes on the other, and five waves per
-// CU (32 KiB of LDS each), which keeps enough bytes outstanding to cover HBM latency while
-// every resident wave computes.
+// half tiles of 32 keys through a wave-private ring of four 8-KiB slots (K and V of two half
+// tiles): no workgroup barrier; a K slot is refilled as soon as its scores are computed and a
+// V slot as soon as its second product is issued, so that about 24 KiB per wave are in
+// flight while it computes, and five waves per CU (32 KiB of LDS each) keep enough bytes
+// outstanding to cover HBM latency.
 #include <cstdint>
 
 #include "kernels.hpp"
@@ -34,9 +35,8 @@ constexpr int kHalf = 32;                      // keys per half tile
 constexpr int kRowBytes = kD * 2;              // 256
 constexpr int kHalfBytes = kHalf * kRowBytes;  // 8 KiB per K or V half tile
 constexpr int kStages = 2;
-constexpr int kAhead = 1;                      // half tiles in flight
 constexpr int kLdsBytes = kStages * 2 * kHalfBytes;
-constexpr int kLoadsPerHalf = 2 * (kHalfBytes / 1024);  // LDS-DMA instructions per half tile
+constexpr int kLoadsPerGroup = kHalfBytes / 1024;  // LDS-DMA instructions per K or V half tile
 constexpr float kRescaleSlack = 8.f;
 
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
@@ -89,19 +89,25 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   // ---- the item: a run of pool tiles for several queries, or one query's own cache ----
   const int item = blockIdx.x;
   const bool self_item = item >= p.n_gm_items;
-  int ent_begin = 0, n_q = 1, qref_begin = 0, n_half = 0, self_len = 0, self_u = 0;
+  // (the schedule lists are read-only while a kernel runs: scalar loads through the constant path)
+  typedef const __attribute__((address_space(4))) int32_t* const_words;
+  const const_words items = (const_words)(reinterpret_cast<uintptr_t>(p.gm_items));
+  const const_words seg_ent = (const_words)(reinterpret_cast<uintptr_t>(p.gm_seg_ent));
+  // the run is a stretch of consecutive tokens: first_key .. first_key + n_keys
+  int n_q = 1, qref_begin = 0, n_half = 0, first_key = 0, n_keys = 0, self_u = 0;
   if (!self_item) {
-    ent_begin = __builtin_amdgcn_readfirstlane(p.gm_items[4 * item + 0]);
-    const int ent_count = __builtin_amdgcn_readfirstlane(p.gm_items[4 * item + 1]);
-    qref_begin = __builtin_amdgcn_readfirstlane(p.gm_items[4 * item + 2]);
-    n_q = __builtin_amdgcn_readfirstlane(p.gm_items[4 * item + 3]);
-    const int last_len = __builtin_amdgcn_readfirstlane(p.gm_seg_ent[2 * (ent_begin + ent_count - 1) + 1]) & 0xFFFF;
-    n_half = 2 * (ent_count - 1) + (last_len + kHalf - 1) / kHalf;
+    const int ent_begin = items[4 * item + 0];
+    const int ent_count = items[4 * item + 1];
+    qref_begin = items[4 * item + 2];
+    n_q = items[4 * item + 3];
+    // tiles of one segment follow each other without gaps and all but the last are full
+    first_key = seg_ent[2 * ent_begin];
+    n_keys = 64 * (ent_count - 1) + (seg_ent[2 * (ent_begin + ent_count - 1) + 1] & 0xFFFF);
   } else {
     self_u = item - p.n_gm_items;
-    self_len = __builtin_amdgcn_readfirstlane(p.self_len[self_u]);
-    n_half = (self_len + kHalf - 1) / kHalf;
+    n_keys = __builtin_amdgcn_readfirstlane(p.self_len[self_u]);
   }
+  n_half = (n_keys + kHalf - 1) / kHalf;
   const __bf16* kbase = self_item ? static_cast<const __bf16*>(p.k_self.ptr) + self_u * p.stride_query +
                                         hk * p.k_self.stride_head
                                   : static_cast<const __bf16*>(p.k_pool.ptr) + hk * p.k_pool.stride_head;
@@ -113,16 +119,8 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
 
   // half tile hh -> (first token, number of valid keys)
   auto half_ref = [&](int hh, int& start, int& len) {
-    if (self_item) {
-      start = hh * kHalf;
-      len = min(kHalf, self_len - start);
-    } else {
-      const int e = ent_begin + hh / 2;
-      const int w0 = __builtin_amdgcn_readfirstlane(p.gm_seg_ent[2 * e]);
-      const int w1 = __builtin_amdgcn_readfirstlane(p.gm_seg_ent[2 * e + 1]) & 0xFFFF;
-      start = w0 + (hh % 2) * kHalf;
-      len = min(kHalf, w1 - (hh % 2) * kHalf);
-    }
+    start = first_key + hh * kHalf;
+    len = min(kHalf, n_keys - hh * kHalf);
   };
 
   // ---- loads: 8 K blocks and 8 V blocks of 1 KiB per half tile ----
@@ -135,29 +133,52 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
     k_lane_off[j] = static_cast<unsigned>((lane / 16) * k_stride + (((lane % 16) ^ (4 * j + lane / 16)) * 8)) * 2u;
   const unsigned v_lane_off =
       static_cast<unsigned>((lane / 16) * v_stride + (((lane % 16) ^ (4 * ((lane / 16) % 4))) * 8)) * 2u;
-  auto issue = [&](int hh) {
+  // K and V of a half tile are separate load groups of kLoadsPerGroup instructions each, so that a
+  // slot can be refilled as soon as ITS product has consumed it
+  auto issue_k = [&](int hh) {
     int start, len;
     half_ref(hh, start, len);
     lds_byte* stage = lds + (hh % kStages) * 2 * kHalfBytes;
     const __bf16* kb = kbase + static_cast<int64_t>(start) * k_stride;
-    const __bf16* vb = vbase + static_cast<int64_t>(start) * v_stride;
     if (len == kHalf) {
 #pragma unroll
-      for (int b = 0; b < kHalfBytes / 1024; ++b) {
+      for (int b = 0; b < kLoadsPerGroup; ++b)
         dma16(kb + static_cast<int64_t>(4 * b) * k_stride, k_lane_off[b % 4], stage + b * 1024);
-        dma16(vb + static_cast<int64_t>(4 * b) * v_stride, v_lane_off, stage + kHalfBytes + b * 1024);
-      }
     } else {
 #pragma unroll
-      for (int b = 0; b < kHalfBytes / 1024; ++b) {
+      for (int b = 0; b < kLoadsPerGroup; ++b) {
         const int row_in = 4 * b + lane / 16;
         const int row = min(row_in, len - 1);  // rows past the tail repeat the last key
         dma16(kb, static_cast<unsigned>(row * k_stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u,
               stage + b * 1024);
-        dma16(vb, static_cast<unsigned>(row * v_stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u,
-              stage + kHalfBytes + b * 1024);
       }
     }
+  };
+  auto issue_v = [&](int hh) {
+    int start, len;
+    half_ref(hh, start, len);
+    lds_byte* stage = lds + (hh % kStages) * 2 * kHalfBytes + kHalfBytes;
+    const __bf16* vb = vbase + static_cast<int64_t>(start) * v_stride;
+    if (len == kHalf) {
+#pragma unroll
+      for (int b = 0; b < kLoadsPerGroup; ++b)
+        dma16(vb + static_cast<int64_t>(4 * b) * v_stride, v_lane_off, stage + b * 1024);
+    } else {
+#pragma unroll
+      for (int b = 0; b < kLoadsPerGroup; ++b) {
+        const int row_in = 4 * b + lane / 16;
+        const int row = min(row_in, len - 1);
+        dma16(vb, static_cast<unsigned>(row * v_stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u,
+              stage + b * 1024);
+      }
+    }
+  };
+  // wait until at most `groups` load groups (0..3) are still outstanding
+  auto wait_groups = [&](int groups) {
+    if (groups >= 3) wait_vmcnt<3 * kLoadsPerGroup>();
+    else if (groups == 2) wait_vmcnt<2 * kLoadsPerGroup>();
+    else if (groups == 1) wait_vmcnt<kLoadsPerGroup>();
+    else wait_vmcnt<0>();
   };
 
   const int k_base = l32 * kRowBytes + ((half ^ (l32 % 16)) * 16);
@@ -205,16 +226,18 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
       for (int i = 0; i < 16; ++i) o[ob][i] = 0.f;
     float m_run = -1.0e30f, l_run = 0.f;
 
-    // ---- wave-private ring of half tiles ----
+    // ---- wave-private ring: load groups go out in the order K(0) V(0) K(1) V(1) K(2) V(2) ...;
+    // K(hh+2) as soon as the scores of hh are computed, V(hh+2) as soon as its second product is
+    // issued, so three of the four 8-KiB slots are in flight most of the time ----
 #pragma unroll
-    for (int a = 0; a < kAhead; ++a)
-      if (a < n_half) issue(a);
+    for (int a = 0; a < kStages; ++a)
+      if (a < n_half) {
+        issue_k(a);
+        issue_v(a);
+      }
     for (int hh = 0; hh < n_half; ++hh) {
-      // refill the stage half tile hh-1 used (its LDS reads were consumed by MFMAs already),
-      // then wait until only the loads issued after those of hh are still outstanding
-      if (hh + kAhead < n_half) issue(hh + kAhead);
-      if (hh + kAhead < n_half) wait_vmcnt<kLoadsPerHalf>();
-      else wait_vmcnt<0>();
+      // K(hh) has landed once only the groups issued after it are outstanding: V(hh), K(hh+1), V(hh+1)
+      wait_groups(1 + (hh + 1 < n_half ? 2 : 0));
       int start, len;
       half_ref(hh, start, len);
       const lds_byte* ks = lds + (hh % kStages) * 2 * kHalfBytes;
@@ -233,6 +256,8 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
         s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, qf[c + 1], s2, 0, 0, 0);
       }
       s += s2;
+      // the K slot is free (its LDS reads were consumed by the MFMAs above): refill it
+      if (hh + kStages < n_half) issue_k(hh + kStages);
       if (len < kHalf) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -256,14 +281,15 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
         bf16x8 v[2];
         bf16x2 p2[8];
       } pf;
-      const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const float p0 = __builtin_amdgcn_exp2f(s[2 * i] - m_run);
         const float p1 = __builtin_amdgcn_exp2f(s[2 * i + 1] - m_run);
         pf.p2[i] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);
-        l_run = __builtin_amdgcn_fdot2_f32_bf16(pf.p2[i], ones, l_run, false);
+        l_run += p0 + p1;
       }
+      // V(hh) has landed once only K(hh+1), V(hh+1) and K(hh+2) are outstanding
+      wait_groups((hh + 1 < n_half ? 2 : 0) + (hh + 2 < n_half ? 1 : 0));
 #pragma unroll
       for (int ch = 0; ch < 2; ++ch)
 #pragma unroll
@@ -274,6 +300,7 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
           const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf.v[ch], o[ob], 0, 0, 0);
         }
+      if (hh + kStages < n_half) issue_v(hh + kStages);
     }
 
     // ---- partial state of every valid column ----
