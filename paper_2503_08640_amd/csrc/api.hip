@@ -165,6 +165,8 @@ void fill_lists(AttnParams& p, const dbsa_layout* L) {
   p.gm_qrefs = L->dev.gm_qrefs;
   p.gm_slot_ptr = L->dev.gm_slot_ptr;
   p.n_gm_items = static_cast<int32_t>(L->gm_items.size() / 4);
+  p.gm_max_queries = 1;
+  for (size_t i = 3; i < L->gm_items.size(); i += 4) p.gm_max_queries = std::max(p.gm_max_queries, L->gm_items[i]);
   p.n_qtiles = static_cast<int32_t>(L->n_qtiles());
   p.n_split = L->n_split;
   p.n_queries = L->n_queries;

@@ -11,11 +11,12 @@
 // (m* = max m_s, l* = sum l_s 2^(m_s - m*), o = sum O_s 2^(m_s - m*) / l*).
 //
 // Tiles move as in the prefill kernel (global_load_lds_dwordx4 into XOR-swizzled LDS), in
-// half tiles of 32 keys through a wave-private ring of four 8-KiB slots (K and V of two half
-// tiles): no workgroup barrier; a K slot is refilled as soon as its scores are computed and a
-// V slot as soon as its second product is issued, so that about 24 KiB per wave are in
-// flight while it computes, and five waves per CU (32 KiB of LDS each) keep enough bytes
-// outstanding to cover HBM latency.
+// half tiles of 32 keys whose K and V parts are separate load groups, through a wave-private
+// ring of three 8-KiB slots: no workgroup barrier; a slot is refilled as soon as the product
+// that reads it is issued, so that 16 KiB per wave are in flight while it computes, and six
+// single-wave workgroups per CU (24 KiB of LDS each) keep enough bytes outstanding to cover
+// HBM latency.  What matters most for the speed of a step is that its workgroups fit the
+// chip in ONE round: a half-filled second round costs a whole item time.
 #include <cstdint>
 
 #include "kernels.hpp"
@@ -34,8 +35,8 @@ constexpr int kD = 128;
 constexpr int kHalf = 32;                      // keys per half tile
 constexpr int kRowBytes = kD * 2;              // 256
 constexpr int kHalfBytes = kHalf * kRowBytes;  // 8 KiB per K or V half tile
-constexpr int kStages = 2;
-constexpr int kLdsBytes = kStages * 2 * kHalfBytes;
+constexpr int kSlots = 3;                      // ring slots of one K or V half tile each
+constexpr int kLdsBytes = kSlots * kHalfBytes;  // 24 KiB per wave: six waves per CU
 constexpr int kLoadsPerGroup = kHalfBytes / 1024;  // LDS-DMA instructions per K or V half tile
 constexpr float kRescaleSlack = 8.f;
 
@@ -138,7 +139,7 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   auto issue_k = [&](int hh) {
     int start, len;
     half_ref(hh, start, len);
-    lds_byte* stage = lds + (hh % kStages) * 2 * kHalfBytes;
+    lds_byte* stage = lds + ((2 * hh) % kSlots) * kHalfBytes;
     const __bf16* kb = kbase + static_cast<int64_t>(start) * k_stride;
     if (len == kHalf) {
 #pragma unroll
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   auto issue_v = [&](int hh) {
     int start, len;
     half_ref(hh, start, len);
-    lds_byte* stage = lds + (hh % kStages) * 2 * kHalfBytes + kHalfBytes;
+    lds_byte* stage = lds + ((2 * hh + 1) % kSlots) * kHalfBytes;
     const __bf16* vb = vbase + static_cast<int64_t>(start) * v_stride;
     if (len == kHalf) {
 #pragma unroll
@@ -173,10 +174,9 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
       }
     }
   };
-  // wait until at most `groups` load groups (0..3) are still outstanding
+  // wait until at most `groups` load groups (0..2) are still outstanding
   auto wait_groups = [&](int groups) {
-    if (groups >= 3) wait_vmcnt<3 * kLoadsPerGroup>();
-    else if (groups == 2) wait_vmcnt<2 * kLoadsPerGroup>();
+    if (groups >= 2) wait_vmcnt<2 * kLoadsPerGroup>();
     else if (groups == 1) wait_vmcnt<kLoadsPerGroup>();
     else wait_vmcnt<0>();
   };
@@ -187,7 +187,12 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   const float c2 = p.scale_log2e;
   const int n_pass = (n_q + qpw - 1) / qpw;
 
-  for (int pass = 0; pass < n_pass; ++pass) {
+  // One workgroup per batch of 32 / r queries of the item (blockIdx.z): an item that serves more
+  // queries than one wave has columns is walked by several workgroups side by side instead of by
+  // one workgroup several times, which would make it the last to finish.
+  const int pass = blockIdx.z;
+  if (pass >= n_pass) return;
+  {
     // ---- this lane's column: query and head ----
     const int q_local = pass * qpw + l32 / r;  // index into the item's query list
     const bool col_valid = q_local < n_q;
@@ -200,11 +205,21 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
       slot = p.gm_qrefs[2 * qi + 1];
     }
     const int head = hk * r + l32 % r;
+    // (the row address is formed here, before the tile loads go out: it waits for the query
+    // reference just loaded, and that wait must not include the tile loads)
+    const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
+                       static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
+    asm volatile("" : "+v"(qp));
 
+    // ---- wave-private ring of three 8-KiB slots: load groups go out in the order K(0) V(0) K(1)
+    // V(1) K(2) ..., group g into slot g % 3, and group g+3 as soon as the product that reads group
+    // g is issued: two slots are in flight while the third is being computed on.  The first
+    // groups are requested before the query row, so that both latencies run together. ----
+    issue_k(0);
+    issue_v(0);
+    if (1 < n_half) issue_k(1);
     bf16x8 qf[kD / 16];
     {
-      const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
-                         static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
 #pragma unroll
       for (int c = 0; c < kD / 16; ++c) {
         const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
@@ -226,22 +241,13 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
       for (int i = 0; i < 16; ++i) o[ob][i] = 0.f;
     float m_run = -1.0e30f, l_run = 0.f;
 
-    // ---- wave-private ring: load groups go out in the order K(0) V(0) K(1) V(1) K(2) V(2) ...;
-    // K(hh+2) as soon as the scores of hh are computed, V(hh+2) as soon as its second product is
-    // issued, so three of the four 8-KiB slots are in flight most of the time ----
-#pragma unroll
-    for (int a = 0; a < kStages; ++a)
-      if (a < n_half) {
-        issue_k(a);
-        issue_v(a);
-      }
     for (int hh = 0; hh < n_half; ++hh) {
-      // K(hh) has landed once only the groups issued after it are outstanding: V(hh), K(hh+1), V(hh+1)
-      wait_groups(1 + (hh + 1 < n_half ? 2 : 0));
+      // K(hh) has landed once only the groups issued after it are outstanding: V(hh), K(hh+1)
+      wait_groups(1 + (hh + 1 < n_half ? 1 : 0));
       int start, len;
       half_ref(hh, start, len);
-      const lds_byte* ks = lds + (hh % kStages) * 2 * kHalfBytes;
-      const lds_byte* vs = ks + kHalfBytes;
+      const lds_byte* ks = lds + ((2 * hh) % kSlots) * kHalfBytes;
+      const lds_byte* vs = lds + ((2 * hh + 1) % kSlots) * kHalfBytes;
 
       // two accumulator chains of four MFMAs instead of one of eight: half the latency
       floatx16 s, s2;
@@ -256,8 +262,9 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
         s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, qf[c + 1], s2, 0, 0, 0);
       }
       s += s2;
-      // the K slot is free (its LDS reads were consumed by the MFMAs above): refill it
-      if (hh + kStages < n_half) issue_k(hh + kStages);
+      // the K slot is free (its LDS reads were consumed by the MFMAs above): it takes the group
+      // three places on, V(hh+1)
+      if (hh + 1 < n_half) issue_v(hh + 1);
       if (len < kHalf) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -288,8 +295,8 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
         pf.p2[i] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);
         l_run += p0 + p1;
       }
-      // V(hh) has landed once only K(hh+1), V(hh+1) and K(hh+2) are outstanding
-      wait_groups((hh + 1 < n_half ? 2 : 0) + (hh + 2 < n_half ? 1 : 0));
+      // V(hh) has landed once only K(hh+1) and V(hh+1) are outstanding
+      wait_groups(hh + 1 < n_half ? 2 : 0);
 #pragma unroll
       for (int ch = 0; ch < 2; ++ch)
 #pragma unroll
@@ -300,7 +307,7 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
           const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf.v[ch], o[ob], 0, 0, 0);
         }
-      if (hh + kStages < n_half) issue_v(hh + kStages);
+      if (hh + 2 < n_half) issue_k(hh + 2);  // into the slot V(hh) just left
     }
 
     // ---- partial state of every valid column ----
@@ -387,7 +394,8 @@ hipError_t launch_decode_group(const AttnParams& p, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid(p.n_gm_items + p.n_queries, p.n_kv_heads), block(64);
+  const int qpw = 32 / (p.n_q_heads / p.n_kv_heads);
+  dim3 grid(p.n_gm_items + p.n_queries, p.n_kv_heads, (p.gm_max_queries + qpw - 1) / qpw), block(64);
   decode_group_kernel<<<grid, block, kLdsBytes, stream>>>(p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -31,6 +31,7 @@ struct AttnParams {
   const int32_t* gm_qrefs;     // [..][2]
   const int64_t* gm_slot_ptr;  // [B+1]
   int32_t n_gm_items;
+  int32_t gm_max_queries;      // most queries any group-major item serves
   int32_t n_qtiles, n_split, n_queries;
   // tensors
   TensorView q, o;            // rows: tokens (prefill) or queries (decode)
