@@ -24,8 +24,9 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-PRE_BLOCK_M = 64            # tokens per Q tile at pre-encode (x 4 query heads of one KV head per workgroup)
-QUERY_BLOCK_M = 64
+# tokens per Q tile (x 4 query heads of one KV head per workgroup)
+from paper_2503_08640_amd.binding import BENCH_BLOCK_M_PREENCODE as PRE_BLOCK_M  # noqa: E402
+from paper_2503_08640_amd.binding import BENCH_BLOCK_M_QUERY as QUERY_BLOCK_M  # noqa: E402
 
 
 def visible_pairs_pre(pool) -> int:
@@ -205,7 +206,7 @@ def main() -> int:
             "useful_tflop_per_step": flops_step / 1e12,
         },
         "roofline": {
-            "kernel": "attn_prefill_kernel<8,1,false> (pre-encode launch; the <8,1,true> instance serves the query prefill)",
+            "kernel": "attn_prefill_kernel<4,1,false> (pre-encode launch; the <4,1,true> instance serves the query prefill)",
             "bound": "mfma", "achieved": pre_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": pre_tflops / PEAK_BF16_TFLOPS, "traffic": load_traffic("attn_prefill_kernel_preencode"),
             "algorithmic": {"useful_tflop_per_launch": flops_pre / 1e12, "launch_ms": pre_ms},

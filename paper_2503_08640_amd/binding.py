@@ -16,6 +16,13 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdbsa.so")
 
+# Q-tile heights the benchmark launches with for grouped-query models (4 query heads per KV head):
+# 32 tokens x 4 heads = four waves per workgroup, two workgroups per compute unit, so that one
+# workgroup's prologue and epilogue overlap the other's tile loop.  The full-size GPU tests use
+# the same values.
+BENCH_BLOCK_M_PREENCODE = 32
+BENCH_BLOCK_M_QUERY = 32
+
 DBSA_OK = 0
 DBSA_ERR_INVALID_ARG = -1
 DBSA_ERR_BAD_BOUNDS = -2

@@ -90,19 +90,23 @@ __device__ inline float half_swap_sum(float x) {
 // LDS byte address lds_addr + 16*l.  Issued through inline assembly so that the transfer
 // stays asynchronous: the kernel waits for it explicitly (vmcnt) right before the workgroup
 // barrier that publishes the stage, instead of before the next LDS read of any stage.
-__device__ inline void dma16(const void* gbase_in, unsigned byte_off, unsigned lds_addr) {
-  // both addresses are wave-uniform by construction; say so to the compiler, which must
-  // place them in scalar registers
-  const uint64_t g = reinterpret_cast<uint64_t>(gbase_in);
-  // (readfirstlane returns a signed int: widen through unsigned, or the low word would be sign-extended)
-  const unsigned g_hi = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(g >> 32)));
-  const unsigned g_lo = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(g & 0xFFFFFFFFu)));
-  const void* gbase = reinterpret_cast<const void*>((static_cast<uint64_t>(g_hi) << 32) | static_cast<uint64_t>(g_lo));
-  const unsigned m0v = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(lds_addr)));
+// Both addresses are wave-uniform and must reach the instruction in scalar registers.  The
+// callers keep every step of their computation scalar (pool bases made uniform once with
+// uniform64, tile starts from scalar loads), so that forming them costs scalar instructions
+// only and no round trip through the vector unit.
+__device__ inline void dma16(uint64_t gbase, unsigned byte_off, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
-               : "s"(m0v), "v"(byte_off), "s"(gbase)
+               : "s"(lds_addr), "v"(byte_off), "s"(gbase)
                : "memory");
+}
+
+// A wave-uniform 64-bit value, in scalar registers as far as the compiler is concerned.
+// (readfirstlane returns a signed int: widen through unsigned, or the low word would be sign-extended)
+__device__ inline uint64_t uniform64(uint64_t x) {
+  const unsigned hi = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(x >> 32)));
+  const unsigned lo = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(x & 0xFFFFFFFFu)));
+  return (static_cast<uint64_t>(hi) << 32) | static_cast<uint64_t>(lo);
 }
 
 // Wait until at most N vector-memory operations of this wave are outstanding (they complete
@@ -155,10 +159,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   if (n_tiles == 0) return;  // cannot happen for a well-formed layout: every row sees itself
   const const_words ent = (const_words)(reinterpret_cast<uintptr_t>(p.list_ent + 2 * static_cast<int64_t>(e0)));
 
-  const __bf16* kpool = static_cast<const __bf16*>(p.k_pool.ptr) + hk * p.k_pool.stride_head;
-  const __bf16* vpool = static_cast<const __bf16*>(p.v_pool.ptr) + hk * p.v_pool.stride_head;
-  const __bf16* kself = static_cast<const __bf16*>(p.k_self.ptr) + hk * p.k_self.stride_head;
-  const __bf16* vself = static_cast<const __bf16*>(p.v_self.ptr) + hk * p.v_self.stride_head;
+  // byte addresses of this KV head's first token
+  const uint64_t kpool = uniform64(reinterpret_cast<uint64_t>(static_cast<const __bf16*>(p.k_pool.ptr) + hk * p.k_pool.stride_head));
+  const uint64_t vpool = uniform64(reinterpret_cast<uint64_t>(static_cast<const __bf16*>(p.v_pool.ptr) + hk * p.v_pool.stride_head));
+  const uint64_t kself = uniform64(reinterpret_cast<uint64_t>(static_cast<const __bf16*>(p.k_self.ptr) + hk * p.k_self.stride_head));
+  const uint64_t vself = uniform64(reinterpret_cast<uint64_t>(static_cast<const __bf16*>(p.v_self.ptr) + hk * p.v_self.stride_head));
   const int kp_stride = static_cast<int>(p.k_pool.stride_tok), vp_stride = static_cast<int>(p.v_pool.stride_tok);
   const int ks_stride = static_cast<int>(p.k_self.stride_tok), vs_stride = static_cast<int>(p.v_self.stride_tok);
 
@@ -179,38 +184,40 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
     k_lane_off[j] = static_cast<unsigned>(row_in * kp_stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u;
     v_lane_off[j] = static_cast<unsigned>(row_in * vp_stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u;
   }
-  auto issue_k = [&](const TileRef& t, int stage) DBSA_INLINE {
-    const __bf16* base = (t.self ? kself : kpool) + static_cast<int64_t>(t.start) * (t.self ? ks_stride : kp_stride);
-    const unsigned dst = lds0 + stage * kTileBytes + wave * kBlocksPerWave * 1024;
-    if (!t.self && t.len == kBN) {
-#pragma unroll
-      for (int j = 0; j < kBlocksPerWave; ++j) dma16(base, k_lane_off[j], dst + j * 1024);
+  // load block j (0 .. kBlocksPerWave-1) of this wave's share of a K / V tile
+  auto issue_k_block = [&](const TileRef& t, int stage, int j) DBSA_INLINE {
+    const uint64_t base = (t.self ? kself : kpool) + static_cast<uint64_t>(static_cast<unsigned>(t.start)) *
+                                                         static_cast<unsigned>(2 * (t.self ? ks_stride : kp_stride));
+    const unsigned dst = lds0 + stage * kTileBytes + (wave * kBlocksPerWave + j) * 1024;
+    if (__builtin_expect(!t.self && t.len == kBN, 1)) {
+      dma16(base, k_lane_off[j], dst);
     } else {
       const int stride = t.self ? ks_stride : kp_stride;
-#pragma unroll
-      for (int j = 0; j < kBlocksPerWave; ++j) {
-        const int row_in = 4 * (wave * kBlocksPerWave + j) + lane / 16;
-        const int row = min(row_in, t.len - 1);  // rows past the tail repeat the last key
-        dma16(base, static_cast<unsigned>(row * stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u, dst + j * 1024);
-      }
+      const int row_in = 4 * (wave * kBlocksPerWave + j) + lane / 16;
+      const int row = min(row_in, t.len - 1);  // rows past the tail repeat the last key
+      dma16(base, static_cast<unsigned>(row * stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u, dst);
     }
   };
-  auto issue_v = [&](const TileRef& t, int stage) DBSA_INLINE {
-    const __bf16* base = (t.self ? vself : vpool) + static_cast<int64_t>(t.start) * (t.self ? vs_stride : vp_stride);
-    const unsigned dst = lds0 + (KS + stage) * kTileBytes + wave * kBlocksPerWave * 1024;
-    if (!t.self && t.len == kBN) {
-#pragma unroll
-      for (int j = 0; j < kBlocksPerWave; ++j) dma16(base, v_lane_off[j], dst + j * 1024);
+  auto issue_v_block = [&](const TileRef& t, int stage, int j) DBSA_INLINE {
+    const uint64_t base = (t.self ? vself : vpool) + static_cast<uint64_t>(static_cast<unsigned>(t.start)) *
+                                                         static_cast<unsigned>(2 * (t.self ? vs_stride : vp_stride));
+    const unsigned dst = lds0 + (KS + stage) * kTileBytes + (wave * kBlocksPerWave + j) * 1024;
+    if (__builtin_expect(!t.self && t.len == kBN, 1)) {
+      dma16(base, v_lane_off[j], dst);
     } else {
       const int stride = t.self ? vs_stride : vp_stride;
-#pragma unroll
-      for (int j = 0; j < kBlocksPerWave; ++j) {
-        const int row_in = 4 * (wave * kBlocksPerWave + j) + lane / 16;
-        const int row = min(row_in, t.len - 1);
-        dma16(base, static_cast<unsigned>(row * stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u,
-              dst + j * 1024);
-      }
+      const int row_in = 4 * (wave * kBlocksPerWave + j) + lane / 16;
+      const int row = min(row_in, t.len - 1);
+      dma16(base, static_cast<unsigned>(row * stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u, dst);
     }
+  };
+  auto issue_k = [&](const TileRef& t, int stage) DBSA_INLINE {
+#pragma unroll
+    for (int j = 0; j < kBlocksPerWave; ++j) issue_k_block(t, stage, j);
+  };
+  auto issue_v = [&](const TileRef& t, int stage) DBSA_INLINE {
+#pragma unroll
+    for (int j = 0; j < kBlocksPerWave; ++j) issue_v_block(t, stage, j);
   };
 
   // ---- per-lane LDS read addresses (absolute LDS byte addresses, stage included) ----
@@ -385,7 +392,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
       else
         ring[(t + kDist) % kRing] = ld_v(std::integral_constant<int, (t + kDist) % 16>{});
       if constexpr (t == 0) {
-        // this step's loads go out behind the first matrix instruction: K(it+2+SL), V(it+SL)
+        // this step's loads go out behind the first matrix instruction: K(it+2+SL), V(it+SL).
+        // (Spreading them over the phase, one per few matrix instructions, measured slower: every
+        // load sits behind a branch on the list length, and each branch splits the straight-line code.)
         if (it + 2 + SL < n_tiles) issue_k(refs[1 + SL], k_wr);
         if (it + SL < n_tiles) issue_v(refs[SL - 1], v_wr);
         if (it + 3 + SL < n_tiles) {

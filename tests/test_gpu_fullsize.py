@@ -75,7 +75,7 @@ def test_config1_preencode_full_size():
 
 
 def test_config2_preencode_full_size():
-    preencode_fullsize(synth.config2_pool(), 64, "cfg2 pre-encode")
+    preencode_fullsize(synth.config2_pool(), B.BENCH_BLOCK_M_PREENCODE, "cfg2 pre-encode")
 
 
 def _query_fullsize(pc, qc, block_m, oracle_queries, decode_steps, what):
@@ -114,7 +114,7 @@ def cfg2():
 def test_config3_query_stage_full_size(cfg2):
     qc = synth.config3_query(cfg2)
     assert int(qc.sel_ptr[1]) == 7
-    _query_fullsize(cfg2, qc, 64, oracle_queries=(0, 7, 15), decode_steps=(0, 31), what="cfg3")
+    _query_fullsize(cfg2, qc, B.BENCH_BLOCK_M_QUERY, oracle_queries=(0, 7, 15), decode_steps=(0, 31), what="cfg3")
 
 
 @pytest.mark.parametrize("ratio", synth.RETRIEVAL_RATIOS)
