@@ -17,9 +17,9 @@ from gpu_util import assert_close, to_dev, to_f64
 pytestmark = pytest.mark.gpu
 
 
-def sample_rows(pool, seed, n_random=96, edge=70):
+def sample_rows(pool, seed, n_random=1024, edge=130):
     """Random rows + the sink + first/last rows of the first, a middle and the last group
-    + the demo boundaries of one group."""
+    + every demo boundary of one group."""
     rng = np.random.default_rng(seed)
     gb = pool.group_token_bounds()
     rows = set(rng.choice(pool.n_tokens, size=n_random, replace=False).tolist())
@@ -28,7 +28,7 @@ def sample_rows(pool, seed, n_random=96, edge=70):
         rows |= set(range(int(gb[g]), int(gb[g]) + edge)) | set(range(int(gb[g + 1]) - edge, int(gb[g + 1])))
     g = min(1, pool.n_groups - 1)
     d0, d1 = pool.group_demo_offsets[g], pool.group_demo_offsets[g + 1]
-    for b in pool.demo_offsets[d0:d1 + 1][:24]:
+    for b in pool.demo_offsets[d0:d1 + 1]:
         rows |= {int(b) - 1, int(b)} & set(range(pool.n_tokens))
     return np.array(sorted(rows), dtype=np.int64)
 
@@ -114,14 +114,17 @@ def cfg2():
 def test_config3_query_stage_full_size(cfg2):
     qc = synth.config3_query(cfg2)
     assert int(qc.sel_ptr[1]) == 7
-    _query_fullsize(cfg2, qc, B.BENCH_BLOCK_M_QUERY, oracle_queries=(0, 7, 15), decode_steps=(0, 31), what="cfg3")
+    _query_fullsize(cfg2, qc, B.BENCH_BLOCK_M_QUERY, oracle_queries=tuple(range(16)), decode_steps=(0, 15, 31),
+                    what="cfg3")
 
 
 @pytest.mark.parametrize("ratio", synth.RETRIEVAL_RATIOS)
 def test_config4_sweep_full_size(cfg2, ratio):
     qc = synth.config4_query(cfg2, ratio)
     assert int(qc.sel_ptr[1]) == {0.10: 2, 0.30: 7, 0.50: 11, 1.00: 22}[ratio]
-    _query_fullsize(cfg2, qc, 32, oracle_queries=(0, 127), decode_steps=(0,), what=f"cfg4 ratio {ratio}")
+    n_oracle = 32 if ratio == 0.10 else 8
+    queries = tuple(int(u) for u in np.linspace(0, qc.n_queries - 1, n_oracle).round())
+    _query_fullsize(cfg2, qc, 32, oracle_queries=queries, decode_steps=(0,), what=f"cfg4 ratio {ratio}")
 
 
 def test_config4_full_retrieval_equals_dense_causal(cfg2):
