@@ -298,3 +298,58 @@ def config4_query(pc: PoolCase, ratio: float, n_queries: int = 128, q_len: int =
     seed = 1004 + 10 * RETRIEVAL_RATIOS.index(ratio) if ratio in RETRIEVAL_RATIOS else 1004
     return make_query_case(f"cfg4_r{int(round(ratio * 100))}", seed, pc, n_queries=n_queries, q_len=q_len,
                            n_select=select_count(ratio, pc.pool.n_groups), n_decode=1)
+
+
+# --------------------------------------------------------------------------
+# the paper's own pool structure (Sec. 3 implementation details; Sec. 5.2 patterns)
+# --------------------------------------------------------------------------
+
+
+def block_pool(demo_lens: np.ndarray, demos_per_block: int, sink_is_first_block: bool = True) -> Pool:
+    """Blocks of ``demos_per_block`` consecutive demos (the last block takes the remainder).
+    With ``sink_is_first_block`` the first block becomes the sink prefix and the remaining
+    blocks the groups; otherwise there is no sink and every block is a group."""
+    lens = np.asarray(demo_lens, dtype=np.int64)
+    n_sink = min(demos_per_block, len(lens) - 1) if sink_is_first_block else 0
+    sink_len = int(lens[:n_sink].sum())
+    rest = lens[n_sink:]
+    offs = np.concatenate([[sink_len], sink_len + np.cumsum(rest)])
+    gdo = list(range(0, len(rest), demos_per_block))
+    if len(rest) - gdo[-1] < max(1, demos_per_block // 2) and len(gdo) > 1:
+        gdo.pop()                      # a short remainder joins the block before it
+    gdo.append(len(rest))
+    return Pool(sink_len, offs.astype(np.int32), np.asarray(gdo, dtype=np.int32))
+
+
+def make_block_pool_case(name: str, seed: int, *, n_demos: int, demos_per_block: int, demo_len_range,
+                         prev_window: int, sink_is_first_block: bool = True, dtype: str = "bf16",
+                         n_q_heads: int = 32, n_kv_heads: int = 8, head_dim: int = 128,
+                         k_channel_sigma: float = 0.5) -> PoolCase:
+    """Draw order: demo lengths, Q, K, V, K channel scales (as make_pool_case)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    lo, hi = demo_len_range
+    pool = block_pool(rng.integers(lo, hi + 1, size=n_demos), demos_per_block, sink_is_first_block)
+    n = pool.n_tokens
+    q = _normal(rng, (n, n_q_heads, head_dim))
+    k = _normal(rng, (n, n_kv_heads, head_dim))
+    v = _normal(rng, (n, n_kv_heads, head_dim))
+    if k_channel_sigma > 0.0:
+        z = rng.standard_normal((n_kv_heads, head_dim)).astype(np.float32)
+        k *= np.exp(np.float32(k_channel_sigma) * z)[None, :, :]
+    return PoolCase(name, seed, dtype, n_q_heads, n_kv_heads, head_dim, 1.0 / float(np.sqrt(head_dim)),
+                    pool, _store(q, dtype), _store(k, dtype), _store(v, dtype), prev_window)
+
+
+def paper_setting_pool(n_demos: int = 2400, demos_per_block: int = 50) -> PoolCase:
+    """The 90k setting as the paper runs it (Sec. 3): 2400 demonstrations of ~37 tokens in
+    blocks of 50, the first block is the attention sink, every block also sees the two
+    blocks before it.  Llama-3.1-8B head shape, synthetic values as in config 2."""
+    return make_block_pool_case("paper90k", 1005, n_demos=n_demos, demos_per_block=demos_per_block,
+                                demo_len_range=(28, 47), prev_window=2)
+
+
+def paper_setting_query(pc: PoolCase, n_queries: int = 16, q_len: int = 64, ratio: float = 0.30,
+                        n_decode: int = 32) -> QueryCase:
+    """30 % of the blocks per query (the sink block is always present), then decode."""
+    return make_query_case("paper90k_q", 1006, pc, n_queries=n_queries, q_len=q_len,
+                           n_select=select_count(ratio, pc.pool.n_groups), n_decode=n_decode)
