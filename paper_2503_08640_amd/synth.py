@@ -293,6 +293,14 @@ def config3_query(pc: PoolCase, n_queries: int = 16, q_len: int = 64, ratio: flo
                            n_select=select_count(ratio, pc.pool.n_groups), n_decode=n_decode)
 
 
+def mha30k_query(pc: PoolCase, n_queries: int = 16, q_len: int = 64, ratio: float = 0.30,
+                 n_decode: int = 32) -> QueryCase:
+    """Query stage over the config-1 pool (the paper's 30k / Llama-2-7B MHA setting, Sec. 3):
+    30 % of 8 groups = 2 groups per query."""
+    return make_query_case("mha30k", 1007, pc, n_queries=n_queries, q_len=q_len,
+                           n_select=select_count(ratio, pc.pool.n_groups), n_decode=n_decode)
+
+
 def config4_query(pc: PoolCase, ratio: float, n_queries: int = 128, q_len: int = 32) -> QueryCase:
     # one seed per ratio so that the four sweeps are independent draws
     seed = 1004 + 10 * RETRIEVAL_RATIOS.index(ratio) if ratio in RETRIEVAL_RATIOS else 1004

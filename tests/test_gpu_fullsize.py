@@ -106,6 +106,15 @@ def _query_fullsize(pc, qc, block_m, oracle_queries, decode_steps, what):
     return lay, kp, vp
 
 
+def test_mha_30k_query_stage_full_size():
+    """The paper's other efficiency setting (Sec. 3: 30k pool, MHA 32 x 128): query prefill and
+    decode over the config-1 pool, 2 of 8 groups per query."""
+    pc = synth.config1_pool()
+    qc = synth.mha30k_query(pc)
+    assert int(qc.sel_ptr[1]) == 2
+    _query_fullsize(pc, qc, 64, oracle_queries=(0, 5, 10, 15), decode_steps=(0, 31), what="MHA 30k")
+
+
 @pytest.fixture(scope="module")
 def cfg2():
     return synth.config2_pool()

@@ -186,6 +186,18 @@ def test_query_and_decode_bf16_ragged_queries(block_m, n_split):
     _run_decode_steps(pc, qc, lay, kp, vp, range(3), f"bm={block_m} ns={n_split}")
 
 
+@pytest.mark.parametrize("hq,hkv,block_m", [(4, 4, 128), (4, 4, 32), (4, 2, 64), (8, 1, 32), (16, 1, 32)])
+def test_query_and_decode_bf16_head_ratios(hq, hkv, block_m):
+    """MHA (one query head per KV head) up to 16 query heads per KV head; 40 queries on few
+    groups so that decode items serve more queries than one wave has columns."""
+    pc = small_pool_case("ratio", 2060 + hq + hkv, hq=hq, hkv=hkv, pool_tokens=2500, groups=3, lens=(32, 128))
+    qc = synth.make_query_case("qr", 2061, pc, n_queries=40, q_len=9, n_select=2, n_decode=2)
+    lay, kp, vp = _query_setup(pc, qc, block_m, 0)
+    oq = B.dbsa_query_attn(lay, to_dev(qc.q), to_dev(qc.k), to_dev(qc.v), kp, vp, pc.scale)
+    assert_close(to_f64(oq), _oracle_query(pc, qc), f"query Hq={hq} Hkv={hkv} bm={block_m}")
+    _run_decode_steps(pc, qc, lay, kp, vp, range(2), f"Hq={hq} Hkv={hkv}")
+
+
 def test_all_groups_selected_matches_dense_causal_oracle_and_order_is_irrelevant():
     pc = small_pool_case("full", 2030, hq=4, hkv=1, pool_tokens=3000, groups=4, lens=(32, 128))
     outs = []
