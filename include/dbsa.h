@@ -118,6 +118,20 @@ int dbsa_layout_build(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, i
                       int32_t flags, void* stream, dbsa_layout** out);
 
 /*
+ * Pre-encode layout for groups appended to an already encoded pool (Sec. 2.1: a group
+ * attends the anchor, its window of preceding groups and itself, and no earlier group
+ * attends it, so the cached K/V of the earlier groups stay valid and the encoding cost of
+ * an addition does not grow with the pool: Sec. 1, and Sec. 2.1 on adding a block at any time).
+ * `pool` describes the WHOLE pool including the new groups; the layout holds the Q tiles
+ * of groups first_group .. n_groups-1 only, each with exactly the list the full pre-encode
+ * layout gives it.  dbsa_preencode_attn with this layout writes the rows of those groups and
+ * leaves every other row of `o` untouched; q/k/v/o are indexed by absolute token as usual.
+ * Errors as dbsa_layout_build; first_group outside [0, n_groups) -> INVALID_ARG.
+ */
+int dbsa_layout_build_append(const dbsa_pool_desc* pool, int32_t first_group, int32_t block_m, int32_t block_n,
+                             int32_t flags, void* stream, dbsa_layout** out);
+
+/*
  * Host views of the lists, valid until the layout is destroyed.
  *   qtile_tab : int32 [n_qtiles][4] = (q_start, q_len, owner, 0); owner is -1 for
  *               the sink segment, else the group (pre-encode) or query index.

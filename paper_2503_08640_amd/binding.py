@@ -35,7 +35,7 @@ DBSA_F32 = 1
 DBSA_LAYOUT_HOST_ONLY = 1
 
 EXPORTED_SYMBOLS = (
-    "dbsa_strerror", "dbsa_layout_build", "dbsa_layout_export", "dbsa_layout_export_decode",
+    "dbsa_strerror", "dbsa_layout_build", "dbsa_layout_build_append", "dbsa_layout_export", "dbsa_layout_export_decode",
     "dbsa_layout_export_decode_groups", "dbsa_layout_export_order", "dbsa_layout_destroy", "dbsa_workspace_bytes", "dbsa_preencode_attn",
     "dbsa_query_attn", "dbsa_decode_attn",
 )
@@ -77,6 +77,9 @@ def lib() -> C.CDLL:
     L.dbsa_layout_build.restype = C.c_int
     L.dbsa_layout_build.argtypes = [C.POINTER(PoolDesc), C.POINTER(SelectDesc), C.c_int32, C.c_int32, C.c_int32,
                                     C.c_void_p, C.POINTER(C.c_void_p)]
+    L.dbsa_layout_build_append.restype = C.c_int
+    L.dbsa_layout_build_append.argtypes = [C.POINTER(PoolDesc), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                           C.POINTER(C.c_void_p)]
     L.dbsa_layout_export.restype = C.c_int
     L.dbsa_layout_export.argtypes = [C.c_void_p, C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int64),
                                      C.POINTER(C.POINTER(C.c_int64)), C.POINTER(C.POINTER(C.c_int32)),
@@ -210,6 +213,19 @@ def dbsa_layout_build(sink_len: int, demo_offsets, group_demo_offsets, prev_wind
                                  DBSA_LAYOUT_HOST_ONLY if host_only else 0, C.c_void_p(stream), C.byref(out))
     _check(rc, "dbsa_layout_build")
     return Layout(out.value, cu_qlens is not None, int(block_m), int(block_n))
+
+
+def dbsa_layout_build_append(sink_len: int, demo_offsets, group_demo_offsets, prev_window: int, first_group: int, *,
+                             block_m: int = 64, block_n: int = 64, host_only: bool = False,
+                             stream: int = 0) -> Layout:
+    """Pre-encode layout holding only the Q tiles of groups first_group.. of the described pool."""
+    do, gdo = _i32(demo_offsets), _i32(group_demo_offsets)
+    pool = PoolDesc(int(sink_len), len(do) - 1, _p32(do), len(gdo) - 1, _p32(gdo), int(prev_window))
+    out = C.c_void_p()
+    rc = lib().dbsa_layout_build_append(C.byref(pool), int(first_group), int(block_m), int(block_n),
+                                        DBSA_LAYOUT_HOST_ONLY if host_only else 0, C.c_void_p(stream), C.byref(out))
+    _check(rc, "dbsa_layout_build_append")
+    return Layout(out.value, False, int(block_m), int(block_n))
 
 
 # ---------------------------------------------------------------------------

@@ -230,14 +230,15 @@ const char* dbsa_strerror(int code) {
   }
 }
 
-int dbsa_layout_build(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, int32_t block_m, int32_t block_n,
-                      int32_t flags, void* stream, dbsa_layout** out) {
+namespace {
+int build_layout(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, int32_t first_group, int32_t block_m,
+                 int32_t block_n, int32_t flags, void* stream, dbsa_layout** out) {
   if (!out || (flags & ~DBSA_LAYOUT_HOST_ONLY)) return DBSA_ERR_INVALID_ARG;
   dbsa_layout* L = new (std::nothrow) dbsa_layout();
   if (!L) return DBSA_ERR_INVALID_ARG;
   int rc = DBSA_OK;
   try {
-    rc = dbsa_build_host_lists(pool, sel, block_m, block_n, L);
+    rc = dbsa_build_host_lists(pool, sel, first_group, block_m, block_n, L);
   } catch (...) {
     rc = DBSA_ERR_INVALID_ARG;
   }
@@ -255,6 +256,18 @@ int dbsa_layout_build(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, i
   }
   *out = L;
   return DBSA_OK;
+}
+}  // namespace
+
+int dbsa_layout_build(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, int32_t block_m, int32_t block_n,
+                      int32_t flags, void* stream, dbsa_layout** out) {
+  return build_layout(pool, sel, -1, block_m, block_n, flags, stream, out);
+}
+
+int dbsa_layout_build_append(const dbsa_pool_desc* pool, int32_t first_group, int32_t block_m, int32_t block_n,
+                             int32_t flags, void* stream, dbsa_layout** out) {
+  if (first_group < 0) return DBSA_ERR_INVALID_ARG;
+  return build_layout(pool, nullptr, first_group, block_m, block_n, flags, stream, out);
 }
 
 int dbsa_layout_export(const dbsa_layout* L, const int32_t** qtile_tab, int64_t* n_qtiles, const int64_t** list_ptr,

@@ -50,7 +50,7 @@ bool strictly_increasing(const int32_t* a, int64_t n) {
 
 }  // namespace
 
-int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, int32_t block_m, int32_t block_n,
+int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, int32_t first_group, int32_t block_m, int32_t block_n,
                           dbsa_layout* L) {
   if (!pool || !L || block_m <= 0 || block_n <= 0 || block_n >= (1 << 16)) return DBSA_ERR_INVALID_ARG;
   if (!pool->demo_offsets || !pool->group_demo_offsets || pool->n_demos < 1 || pool->n_groups < 1 ||
@@ -65,6 +65,7 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
     return DBSA_ERR_BAD_BOUNDS;
 
   const int32_t G = pool->n_groups;
+  if (first_group >= 0 && (sel || first_group >= G)) return DBSA_ERR_INVALID_ARG;
   std::vector<Seg> group(G);
   for (int32_t g = 0; g < G; ++g) group[g] = Seg{doff[gdo[g]], doff[gdo[g + 1]]};
   const Seg sink{0, S};
@@ -85,12 +86,14 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
 
   if (!sel) {
     // ---- stage 1 ----
-    for (int64_t q0 = 0; q0 < S; q0 += block_m) {
+    // An appended group sees the sink, its window of preceding groups and itself; nothing
+    // already encoded sees it (Sec. 2.1), so encoding it means walking its own Q tiles only.
+    for (int64_t q0 = 0; q0 < S && first_group < 0; q0 += block_m) {
       const int32_t qn = static_cast<int32_t>(std::min<int64_t>(block_m, S - q0));
       push_causal_segment(L->list_ent, sink, block_n, static_cast<int32_t>(q0), qn, DBSA_TILE_FULL, DBSA_TILE_CAUSAL);
       close_tile(static_cast<int32_t>(q0), qn, -1);
     }
-    for (int32_t g = 0; g < G; ++g) {
+    for (int32_t g = std::max(first_group, 0); g < G; ++g) {
       const int32_t first_prev = std::max<int64_t>(0, static_cast<int64_t>(g) - pool->prev_window);
       for (int64_t q0 = group[g].begin; q0 < group[g].end; q0 += block_m) {
         const int32_t qn = static_cast<int32_t>(std::min<int64_t>(block_m, group[g].end - q0));

@@ -53,5 +53,6 @@ struct dbsa_layout {
 };
 
 // Pure host integer work; returns a DBSA_* code and fills `L` on success.
-int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, int32_t block_m, int32_t block_n,
+// first_group < 0: every segment; >= 0 (pre-encode only): Q tiles of groups first_group.. alone
+int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, int32_t first_group, int32_t block_m, int32_t block_n,
                           dbsa_layout* L);

@@ -7,6 +7,7 @@ import re
 import numpy as np
 import pytest
 
+from oracle import dbsa_oracle as orc
 from oracle import layout_oracle as lo
 from paper_2503_08640_amd import binding as B
 from paper_2503_08640_amd import synth
@@ -59,6 +60,33 @@ def test_preencode_lists_match_oracle_on_random_pools(seed):
     assert np.all(np.diff(owners) >= 0)                      # owner by owner
     same = owners[:-1] == owners[1:]
     assert np.all(lens[:-1][same] >= lens[1:][same])         # longest list of an owner first
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_append_layout_is_the_tail_of_the_full_layout(seed):
+    """Sec. 2.1: an added group attends the anchor, its window and itself, and nothing encoded
+    earlier attends it: its Q tiles and lists are those of the full pre-encode layout."""
+    rng = np.random.default_rng(200 + seed)
+    pool = rand_pool(rng, sink_len=int(rng.integers(0, 12)), n_groups=int(rng.integers(2, 7)))
+    w = int(rng.integers(0, 3))
+    bm, bn = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+    g0 = int(rng.integers(0, pool.n_groups))
+    lay = B.dbsa_layout_build_append(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, w, g0, block_m=bm,
+                                     block_n=bn, host_only=True)
+    tab, ptr, ent = lo.preencode_layout(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, w, bm, bn)
+    keep = np.nonzero(tab[:, 2] >= g0)[0]
+    assert len(keep) > 0 and np.array_equal(keep, np.arange(keep[0], len(tab)))   # a suffix of the tile table
+    e0 = ptr[keep[0]]
+    assert_same_lists(lay.export(), (tab[keep], ptr[keep[0]:] - e0, ent[e0:]))
+    # the oracle's predicate says the same thing: no row before the new groups sees a key inside them
+    first_new = int(pool.group_token_bounds()[g0])
+    demo_of, group_of = orc.token_maps(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets)
+    vis = orc.mask_pre(np.arange(first_new), pool.sink_len, demo_of, group_of, w)
+    assert not vis[:, first_new:].any()
+    for bad in (-1, pool.n_groups):
+        with pytest.raises(B.DbsaError):
+            B.dbsa_layout_build_append(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, w, bad, block_m=bm,
+                                       block_n=bn, host_only=True)
 
 
 @pytest.mark.parametrize("seed", range(8))
