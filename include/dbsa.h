@@ -152,6 +152,27 @@ int dbsa_layout_export_decode(const dbsa_layout* layout, const int64_t** dec_ptr
                               int64_t* n_dec_ent, const int64_t** split_ptr, int32_t* n_split);
 
 /*
+ * Re-positioning data of a query-stage layout (INVALID_ARG for a pre-encode layout).
+ * Sec. 2.2: the caches of the anchor and of the selected groups are concatenated in the
+ * caller's order and receive new in-order position ids 0 .. |D'|-1; the query follows at
+ * ids |D'| + a.  The *_rope attention calls expect keys rotated at the id they were ENCODED
+ * with (pool keys: their token index, Sec. 2.1 "sequential position ids"; a query's own
+ * keys: their index inside the query) and move a run of keys to its new ids by rotating the
+ * query row back by the run's displacement instead (rotary scores depend on id differences
+ * only), so no per-query copy of the keys is ever made.
+ *   list_shift : int32 [n_ent], parallel to list_ent.  Row number i of a Q tile (i = 0 at the
+ *                tile's first row) scores the keys of entry e after a rotation at id
+ *                list_shift[e] + i.
+ *   qref_shift : int32 [n_qrefs], parallel to qrefs of the group-major decode schedule: the
+ *                decode row of query u scores the item's keys after a rotation at id
+ *                qref_shift[ref] + self_len[u] - 1; its own cached keys at self_len[u] - 1.
+ *   cache_len  : int32 [B] = |D'| of each query (sink + selected groups).
+ * Any output pointer may be NULL; views are valid until the layout is destroyed.
+ */
+int dbsa_layout_export_positions(const dbsa_layout* layout, const int32_t** list_shift, const int32_t** qref_shift,
+                                 const int32_t** cache_len);
+
+/*
  * Group-major decode schedule of a query-stage layout (INVALID_ARG for a pre-encode
  * layout).  Queries that selected the same group read the same KV (Sec. 2.2: the caches
  * of the selected groups are reused in place), so one work item covers a run of KV tiles

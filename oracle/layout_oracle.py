@@ -161,3 +161,39 @@ def decode_group_schedule(sink_len, demo_offsets, group_demo_offsets, n_queries,
     return dict(seg_ptr=np.asarray(seg_ptr, np.int64), seg_ent=_pack(seg_ent),
                 items=np.asarray(items, np.int32).reshape(-1, 4), qrefs=np.asarray(qrefs, np.int32).reshape(-1, 2),
                 slot_ptr=slot_ptr)
+
+
+def position_shifts(sink_len, demo_offsets, group_demo_offsets, cu_qlens, sel_ptr, sel_idx, qtile_tab, list_ptr,
+                    list_ent, seg_ent, items, qrefs):
+    """Re-positioning data (Sec. 2.2), derived from the new position ids themselves: the
+    concatenated cache of query u lists its pool tokens in order and the i-th of them gets id i.
+    A list entry (or schedule item) whose first key moves from id j to id j' has displacement
+    j' - j; a query row at new id ``cache_len + a`` is rotated at ``cache_len + a - (j' - j)``
+    instead.  Returns (list_shift parallel to ``list_ent`` with the tile's first local row
+    index folded in, qref_shift parallel to ``qrefs``, cache_len [B])."""
+    from . import rope_oracle as ro
+    n_queries = len(cu_qlens) - 1
+    new_id, cache_len = [], []
+    for u in range(n_queries):
+        ids = ro.selected_token_ids(sink_len, demo_offsets, group_demo_offsets,
+                                    sel_idx[int(sel_ptr[u]):int(sel_ptr[u + 1])])
+        new_id.append({int(j): i for i, j in enumerate(ids)})
+        cache_len.append(len(ids))
+    list_shift = np.zeros(len(list_ent), dtype=np.int32)
+    for t in range(len(qtile_tab)):
+        q0, _, u, _ = (int(x) for x in qtile_tab[t])
+        a0 = q0 - int(cu_qlens[u])
+        for e in range(int(list_ptr[t]), int(list_ptr[t + 1])):
+            j, kind = int(list_ent[e, 0]), int(list_ent[e, 1]) >> 16
+            if kind in (KIND_SELF_FULL, KIND_SELF_CAUSAL):
+                list_shift[e] = a0                                  # own keys keep their local ids
+            else:
+                list_shift[e] = cache_len[u] - (new_id[u][j] - j) + a0
+    qref_shift = np.zeros(len(qrefs), dtype=np.int32)
+    for (ent_begin, _, ref_begin, n_q) in (tuple(int(x) for x in it) for it in items):
+        j = int(seg_ent[ent_begin, 0])
+        for ref in range(ref_begin, ref_begin + n_q):
+            u = int(qrefs[ref, 0])
+            qref_shift[ref] = cache_len[u] - (new_id[u][j] - j)
+    return list_shift, qref_shift, np.asarray(cache_len, dtype=np.int32)
+

@@ -36,7 +36,7 @@ DBSA_LAYOUT_HOST_ONLY = 1
 
 EXPORTED_SYMBOLS = (
     "dbsa_strerror", "dbsa_layout_build", "dbsa_layout_build_append", "dbsa_layout_export", "dbsa_layout_export_decode",
-    "dbsa_layout_export_decode_groups", "dbsa_layout_export_order", "dbsa_layout_destroy", "dbsa_workspace_bytes", "dbsa_preencode_attn",
+    "dbsa_layout_export_decode_groups", "dbsa_layout_export_order", "dbsa_layout_export_positions", "dbsa_layout_destroy", "dbsa_workspace_bytes", "dbsa_preencode_attn",
     "dbsa_query_attn", "dbsa_decode_attn",
 )
 
@@ -93,6 +93,8 @@ def lib() -> C.CDLL:
         C.c_void_p, C.POINTER(C.POINTER(C.c_int64)), C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int64),
         C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int64), C.POINTER(C.POINTER(C.c_int32)),
         C.POINTER(C.c_int64), C.POINTER(C.POINTER(C.c_int64)), C.POINTER(C.c_int32)]
+    L.dbsa_layout_export_positions.restype = C.c_int
+    L.dbsa_layout_export_positions.argtypes = [C.c_void_p] + [C.POINTER(C.POINTER(C.c_int32))] * 3
     L.dbsa_layout_export_order.restype = C.c_int
     L.dbsa_layout_export_order.argtypes = [C.c_void_p, C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int64)]
     L.dbsa_layout_destroy.restype = None
@@ -190,6 +192,21 @@ class Layout:
         op, n = C.POINTER(C.c_int32)(), C.c_int64()
         _check(lib().dbsa_layout_export_order(self.handle, C.byref(op), C.byref(n)), "dbsa_layout_export_order")
         return np.ctypeslib.as_array(op, shape=(n.value,)).copy() if n.value else np.zeros(0, np.int32)
+
+    def export_positions(self, n_queries: int):
+        """-> (list_shift [n_ent], qref_shift [n_qrefs], cache_len [B]) int32 copies."""
+        ls, qs, cl = (C.POINTER(C.c_int32)() for _ in range(3))
+        _check(lib().dbsa_layout_export_positions(self.handle, C.byref(ls), C.byref(qs), C.byref(cl)),
+               "dbsa_layout_export_positions")
+        n_ent = self.export()[2].shape[0]
+        it, ni, qr, nr = C.POINTER(C.c_int32)(), C.c_int64(), C.POINTER(C.c_int32)(), C.c_int64()
+        _check(lib().dbsa_layout_export_decode_groups(self.handle, None, None, None, C.byref(it), C.byref(ni),
+                                                      C.byref(qr), C.byref(nr), None, None),
+               "dbsa_layout_export_decode_groups")
+
+        def arr(p, n):
+            return np.ctypeslib.as_array(p, shape=(n,)).copy() if n else np.zeros(0, np.int32)
+        return arr(ls, n_ent), arr(qs, nr.value), arr(cl, n_queries)
 
     def workspace_bytes(self, n_q_heads: int, head_dim: int) -> int:
         return int(lib().dbsa_workspace_bytes(self.handle, n_q_heads, head_dim))

@@ -65,11 +65,12 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
                b_ent = L->list_ent.size() * sizeof(int32_t), b_ord = L->order.size() * sizeof(int32_t),
                b_dec = L->dec_ent.size() * sizeof(int32_t), b_spl = L->split_ptr.size() * sizeof(int64_t),
                b_gse = L->gm_seg_ent.size() * sizeof(int32_t), b_git = L->gm_items.size() * sizeof(int32_t),
-               b_gqr = L->gm_qrefs.size() * sizeof(int32_t), b_gsp = L->gm_slot_ptr.size() * sizeof(int64_t);
+               b_gqr = L->gm_qrefs.size() * sizeof(int32_t), b_gsp = L->gm_slot_ptr.size() * sizeof(int64_t),
+               b_lsh = L->list_shift.size() * sizeof(int32_t), b_gqs = L->gm_qshift.size() * sizeof(int32_t);
   const size_t o_tab = 0, o_ptr = o_tab + pad(b_tab), o_ent = o_ptr + pad(b_ptr), o_ord = o_ent + pad(b_ent),
                o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), o_gse = o_spl + pad(b_spl),
                o_git = o_gse + pad(b_gse), o_gqr = o_git + pad(b_git), o_gsp = o_gqr + pad(b_gqr),
-               total = o_gsp + pad(b_gsp) + 256;
+               o_lsh = o_gsp + pad(b_gsp), o_gqs = o_lsh + pad(b_lsh), total = o_gqs + pad(b_gqs) + 256;
   ListBlock blk{};
   hipError_t e = acquire_block(total, &blk);
   if (e != hipSuccess) return e;
@@ -87,6 +88,8 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   put(o_git, L->gm_items.data(), b_git);
   put(o_gqr, L->gm_qrefs.data(), b_gqr);
   put(o_gsp, L->gm_slot_ptr.data(), b_gsp);
+  put(o_lsh, L->list_shift.data(), b_lsh);
+  put(o_gqs, L->gm_qshift.data(), b_gqs);
   e = hipMemcpyAsync(blk.dev, blk.pinned, total, hipMemcpyHostToDevice, stream);
   if (e == hipSuccess) e = hipStreamSynchronize(stream);  // the staging twin may be reused after return
   if (e != hipSuccess) {
@@ -108,6 +111,8 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   L->dev.gm_items = reinterpret_cast<int32_t*>(b + o_git);
   L->dev.gm_qrefs = reinterpret_cast<int32_t*>(b + o_gqr);
   L->dev.gm_slot_ptr = reinterpret_cast<int64_t*>(b + o_gsp);
+  L->dev.list_shift = reinterpret_cast<int32_t*>(b + o_lsh);
+  L->dev.gm_qshift = reinterpret_cast<int32_t*>(b + o_gqs);
   return hipSuccess;
 }
 
@@ -278,6 +283,15 @@ int dbsa_layout_export(const dbsa_layout* L, const int32_t** qtile_tab, int64_t*
   if (list_ptr) *list_ptr = L->list_ptr.data();
   if (list_ent) *list_ent = L->list_ent.data();
   if (n_ent) *n_ent = L->n_ent();
+  return DBSA_OK;
+}
+
+int dbsa_layout_export_positions(const dbsa_layout* L, const int32_t** list_shift, const int32_t** qref_shift,
+                                 const int32_t** cache_len) {
+  if (!L || !L->query_stage) return DBSA_ERR_INVALID_ARG;
+  if (list_shift) *list_shift = L->list_shift.data();
+  if (qref_shift) *qref_shift = L->gm_qshift.data();
+  if (cache_len) *cache_len = L->cache_len.data();
   return DBSA_OK;
 }
 

@@ -126,6 +126,7 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
     L->n_query_tokens = sel->cu_qlens[B];
     L->dec_ptr.assign(1, 0);
     size_t shortest = SIZE_MAX;
+    std::vector<int32_t> dec_shift;  // per decode-list entry of the current query
     for (int32_t u = 0; u < B; ++u) {
       // pool part, shared by all Q tiles of the query and by decode
       const size_t dec_begin = L->dec_ent.size();
@@ -134,6 +135,22 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
         push_whole_segment(L->dec_ent, group[sel->sel_idx[e]], block_n, DBSA_TILE_FULL);
       L->dec_ptr.push_back(static_cast<int64_t>(L->dec_ent.size() / 2));
       shortest = std::min(shortest, (L->dec_ent.size() - dec_begin) / 2);
+      // new ids (Sec. 2.2): the sink keeps 0 .. S-1, the k-th selected group follows the (k-1)-th,
+      // the query follows the cache.  A run whose first key moves from id j to id j' leaves the
+      // query row (at id cache_len + a) to be rotated at id cache_len + a - (j' - j).
+      int64_t cache_len = S;
+      for (int32_t e = sel->sel_ptr[u]; e < sel->sel_ptr[u + 1]; ++e)
+        cache_len += group[sel->sel_idx[e]].end - group[sel->sel_idx[e]].begin;
+      L->cache_len.push_back(static_cast<int32_t>(cache_len));
+      dec_shift.clear();
+      dec_shift.insert(dec_shift.end(), (static_cast<size_t>(S) + block_n - 1) / block_n, static_cast<int32_t>(cache_len));
+      int64_t new_first = S;
+      for (int32_t e = sel->sel_ptr[u]; e < sel->sel_ptr[u + 1]; ++e) {
+        const Seg gs = group[sel->sel_idx[e]];
+        const size_t n_t = (static_cast<size_t>(gs.end - gs.begin) + block_n - 1) / block_n;
+        dec_shift.insert(dec_shift.end(), n_t, static_cast<int32_t>(cache_len - (new_first - gs.begin)));
+        new_first += gs.end - gs.begin;
+      }
 
       const Seg self{sel->cu_qlens[u], sel->cu_qlens[u + 1]};
       for (int64_t q0 = self.begin; q0 < self.end; q0 += block_m) {
@@ -141,6 +158,9 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
         L->list_ent.insert(L->list_ent.end(), L->dec_ent.begin() + dec_begin, L->dec_ent.end());
         push_causal_segment(L->list_ent, self, block_n, static_cast<int32_t>(q0), qn, DBSA_TILE_SELF_FULL,
                             DBSA_TILE_SELF_CAUSAL);
+        const int32_t a0 = static_cast<int32_t>(q0 - self.begin);  // local index of the tile's first row
+        for (int32_t s : dec_shift) L->list_shift.push_back(s + a0);
+        L->list_shift.resize(L->list_ent.size() / 2, a0);           // own keys sit at their local index
         close_tile(static_cast<int32_t>(q0), qn, u);
       }
     }
@@ -191,6 +211,17 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
                                      : std::min<int64_t>(16, (tile_batches + 191) / 192);
     chunk = std::max<int64_t>(1, chunk);
     L->gm_chunk_tiles = static_cast<int32_t>(chunk);
+    // displacement of segment s for user u, as in list_shift but without a tile offset
+    std::vector<int32_t> seg_shift(static_cast<size_t>(B) * (G + 1), 0);
+    for (int32_t u = 0; u < B; ++u) {
+      seg_shift[static_cast<size_t>(u) * (G + 1)] = L->cache_len[u];
+      int64_t new_first = S;
+      for (int32_t e = sel->sel_ptr[u]; e < sel->sel_ptr[u + 1]; ++e) {
+        const int32_t g = sel->sel_idx[e];
+        seg_shift[static_cast<size_t>(u) * (G + 1) + g + 1] = static_cast<int32_t>(L->cache_len[u] - (new_first - group[g].begin));
+        new_first += group[g].end - group[g].begin;
+      }
+    }
     std::vector<int64_t> n_slots(B, 0);
     // first pass: count slots per query; second pass: emit items with absolute slot numbers
     for (int pass = 0; pass < 2; ++pass) {
@@ -216,6 +247,7 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
               else {
                 L->gm_qrefs.push_back(u);
                 L->gm_qrefs.push_back(static_cast<int32_t>(L->gm_slot_ptr[u] + next[u]++));
+                L->gm_qshift.push_back(seg_shift[static_cast<size_t>(u) * (G + 1) + s]);
               }
             }
           }

@@ -22,6 +22,8 @@ struct dbsa_device_lists {
   int32_t* gm_items = nullptr;    // [n_items][4]
   int32_t* gm_qrefs = nullptr;    // [n_qrefs][2]
   int64_t* gm_slot_ptr = nullptr; // [B+1]
+  int32_t* list_shift = nullptr;  // [n_ent]
+  int32_t* gm_qshift = nullptr;   // [n_qrefs]
 };
 
 struct dbsa_layout {
@@ -45,6 +47,16 @@ struct dbsa_layout {
   std::vector<int32_t> gm_items;    // 4 per item: (ent_begin, ent_count, qref_begin, n_q)
   std::vector<int32_t> gm_qrefs;    // 2 per reference: (query, slot)
   std::vector<int64_t> gm_slot_ptr; // [B+1]; the last slot of a query is its own-cache partial
+  // re-positioning (Sec. 2.2: new in-order position ids for the concatenated selected caches).
+  // Keys are stored rotated at the id they were encoded with (pool keys: their token index; a
+  // query's own keys: their index inside the query), so moving a run of keys to its new ids is
+  // the same as rotating the QUERY row back by the run's displacement.  A row with local index a
+  // (inside its query) scores the keys of list entry e after a rotation at id  list_shift[e] +
+  // (a - first local index of its Q tile);  a decode row of query u scores the keys of a
+  // schedule item after a rotation at id  gm_qshift[ref] + self_len[u] - 1.
+  std::vector<int32_t> list_shift;  // [n_ent]
+  std::vector<int32_t> gm_qshift;   // [n_qrefs]
+  std::vector<int32_t> cache_len;   // [B]: |D'| of query u = sink + its selected groups
 
   dbsa_device_lists dev;
 

@@ -62,6 +62,29 @@ def test_preencode_lists_match_oracle_on_random_pools(seed):
     assert np.all(lens[:-1][same] >= lens[1:][same])         # longest list of an owner first
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_repositioning_shifts_match_the_new_position_ids(seed):
+    rng = np.random.default_rng(300 + seed)
+    pool = rand_pool(rng, sink_len=int(rng.integers(0, 7)), n_groups=int(rng.integers(1, 7)))
+    nq = int(rng.integers(1, 6))
+    qlens = rng.integers(1, 12, size=nq)
+    cu = np.concatenate([[0], np.cumsum(qlens)]).astype(np.int32)
+    sels = [rng.permutation(pool.n_groups)[:int(rng.integers(0, pool.n_groups + 1))] for _ in range(nq)]
+    sel_ptr = np.concatenate([[0], np.cumsum([len(s) for s in sels])]).astype(np.int32)
+    sel_idx = np.concatenate(sels).astype(np.int32) if sel_ptr[-1] else np.zeros(0, np.int32)
+    bm, bn = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+    lay = B.dbsa_layout_build(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, cu_qlens=cu, sel_ptr=sel_ptr,
+                              sel_idx=sel_idx, n_split=int(rng.integers(0, 4)), block_m=bm, block_n=bn, host_only=True)
+    tab, ptr, ent = lay.export()
+    g = lay.export_decode_groups(pool.n_groups, nq)
+    got = lay.export_positions(nq)
+    want = lo.position_shifts(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, cu, sel_ptr, sel_idx, tab, ptr,
+                              ent, g["seg_ent"], g["items"], g["qrefs"])
+    for a, b, name in zip(got, want, ("list_shift", "qref_shift", "cache_len")):
+        assert a.dtype == b.dtype and np.array_equal(a, b), name
+    assert np.all(got[0] >= 0) and np.all(got[1] >= 0)
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_append_layout_is_the_tail_of_the_full_layout(seed):
     """Sec. 2.1: an added group attends the anchor, its window and itself, and nothing encoded
