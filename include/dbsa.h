@@ -274,6 +274,60 @@ int dbsa_decode_attn(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_tensor 
                      dbsa_tensor o, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                      float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * ---- query stage with re-positioning (Sec. 2.2) --------------------------------------------
+ * The paper caches the pool's keys before the rotary transformation and, per test query,
+ * re-applies it to the concatenated selected caches with new in-order position ids.  Here the
+ * cached keys carry the rotation of the id they were ENCODED with instead (an invertible
+ * change of what is stored), and a run of keys is moved to its new ids by rotating the query
+ * row the opposite way -- rotary scores depend on id differences only.  One key tensor serves
+ * every query, which is what lets decode fetch a group once for all queries that selected it.
+ * Rotary convention: channel i pairs with channel i + D/2, angle = id * inv_freq[i].
+ */
+
+/*
+ * table[n][i] = (cos, sin)(n * inv_freq[i]) as fp32 pairs, n < n_pos, i < head_dim/2, evaluated
+ * in fp64 on the device.  inv_freq: host, [head_dim/2]; table: device, n_pos * head_dim floats,
+ * 16-byte aligned.  Enqueued on `stream`.  Errors: INVALID_ARG, HIP.
+ */
+int dbsa_rope_table(const double* inv_freq, int32_t head_dim, int32_t n_pos, float* table, void* stream);
+
+/*
+ * out[t][h] = x[t][h] rotated at id positions[t] (device int32 [n_tokens]), or at first_id + t
+ * when positions is NULL: the encoding-time rotation (pool keys: ids 0 .. N-1, Sec. 2.1; a
+ * query's own keys: their index inside the query).  x and out may be the same tensor.  ids are
+ * clamped to [0, n_pos).  head_dim a multiple of 16 up to 128.  Errors: INVALID_ARG,
+ * UNSUPPORTED, HIP.
+ */
+int dbsa_rope_apply(dbsa_tensor x, dbsa_tensor out, int32_t n_tokens, int32_t n_heads, int32_t head_dim, int32_t dtype,
+                    const int32_t* positions, int32_t first_id, const float* table, int32_t n_pos, void* stream);
+
+/*
+ * dbsa_query_attn with re-positioning.  q_self is UN-rotated; k_self holds each query's own keys
+ * rotated at their index inside the query; k_pool holds pool keys rotated at their token index.
+ * rope_table as written by dbsa_rope_table with n_pos > list_shift[e] + rows of the Q tile for
+ * every list entry (else INVALID_ARG; 2 * pool tokens + the longest query always suffices: a
+ * group that moves towards the front of the cache is reached by rotating the query FORWARD).  bf16, head_dim 128, tile sizes of the MFMA kernels (else
+ * UNSUPPORTED).  Everything else as dbsa_query_attn.
+ */
+int dbsa_query_attn_rope(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_tensor k_self, dbsa_tensor v_self,
+                         dbsa_tensor k_pool, dbsa_tensor v_pool, dbsa_tensor o, float* lse, const float* rope_table,
+                         int32_t rope_n_pos, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                         float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * dbsa_decode_attn with re-positioning.  q_step is UN-rotated; the self caches hold keys rotated
+ * at their index inside the query (the new token, index self_len[u] - 1, included).  ids beyond
+ * the table are clamped, so rope_n_pos must exceed qref_shift[ref] + self_len[u] for every
+ * reference (2 * pool tokens + the longest self cache always suffices).
+ * bf16, head_dim 128, 32 % (n_q_heads / n_kv_heads) == 0 (else UNSUPPORTED).
+ */
+int dbsa_decode_attn_rope(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_tensor k_selfcache,
+                          dbsa_tensor v_selfcache, const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool,
+                          dbsa_tensor v_pool, dbsa_tensor o, const float* rope_table, int32_t rope_n_pos,
+                          int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                          float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -37,7 +37,8 @@ DBSA_LAYOUT_HOST_ONLY = 1
 EXPORTED_SYMBOLS = (
     "dbsa_strerror", "dbsa_layout_build", "dbsa_layout_build_append", "dbsa_layout_export", "dbsa_layout_export_decode",
     "dbsa_layout_export_decode_groups", "dbsa_layout_export_order", "dbsa_layout_export_positions", "dbsa_layout_destroy", "dbsa_workspace_bytes", "dbsa_preencode_attn",
-    "dbsa_query_attn", "dbsa_decode_attn",
+    "dbsa_query_attn", "dbsa_decode_attn", "dbsa_rope_table", "dbsa_rope_apply", "dbsa_query_attn_rope",
+    "dbsa_decode_attn_rope",
 )
 
 
@@ -106,6 +107,17 @@ def lib() -> C.CDLL:
     L.dbsa_preencode_attn.argtypes = [C.c_void_p, Tensor, Tensor, Tensor, Tensor, C.c_void_p] + tail
     L.dbsa_query_attn.restype = C.c_int
     L.dbsa_query_attn.argtypes = [C.c_void_p, Tensor, Tensor, Tensor, Tensor, Tensor, Tensor, C.c_void_p] + tail
+    L.dbsa_rope_table.restype = C.c_int
+    L.dbsa_rope_table.argtypes = [C.POINTER(C.c_double), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    L.dbsa_rope_apply.restype = C.c_int
+    L.dbsa_rope_apply.argtypes = [Tensor, Tensor, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
+                                  C.c_void_p, C.c_int32, C.c_void_p]
+    L.dbsa_query_attn_rope.restype = C.c_int
+    L.dbsa_query_attn_rope.argtypes = [C.c_void_p, Tensor, Tensor, Tensor, Tensor, Tensor, Tensor, C.c_void_p,
+                                       C.c_void_p, C.c_int32] + tail
+    L.dbsa_decode_attn_rope.restype = C.c_int
+    L.dbsa_decode_attn_rope.argtypes = [C.c_void_p, Tensor, Tensor, Tensor, C.c_void_p, C.c_int64, Tensor, Tensor,
+                                        Tensor, C.c_void_p, C.c_int32] + tail
     L.dbsa_decode_attn.restype = C.c_int
     L.dbsa_decode_attn.argtypes = [C.c_void_p, Tensor, Tensor, Tensor, C.c_void_p, C.c_int64, Tensor, Tensor,
                                    Tensor] + tail
@@ -311,3 +323,63 @@ def dbsa_decode_attn(layout: Layout, q_step, k_cache, v_cache, self_len, k_pool,
                                 C.c_void_p(_stream()))
     _check(rc, "dbsa_decode_attn")
     return o
+
+
+# ---------------------------------------------------------------------------
+# query stage with re-positioning
+# ---------------------------------------------------------------------------
+
+def dbsa_rope_table(inv_freq, n_pos: int, device="cuda"):
+    """-> fp32 device tensor [n_pos, D/2, 2] of (cos, sin)(id * inv_freq[i])."""
+    import torch
+    f = np.ascontiguousarray(inv_freq, dtype=np.float64)
+    table = torch.empty((int(n_pos), len(f), 2), dtype=torch.float32, device=device)
+    rc = lib().dbsa_rope_table(f.ctypes.data_as(C.POINTER(C.c_double)), 2 * len(f), int(n_pos),
+                               C.c_void_p(table.data_ptr()), C.c_void_p(_stream()))
+    _check(rc, "dbsa_rope_table")
+    return table
+
+
+def dbsa_rope_apply(x, table, positions=None, first_id: int = 0, out=None):
+    """x [T, H, D] rotated at ``positions`` (int32 device tensor [T]) or at first_id + t."""
+    import torch
+    o = torch.empty_like(x) if out is None else out
+    rc = lib().dbsa_rope_apply(_tensor(x), _tensor(o), x.shape[0], x.shape[1], x.shape[2], _dtype_code(x),
+                               C.c_void_p(positions.data_ptr() if positions is not None else None), int(first_id),
+                               C.c_void_p(table.data_ptr()), table.shape[0], C.c_void_p(_stream()))
+    _check(rc, "dbsa_rope_apply")
+    return o
+
+
+def dbsa_query_attn_rope(layout: Layout, q_self, k_self, v_self, k_pool, v_pool, table, scale: float, out=None):
+    """Stage-2 prefill with re-positioning: q_self un-rotated, keys rotated at their encoding ids."""
+    import torch
+    o = torch.empty_like(q_self) if out is None else out
+    rc = lib().dbsa_query_attn_rope(layout.handle, _tensor(q_self), _tensor(k_self), _tensor(v_self), _tensor(k_pool),
+                                    _tensor(v_pool), _tensor(o), None, C.c_void_p(table.data_ptr()), table.shape[0],
+                                    _dtype_code(q_self), q_self.shape[1], k_pool.shape[1], q_self.shape[2],
+                                    float(scale), None, 0, C.c_void_p(_stream()))
+    _check(rc, "dbsa_query_attn_rope")
+    return o
+
+
+def dbsa_decode_attn_rope(layout: Layout, q_step, k_cache, v_cache, self_len, k_pool, v_pool, table, scale: float,
+                          out=None, workspace=None):
+    """One decode step with re-positioning (see dbsa_decode_attn for the shapes)."""
+    import torch
+    assert k_cache.dim() == 4 and k_cache.stride(3) == 1 and v_cache.stride() == k_cache.stride()
+    o = torch.empty_like(q_step) if out is None else out
+    need = layout.workspace_bytes(q_step.shape[1], q_step.shape[2])
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q_step.device)
+    kc = Tensor(k_cache.data_ptr(), k_cache.stride(1), k_cache.stride(2))
+    vc = Tensor(v_cache.data_ptr(), v_cache.stride(1), v_cache.stride(2))
+    rc = lib().dbsa_decode_attn_rope(layout.handle, _tensor(q_step), kc, vc, C.c_void_p(self_len.data_ptr()),
+                                     k_cache.stride(0), _tensor(k_pool), _tensor(v_pool), _tensor(o),
+                                     C.c_void_p(table.data_ptr()), table.shape[0], _dtype_code(q_step),
+                                     q_step.shape[1], k_pool.shape[1], q_step.shape[2], float(scale),
+                                     C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                     C.c_void_p(_stream()))
+    _check(rc, "dbsa_decode_attn_rope")
+    return o
+

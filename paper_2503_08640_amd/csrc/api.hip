@@ -169,6 +169,8 @@ void fill_lists(AttnParams& p, const dbsa_layout* L) {
   p.gm_items = L->dev.gm_items;
   p.gm_qrefs = L->dev.gm_qrefs;
   p.gm_slot_ptr = L->dev.gm_slot_ptr;
+  p.list_shift = L->dev.list_shift;
+  p.gm_qshift = L->dev.gm_qshift;
   p.n_gm_items = static_cast<int32_t>(L->gm_items.size() / 4);
   p.gm_max_queries = 1;
   for (size_t i = 3; i < L->gm_items.size(); i += 4) p.gm_max_queries = std::max(p.gm_max_queries, L->gm_items[i]);
@@ -181,7 +183,8 @@ void fill_lists(AttnParams& p, const dbsa_layout* L) {
 
 int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, dbsa_tensor k_self, dbsa_tensor v_self,
                    dbsa_tensor k_pool, dbsa_tensor v_pool, dbsa_tensor o, float* lse, int32_t dtype, int32_t hq,
-                   int32_t hkv, int32_t d, float scale, void* stream) {
+                   int32_t hkv, int32_t d, float scale, void* stream, const float* rope_table = nullptr,
+                   int32_t rope_n_pos = 0) {
   if (!L || !L->on_device || L->query_stage != want_query_stage) return DBSA_ERR_INVALID_ARG;
   if (int rc = check_shapes(dtype, hq, hkv, d, scale)) return rc;
   if (!tensor_ok(q, dtype) || !tensor_ok(k_pool, dtype) || !tensor_ok(v_pool, dtype) || !tensor_ok(o, dtype))
@@ -202,6 +205,8 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
   p.n_kv_heads = hkv;
   p.scale = scale;
   p.scale_log2e = scale * 1.4426950408889634f;
+  p.rope_table = rope_table;
+  p.rope_n_pos = rope_n_pos;
   hipError_t e;
   if (dtype == DBSA_BF16) {
     if (!mfma_tile_sizes_ok(L)) return DBSA_ERR_UNSUPPORTED;
@@ -209,14 +214,23 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
     // the pipelined kernel addresses a tile's rows with 32-bit byte offsets
     const int64_t max_stride = std::max(std::max(p.k_pool.stride_tok, p.v_pool.stride_tok),
                                         std::max(p.k_self.stride_tok, p.v_self.stride_tok));
+    // only the pipelined kernel re-positions
+    if (rope_table && !(d == 128 && max_stride < (int64_t{1} << 24))) return DBSA_ERR_UNSUPPORTED;
     e = (d == 128 && max_stride < (int64_t{1} << 24))
             ? launch_prefill_pipelined(p, static_cast<hipStream_t>(stream))
             : launch_prefill_mfma(p, d, static_cast<hipStream_t>(stream));
   } else {
+    if (rope_table) return DBSA_ERR_UNSUPPORTED;
     e = launch_prefill_plain(p, d, /*bf16_storage=*/false, static_cast<hipStream_t>(stream));
   }
   return e == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;
 }
+
+int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
+                  const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool, dbsa_tensor v_pool,
+                  dbsa_tensor o, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                  float softmax_scale, void* workspace, size_t workspace_bytes, void* stream,
+                  const float* rope_table, int32_t rope_n_pos);
 
 }  // namespace
 
@@ -362,6 +376,65 @@ int dbsa_decode_attn(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_sel
                      const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool, dbsa_tensor v_pool,
                      dbsa_tensor o, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                      float softmax_scale, void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_common(L, q_step, k_selfcache, v_selfcache, self_len, stride_query, k_pool, v_pool, o, dtype,
+                       n_q_heads, n_kv_heads, head_dim, softmax_scale, workspace, workspace_bytes, stream, nullptr, 0);
+}
+
+int dbsa_rope_table(const double* inv_freq, int32_t head_dim, int32_t n_pos, float* table, void* stream) {
+  if (!inv_freq || !table || n_pos < 1 || head_dim < 2 || head_dim > 128 || head_dim % 2 != 0)
+    return DBSA_ERR_INVALID_ARG;
+  return launch_rope_table(inv_freq, head_dim, n_pos, table, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? DBSA_OK
+             : DBSA_ERR_HIP;
+}
+
+int dbsa_rope_apply(dbsa_tensor x, dbsa_tensor out, int32_t n_tokens, int32_t n_heads, int32_t head_dim, int32_t dtype,
+                    const int32_t* positions, int32_t first_id, const float* table, int32_t n_pos, void* stream) {
+  if (dtype != DBSA_BF16 && dtype != DBSA_F32) return DBSA_ERR_UNSUPPORTED;
+  if (head_dim % 16 != 0 || head_dim < 16 || head_dim > 128) return DBSA_ERR_UNSUPPORTED;
+  if (!x.ptr || !out.ptr || !table || n_tokens < 0 || n_heads < 1 || n_pos < 1 || x.stride_tok <= 0 ||
+      x.stride_head <= 0 || out.stride_tok <= 0 || out.stride_head <= 0)
+    return DBSA_ERR_INVALID_ARG;
+  return launch_rope_apply(view(x), view(out), n_tokens, n_heads, head_dim, dtype == DBSA_BF16, positions, first_id,
+                           table, n_pos, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? DBSA_OK
+             : DBSA_ERR_HIP;
+}
+
+int dbsa_query_attn_rope(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_tensor k_self, dbsa_tensor v_self,
+                         dbsa_tensor k_pool, dbsa_tensor v_pool, dbsa_tensor o, float* lse, const float* rope_table,
+                         int32_t rope_n_pos, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                         float softmax_scale, void* /*workspace*/, size_t /*workspace_bytes*/, void* stream) {
+  if (!rope_table || rope_n_pos < 1 || !layout || !layout->query_stage) return DBSA_ERR_INVALID_ARG;
+  // the largest id any row will look up must be inside the table
+  int64_t need = 0;
+  for (int64_t t = 0; t < layout->n_qtiles(); ++t)
+    for (int64_t e = layout->list_ptr[t]; e < layout->list_ptr[t + 1]; ++e)
+      need = std::max<int64_t>(need, static_cast<int64_t>(layout->list_shift[e]) + layout->qtile_tab[4 * t + 1]);
+  if (need > rope_n_pos) return DBSA_ERR_INVALID_ARG;
+  return prefill_common(layout, true, q_self, k_self, v_self, k_pool, v_pool, o, lse, dtype, n_q_heads, n_kv_heads,
+                        head_dim, softmax_scale, stream, rope_table, rope_n_pos);
+}
+
+int dbsa_decode_attn_rope(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
+                          const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool, dbsa_tensor v_pool,
+                          dbsa_tensor o, const float* rope_table, int32_t rope_n_pos, int32_t dtype,
+                          int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+  if (!rope_table || rope_n_pos < 1) return DBSA_ERR_INVALID_ARG;
+  return decode_common(L, q_step, k_selfcache, v_selfcache, self_len, stride_query, k_pool, v_pool, o, dtype,
+                       n_q_heads, n_kv_heads, head_dim, softmax_scale, workspace, workspace_bytes, stream, rope_table,
+                       rope_n_pos);
+}
+
+}  // extern "C"
+
+namespace {
+int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
+                  const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool, dbsa_tensor v_pool,
+                  dbsa_tensor o, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                  float softmax_scale, void* workspace, size_t workspace_bytes, void* stream,
+                  const float* rope_table, int32_t rope_n_pos) {
   if (!L || !L->on_device || !L->query_stage || !self_len) return DBSA_ERR_INVALID_ARG;
   if (int rc = check_shapes(dtype, n_q_heads, n_kv_heads, head_dim, softmax_scale)) return rc;
   if (!tensor_ok(q_step, dtype) || !tensor_ok(k_selfcache, dtype) || !tensor_ok(v_selfcache, dtype) ||
@@ -383,6 +456,8 @@ int dbsa_decode_attn(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_sel
   p.n_kv_heads = n_kv_heads;
   p.scale = softmax_scale;
   p.scale_log2e = softmax_scale * 1.4426950408889634f;
+  p.rope_table = rope_table;
+  p.rope_n_pos = rope_n_pos;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (dtype == DBSA_BF16) {
@@ -398,13 +473,14 @@ int dbsa_decode_attn(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_sel
       // every KV run is walked once for all the queries that selected it
       e = launch_decode_group(p, s);
     } else {
+      if (rope_table) return DBSA_ERR_UNSUPPORTED;  // only the group-major kernel re-positions
       e = launch_decode_mfma(p, head_dim, s);
       if (e == hipSuccess) e = launch_decode_merge(p, head_dim, /*out_bf16=*/true, s);
     }
   } else {
+    if (rope_table) return DBSA_ERR_UNSUPPORTED;
     e = launch_decode_plain(p, head_dim, /*bf16_storage=*/false, s);
   }
   return e == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;
 }
-
-}  // extern "C"
+}  // namespace

@@ -79,6 +79,9 @@ __device__ inline void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
+// ROPE: the query row is un-rotated and is rotated here at the id that stands for the new
+// in-order position of the item's keys (Sec. 2.2), see AttnParams::gm_qshift.
+template <bool ROPE>
 __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   lds_byte* lds = (lds_byte*)smem;
@@ -196,15 +199,23 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
     // ---- this lane's column: query and head ----
     const int q_local = pass * qpw + l32 / r;  // index into the item's query list
     const bool col_valid = q_local < n_q;
-    int u = self_u, slot;
+    int u = self_u, slot, rot_id = 0;
     if (self_item) {
       slot = static_cast<int>(p.gm_slot_ptr[self_u + 1]) - 1;
     } else {
       const int qi = qref_begin + min(q_local, n_q - 1);
       u = p.gm_qrefs[2 * qi];
       slot = p.gm_qrefs[2 * qi + 1];
+      if (ROPE) rot_id = p.gm_qshift[qi];
     }
     const int head = hk * r + l32 % r;
+    // table row of this column: 16 floats (cos, sin of 8 channel pairs) per (chunk c < 4, half)
+    const float* rot = nullptr;
+    if (ROPE) {
+      rot_id = min(max(rot_id + p.self_len[u] - 1, 0), p.rope_n_pos - 1);
+      rot = p.rope_table + static_cast<int64_t>(rot_id) * kD + 16 * half;
+      asm volatile("" : "+v"(rot));
+    }
     // (the row address is formed here, before the tile loads go out: it waits for the query
     // reference just loaded, and that wait must not include the tile loads)
     const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
@@ -219,7 +230,31 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
     issue_v(0);
     if (1 < n_half) issue_k(1);
     bf16x8 qf[kD / 16];
-    {
+    if (ROPE) {
+      // channel d < 64 of chunk c pairs with channel d + 64 of chunk c + 4, both held by this lane
+#pragma unroll
+      for (int c = 0; c < kD / 32; ++c) {
+        const bf16x8 lo = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
+        const bf16x8 hi = *reinterpret_cast<const bf16x8*>(qp + 16 * (c + kD / 32));
+        floatx4 cs[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) cs[j] = *reinterpret_cast<const floatx4*>(rot + 32 * c + 4 * j);
+        union {
+          bf16x8 v;
+          bf16x2 p2[4];
+        } a, b;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float x0 = static_cast<float>(lo[2 * e]), y0 = static_cast<float>(hi[2 * e]);
+          const float x1 = static_cast<float>(lo[2 * e + 1]), y1 = static_cast<float>(hi[2 * e + 1]);
+          const float c0 = cs[e][0] * c2, s0 = cs[e][1] * c2, c1 = cs[e][2] * c2, s1 = cs[e][3] * c2;
+          a.p2[e] = __builtin_convertvector(floatx2{x0 * c0 - y0 * s0, x1 * c1 - y1 * s1}, bf16x2);
+          b.p2[e] = __builtin_convertvector(floatx2{y0 * c0 + x0 * s0, y1 * c1 + x1 * s1}, bf16x2);
+        }
+        qf[c] = a.v;
+        qf[c + kD / 32] = b.v;
+      }
+    } else {
 #pragma unroll
       for (int c = 0; c < kD / 16; ++c) {
         const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
@@ -389,14 +424,20 @@ __global__ __launch_bounds__(kD) void decode_group_merge_kernel(AttnParams p) {
 hipError_t launch_decode_group(const AttnParams& p, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_kernel<false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_kernel<true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int qpw = 32 / (p.n_q_heads / p.n_kv_heads);
   dim3 grid(p.n_gm_items + p.n_queries, p.n_kv_heads, (p.gm_max_queries + qpw - 1) / qpw), block(64);
-  decode_group_kernel<<<grid, block, kLdsBytes, stream>>>(p);
+  if (p.rope_table)
+    decode_group_kernel<true><<<grid, block, kLdsBytes, stream>>>(p);
+  else
+    decode_group_kernel<false><<<grid, block, kLdsBytes, stream>>>(p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   decode_group_merge_kernel<<<dim3(p.n_queries * p.n_q_heads), dim3(kD), 0, stream>>>(p);

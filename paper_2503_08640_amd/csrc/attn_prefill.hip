@@ -43,6 +43,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kD = 128;
@@ -126,7 +127,11 @@ struct TileRef {
 // call's own K/V (query prefill) besides pool tiles (pre-encode lists name pool tiles only).
 // Row block g = wave covers query head (blockIdx.x * heads_per_block + g / spb) and tokens
 // q_start + (g % spb)*32 .. +31, spb = block_m / 32.
-template <int NW, int SL, bool SELF>
+// ROPE (query prefill only): Q is un-rotated; the keys carry the rotation of the id they were
+// encoded with, and every list entry names the id at which its rows must be rotated instead
+// (AttnParams::list_shift: the new in-order positions of Sec. 2.2 as a rotation of the query).
+// Entries of one segment share that id, so the Q fragments are rebuilt at segment changes only.
+template <int NW, int SL, bool SELF, bool ROPE = false>
 __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   constexpr int kBlocksPerWave = 16 / NW;  // 1-KiB load blocks of one operand per wave (NW <= 8 < 16)
@@ -252,7 +257,43 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   // ---- Q^T fragments, pre-multiplied by scale*log2(e) ----
   const float c2 = p.scale_log2e;
   bf16x8 qf[kD / 16];
-  {
+  const const_words lshift = (const_words)(reinterpret_cast<uintptr_t>(p.list_shift + (ROPE ? e0 : 0)));
+  // rebuilds qf rotated at id shift + (row inside the tile); channel d < 64 of chunk c pairs with
+  // channel d + 64 of chunk c + 4, both held by this lane
+  auto load_q_rotated = [&](int shift) DBSA_INLINE {
+    const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(row_tok) * p.q.stride_tok +
+                       static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
+    const int id = min(max(shift + row_local, 0), p.rope_n_pos - 1);
+    const float* rot = p.rope_table + static_cast<int64_t>(id) * kD + 16 * half;
+#pragma unroll
+    for (int c = 0; c < kD / 32; ++c) {
+      const bf16x8 lo = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
+      const bf16x8 hi = *reinterpret_cast<const bf16x8*>(qp + 16 * (c + kD / 32));
+      floatx4 cs[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) cs[j] = *reinterpret_cast<const floatx4*>(rot + 32 * c + 4 * j);
+      union {
+        bf16x8 v;
+        bf16x2 p2[4];
+      } a, b;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float x0 = static_cast<float>(lo[2 * e]), y0 = static_cast<float>(hi[2 * e]);
+        const float x1 = static_cast<float>(lo[2 * e + 1]), y1 = static_cast<float>(hi[2 * e + 1]);
+        const float c0 = cs[e][0] * c2, s0 = cs[e][1] * c2, c1 = cs[e][2] * c2, s1 = cs[e][3] * c2;
+        a.p2[e] = __builtin_convertvector(floatx2{x0 * c0 - y0 * s0, x1 * c1 - y1 * s1}, bf16x2);
+        b.p2[e] = __builtin_convertvector(floatx2{y0 * c0 + x0 * s0, y1 * c1 + x1 * s1}, bf16x2);
+      }
+      qf[c] = a.v;
+      qf[c + kD / 32] = b.v;
+    }
+  };
+  int cur_shift = 0, nxt_shift = 0;  // rotation ids of the entry whose scores are computed next / after that
+  if constexpr (ROPE) {
+    cur_shift = lshift[0];
+    nxt_shift = n_tiles > 1 ? lshift[1] : cur_shift;
+    load_q_rotated(cur_shift);
+  } else {
     const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(row_tok) * p.q.stride_tok +
                        static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
 #pragma unroll
@@ -376,6 +417,13 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
         }
     }
 
+    if constexpr (ROPE) {
+      // this step computes the scores of entry it+1: rebuild Q when that entry starts a new segment
+      if (__builtin_expect(nxt_shift != cur_shift, 0)) {
+        cur_shift = nxt_shift;
+        load_q_rotated(cur_shift);
+      }
+    }
     const bool has_next = it + 1 < n_tiles;
     const TileRef nxt = refs[0];
     int in_w0 = 0, in_w1 = 0;  // list entry it+3+SL (zero past the end), needed by the next step's K load
@@ -400,6 +448,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
         if (it + 3 + SL < n_tiles) {
           in_w0 = ent[2 * (it + 3 + SL)];
           in_w1 = ent[2 * (it + 3 + SL) + 1];
+        }
+        if constexpr (ROPE) {
+          if (it + 2 < n_tiles) nxt_shift = lshift[it + 2];
         }
       }
       if constexpr (t > 0) {
@@ -497,23 +548,24 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   }
 }
 
-template <int NW, int SL, bool SELF>
+template <int NW, int SL, bool SELF, bool ROPE = false>
 hipError_t launch_cfg(const AttnParams& p, hipStream_t stream) {
   constexpr int lds_bytes = (3 + 2 * SL) * kTileBytes;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_kernel<NW, SL, SELF>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_kernel<NW, SL, SELF, ROPE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   dim3 grid(p.n_q_heads / p.heads_per_block, p.n_qtiles), block(NW * 64);
-  attn_prefill_kernel<NW, SL, SELF><<<grid, block, lds_bytes, stream>>>(p);
+  attn_prefill_kernel<NW, SL, SELF, ROPE><<<grid, block, lds_bytes, stream>>>(p);
   return hipGetLastError();
 }
 
 template <int NW, int SL>
 hipError_t launch_stage(const AttnParams& p, hipStream_t stream) {
+  if (p.rope_table) return p.query_stage ? launch_cfg<NW, SL, true, true>(p, stream) : hipErrorInvalidValue;
   return p.query_stage ? launch_cfg<NW, SL, true>(p, stream) : launch_cfg<NW, SL, false>(p, stream);
 }
 

@@ -46,6 +46,11 @@ struct AttnParams {
   int32_t n_q_heads, n_kv_heads, block_m, block_n;
   int32_t heads_per_block;    // query heads handled by one workgroup (divides Hq/Hkv)
   int32_t query_stage;        // prefill-shaped calls: 1 = query prefill (lists may name self tiles), 0 = pre-encode
+  // re-positioning (null table: inputs carry their final positions already)
+  const float* rope_table;    // [rope_n_pos][D/2][2] fp32 (cos, sin) of id * inv_freq
+  int32_t rope_n_pos;
+  const int32_t* list_shift;  // [n_ent]: rotation id of row i of a Q tile for entry e = list_shift[e] + i
+  const int32_t* gm_qshift;   // [n_qrefs]: rotation id of a decode row = gm_qshift[ref] + self_len - 1
   float scale;                // softmax scale
   float scale_log2e;          // scale * log2(e)
 };
@@ -58,6 +63,12 @@ hipError_t launch_prefill_pipelined(const AttnParams& p, hipStream_t stream);
 hipError_t launch_decode_group(const AttnParams& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const AttnParams& p, int head_dim, hipStream_t stream);
 hipError_t launch_decode_merge(const AttnParams& p, int head_dim, bool out_bf16, hipStream_t stream);
+
+// rotary tables and the encoding-time rotation (rope.hip)
+hipError_t launch_rope_table(const double* inv_freq, int head_dim, int n_pos, float* table, hipStream_t stream);
+hipError_t launch_rope_apply(const TensorView& x, const TensorView& out, int n_tokens, int n_heads, int head_dim,
+                             bool bf16, const int32_t* positions, int first_id, const float* table, int n_pos,
+                             hipStream_t stream);
 
 // plain fp32-arithmetic kernels for fp32 or bf16 storage (attn_plain.hip)
 hipError_t launch_prefill_plain(const AttnParams& p, int head_dim, bool bf16_storage, hipStream_t stream);
