@@ -311,7 +311,7 @@ def main() -> int:
             "useful_tflop_per_step": flops_step / 1e12,
         },
         "roofline": {
-            "kernel": "attn_prefill_kernel<4,1,false> (pre-encode launch; the <4,1,true> instance serves the query prefill)",
+            "kernel": "attn_prefill_kernel<4,1,false,false> (pre-encode launch; the <4,1,true,false> instance serves the query prefill)",
             "bound": "mfma", "achieved": pre_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": pre_tflops / PEAK_BF16_TFLOPS, "traffic": load_traffic("attn_prefill_kernel_preencode"),
             "algorithmic": {"useful_tflop_per_launch": flops_pre / 1e12, "launch_ms": pre_ms},
