@@ -20,7 +20,8 @@
 //   * operand fragments travel through one ring of registers, read from LDS kRing - 1
 //     matrix instructions ahead of their use, across the K -> V -> next-K boundaries.
 //   * Q is pre-multiplied by scale*log2(e) when its fragments are loaded, and the score
-//     accumulators start at minus the running row maximum, so that a probability is one
+//     accumulators start at minus the running row maximum (the C operand of a score block's
+//     first matrix instruction is a register block holding it), so that a probability is one
 //     v_exp_f32 of the MFMA result; the row sum is accumulated in fp32 with plain adds
 //     (v_dot2c_f32_bf16 with a vector of ones would be fewer instructions, but measured it
 //     stalls ~15 cycles behind every MFMA in flight: dot instructions share the matrix pipe).
@@ -370,12 +371,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        s_a[kb][i] -= m_run;
-        s_b[kb][i] = -m_run;
-      }
+      for (int i = 0; i < 16; ++i) s_a[kb][i] -= m_run;
     mx_cur = 0.f;
   }
+  // minus the running maximum in every element: the C operand of the first matrix instruction of
+  // each score block, so that accumulators need no per-step initialisation
+  floatx16 neg_m;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) neg_m[i] = -m_run;
 
   // the fragment reads now walk K stage 1 (tile 1) and V stage 0 (tile 0); the first kDist
   // fragments of K(1) enter the ring (stale data if the list has one entry: never used)
@@ -387,7 +390,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   static_for<kDist>([&](auto T) DBSA_INLINE { ring[decltype(T)::value % kRing] = ld_k(T); });
 
   // One tile step.  On entry s_cur holds the (masked) scores of tile `it` minus m_run, mx_cur
-  // their row maximum, s_nxt minus m_run in every element, and the ring the first kDist
+  // their row maximum, neg_m minus m_run in every element, and the ring the first kDist
   // fragments of K(it+1).  K(it+1) is visible since the previous barrier; V(it) becomes
   // visible with this one.  The last tile computes an s_nxt nobody uses (stale LDS contents)
   // so that every tile runs the same straight-line code.
@@ -411,10 +414,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          s_cur[kb][i] -= delta;
-          s_nxt[kb][i] -= delta;
-        }
+        for (int i = 0; i < 16; ++i) s_cur[kb][i] -= delta;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) neg_m[i] -= delta;
     }
 
     if constexpr (ROPE) {
@@ -434,7 +436,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
     __builtin_amdgcn_sched_barrier(0);
     static_for<16>([&](auto T) DBSA_INLINE {
       constexpr int t = decltype(T)::value;
-      s_nxt[t / 8] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[t % kRing], qf[t % 8], s_nxt[t / 8], 0, 0, 0);
+      s_nxt[t / 8] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[t % kRing], qf[t % 8], t % 8 == 0 ? neg_m : s_nxt[t / 8],
+                                                             0, 0, 0);
       if constexpr (t + kDist < 16)
         ring[(t + kDist) % kRing] = ld_k(std::integral_constant<int, (t + kDist) % 16>{});
       else
@@ -479,7 +482,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
 
     // -- O^T += V(it)^T P^T (matrix pipe) || row maximum of tile it+1, next accumulator init (vector ALU) --
     float mt = s_nxt[0][0];
-    const float neg_m = -m_run;
     __builtin_amdgcn_sched_barrier(0);
     static_for<16>([&](auto T) DBSA_INLINE {
       constexpr int t = decltype(T)::value;
@@ -495,10 +497,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
       else
         ring[(16 + t + kDist) % kRing] = ld_k(std::integral_constant<int, (t + kDist) % 16>{});
       mt = fmaxf(mt, fmaxf(s_nxt[t / 8][2 * (t % 8)], s_nxt[t / 8][2 * (t % 8) + 1]));
-      // s_cur is dead (its exponentials are done): it becomes the score accumulator of the next step
-      s_cur[t / 8][2 * (t % 8)] = neg_m;
-      s_cur[t / 8][2 * (t % 8) + 1] = neg_m;
-      asm volatile("" : "+v"(mt), "+v"(s_cur[t / 8][2 * (t % 8)]), "+v"(s_cur[t / 8][2 * (t % 8) + 1]));
+      asm volatile("" : "+v"(mt));
       __builtin_amdgcn_sched_barrier(0);
     });
     mx_cur = half_swap_max(mt);
