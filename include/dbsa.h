@@ -82,6 +82,14 @@ typedef struct {
   const int32_t* sel_ptr;   /* [B+1] CSR row pointers into sel_idx; [0] == 0; non-decreasing              */
   const int32_t* sel_idx;   /* selected group indices; the caller's order is kept in the lists            */
   int32_t n_split;          /* decode: KV splits per (query, KV head); 0 = let the library choose          */
+  const int32_t* page_start;/* NULL: k_pool / v_pool hold the pool contiguously, token j at row j.  Else
+                               [n_groups+1]: the row, in the k_pool / v_pool tensors handed to the query
+                               and decode calls, of the first token of the sink (index 0) and of group g
+                               (index g+1), each segment contiguous from there -- groups live in pages of
+                               an arena and may be offloaded or re-encoded independently (Sec. 4, storage
+                               cost).  -1 = not resident: selecting such a group is BAD_SELECTION; resident
+                               pages that overlap are BAD_BOUNDS.  The lists then name arena rows; position
+                               data (dbsa_layout_export_positions) keeps referring to pool token ids.     */
 } dbsa_select_desc;
 
 typedef struct dbsa_layout dbsa_layout; /* opaque; owns host and device copies of its index lists */

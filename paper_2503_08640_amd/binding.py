@@ -55,7 +55,7 @@ class PoolDesc(C.Structure):
 
 class SelectDesc(C.Structure):
     _fields_ = [("n_queries", C.c_int32), ("cu_qlens", C.POINTER(C.c_int32)), ("sel_ptr", C.POINTER(C.c_int32)),
-                ("sel_idx", C.POINTER(C.c_int32)), ("n_split", C.c_int32)]
+                ("sel_idx", C.POINTER(C.c_int32)), ("n_split", C.c_int32), ("page_start", C.POINTER(C.c_int32))]
 
 
 class Tensor(C.Structure):
@@ -226,7 +226,7 @@ class Layout:
 
 def dbsa_layout_build(sink_len: int, demo_offsets, group_demo_offsets, prev_window: int = 0, *, cu_qlens=None,
                       sel_ptr=None, sel_idx=None, n_split: int = 0, block_m: int = 64, block_n: int = 64,
-                      host_only: bool = False, stream: int = 0) -> Layout:
+                      host_only: bool = False, stream: int = 0, page_start=None) -> Layout:
     do, gdo = _i32(demo_offsets), _i32(group_demo_offsets)
     pool = PoolDesc(int(sink_len), len(do) - 1, _p32(do), len(gdo) - 1, _p32(gdo), int(prev_window))
     sel_ref = None
@@ -235,7 +235,9 @@ def dbsa_layout_build(sink_len: int, demo_offsets, group_demo_offsets, prev_wind
         cu, sp = _i32(cu_qlens), _i32(sel_ptr)
         si = _i32(sel_idx if sel_idx is not None else [])
         keep += [cu, sp, si]
-        sel = SelectDesc(len(cu) - 1, _p32(cu), _p32(sp), _p32(si), int(n_split))
+        ps = _i32(page_start) if page_start is not None else None
+        keep.append(ps)
+        sel = SelectDesc(len(cu) - 1, _p32(cu), _p32(sp), _p32(si), int(n_split), _p32(ps))
         sel_ref = C.byref(sel)
     out = C.c_void_p()
     rc = lib().dbsa_layout_build(C.byref(pool), sel_ref, int(block_m), int(block_n),

@@ -10,7 +10,9 @@
 #include "layout.hpp"
 
 #include <algorithm>
+#include <climits>
 #include <numeric>
+#include <utility>
 
 namespace {
 
@@ -84,6 +86,11 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
     L->list_ptr.push_back(static_cast<int64_t>(L->list_ent.size() / 2));
   };
 
+  // where the segments sit in the tensors the query-stage calls will be given (the pool itself
+  // unless the caller keeps groups in arena pages)
+  Seg sink_at = sink;
+  std::vector<Seg> group_at = group;
+
   if (!sel) {
     // ---- stage 1 ----
     // An appended group sees the sink, its window of preceding groups and itself; nothing
@@ -122,6 +129,28 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
         seen[g] = u;
       }
 
+    if (sel->page_start) {
+      const int32_t* ps = sel->page_start;
+      std::vector<std::pair<int64_t, int64_t>> resident;
+      if (S > 0) {
+        if (ps[0] < 0) return DBSA_ERR_BAD_BOUNDS;  // the anchor is part of every query's cache
+        sink_at = Seg{ps[0], ps[0] + S};
+        resident.emplace_back(ps[0], static_cast<int64_t>(ps[0]) + S);
+      }
+      for (int32_t g = 0; g < G; ++g) {
+        const int32_t len = group[g].end - group[g].begin;
+        if (ps[g + 1] < 0) continue;
+        if (static_cast<int64_t>(ps[g + 1]) + len > INT32_MAX) return DBSA_ERR_BAD_BOUNDS;
+        group_at[g] = Seg{ps[g + 1], ps[g + 1] + len};
+        resident.emplace_back(ps[g + 1], static_cast<int64_t>(ps[g + 1]) + len);
+      }
+      std::sort(resident.begin(), resident.end());
+      for (size_t i = 1; i < resident.size(); ++i)
+        if (resident[i].first < resident[i - 1].second) return DBSA_ERR_BAD_BOUNDS;
+      for (int32_t e = 0; e < sel->sel_ptr[B]; ++e)
+        if (ps[sel->sel_idx[e] + 1] < 0) return DBSA_ERR_BAD_SELECTION;
+    }
+
     L->n_queries = B;
     L->n_query_tokens = sel->cu_qlens[B];
     L->dec_ptr.assign(1, 0);
@@ -130,9 +159,9 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
     for (int32_t u = 0; u < B; ++u) {
       // pool part, shared by all Q tiles of the query and by decode
       const size_t dec_begin = L->dec_ent.size();
-      push_whole_segment(L->dec_ent, sink, block_n, DBSA_TILE_FULL);
+      push_whole_segment(L->dec_ent, sink_at, block_n, DBSA_TILE_FULL);
       for (int32_t e = sel->sel_ptr[u]; e < sel->sel_ptr[u + 1]; ++e)
-        push_whole_segment(L->dec_ent, group[sel->sel_idx[e]], block_n, DBSA_TILE_FULL);
+        push_whole_segment(L->dec_ent, group_at[sel->sel_idx[e]], block_n, DBSA_TILE_FULL);
       L->dec_ptr.push_back(static_cast<int64_t>(L->dec_ent.size() / 2));
       shortest = std::min(shortest, (L->dec_ent.size() - dec_begin) / 2);
       // new ids (Sec. 2.2): the sink keeps 0 .. S-1, the k-th selected group follows the (k-1)-th,
@@ -194,10 +223,10 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
       for (int32_t e = sel->sel_ptr[u]; e < sel->sel_ptr[u + 1]; ++e) users[sel->sel_idx[e] + 1].push_back(u);
     for (auto& v : users) std::sort(v.begin(), v.end());
     L->gm_seg_ptr.assign(1, 0);
-    push_whole_segment(L->gm_seg_ent, sink, block_n, DBSA_TILE_FULL);
+    push_whole_segment(L->gm_seg_ent, sink_at, block_n, DBSA_TILE_FULL);
     L->gm_seg_ptr.push_back(static_cast<int64_t>(L->gm_seg_ent.size() / 2));
     for (int32_t g = 0; g < G; ++g) {
-      push_whole_segment(L->gm_seg_ent, group[g], block_n, DBSA_TILE_FULL);
+      push_whole_segment(L->gm_seg_ent, group_at[g], block_n, DBSA_TILE_FULL);
       L->gm_seg_ptr.push_back(static_cast<int64_t>(L->gm_seg_ent.size() / 2));
     }
     int64_t max_tiles = 1, tile_batches = 0;

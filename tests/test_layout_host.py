@@ -85,6 +85,79 @@ def test_repositioning_shifts_match_the_new_position_ids(seed):
     assert np.all(got[0] >= 0) and np.all(got[1] >= 0)
 
 
+def _arena_pages(rng, pool, needed):
+    """Scatter the sink and the groups in ``needed`` over an arena with gaps, in random order;
+    other groups are resident or not at random.  -> page_start [G+1]."""
+    gb = pool.group_token_bounds()
+    lens = [pool.sink_len] + [int(gb[g + 1] - gb[g]) for g in range(pool.n_groups)]
+    resident = [s for s in range(pool.n_groups + 1) if s == 0 or (s - 1) in needed or rng.random() < 0.5]
+    page_start = np.full(pool.n_groups + 1, -1, dtype=np.int32)
+    at = int(rng.integers(0, 5))
+    for s in rng.permutation(resident):
+        page_start[s] = at
+        at += lens[s] + int(rng.integers(0, 7))
+    return page_start
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_paged_layout_names_arena_rows_and_keeps_positions(seed):
+    """Sec. 4 (storage cost): groups may be offloaded or re-encoded; the query stage only needs
+    the selected ones, wherever they sit."""
+    rng = np.random.default_rng(400 + seed)
+    pool = rand_pool(rng, sink_len=int(rng.integers(0, 7)), n_groups=int(rng.integers(1, 7)))
+    nq = int(rng.integers(1, 5))
+    cu = np.concatenate([[0], np.cumsum(rng.integers(1, 12, size=nq))]).astype(np.int32)
+    sels = [rng.permutation(pool.n_groups)[:int(rng.integers(0, pool.n_groups + 1))] for _ in range(nq)]
+    sel_ptr = np.concatenate([[0], np.cumsum([len(s) for s in sels])]).astype(np.int32)
+    sel_idx = np.concatenate(sels).astype(np.int32) if sel_ptr[-1] else np.zeros(0, np.int32)
+    bm, bn = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+    page_start = _arena_pages(rng, pool, set(int(g) for g in sel_idx))
+    kw = dict(cu_qlens=cu, sel_ptr=sel_ptr, sel_idx=sel_idx, n_split=2, block_m=bm, block_n=bn, host_only=True)
+    plain = B.dbsa_layout_build(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, **kw)
+    paged = B.dbsa_layout_build(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, page_start=page_start, **kw)
+    gb = pool.group_token_bounds()
+    seg_lo = np.concatenate([[0], gb[:-1]]).astype(np.int64)        # logical first token of sink, groups
+
+    def to_arena(ent, self_kinds=True):
+        out = ent.copy()
+        for i in range(len(ent)):
+            if self_kinds and (int(ent[i, 1]) >> 16) >= lo.KIND_SELF_FULL:
+                continue                                             # a query's own tokens are not paged
+            j = int(ent[i, 0])
+            s = 0 if j < pool.sink_len else 1 + int(np.searchsorted(gb, j, side="right") - 1)
+            out[i, 0] = page_start[s] + (j - seg_lo[s])
+        return out
+
+    tab, ptr, ent = plain.export()
+    assert_same_lists(paged.export(), (tab, ptr, to_arena(ent)))
+    dp, de, sp = plain.export_decode(nq)
+    dp2, de2, sp2 = paged.export_decode(nq)
+    assert np.array_equal(dp, dp2) and np.array_equal(sp, sp2) and np.array_equal(de2, to_arena(de, False))
+    g1, g2 = plain.export_decode_groups(pool.n_groups, nq), paged.export_decode_groups(pool.n_groups, nq)
+    for key in ("seg_ptr", "items", "qrefs", "slot_ptr"):
+        assert np.array_equal(g1[key], g2[key]), key
+    used = np.unique(np.concatenate([np.arange(int(a), int(a) + int(n)) for a, n in g1["items"][:, :2]] + [[]]))
+    used = used.astype(np.int64)
+    assert np.array_equal(g2["seg_ent"][used], to_arena(g1["seg_ent"][used], False))
+    for a, b in zip(plain.export_positions(nq), paged.export_positions(nq)):
+        assert np.array_equal(a, b)                                  # positions are about token ids, not rows
+    if sel_ptr[-1]:
+        gone = page_start.copy()
+        gone[int(sel_idx[0]) + 1] = -1
+        with pytest.raises(B.DbsaError) as ei:
+            B.dbsa_layout_build(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, page_start=gone, **kw)
+        assert ei.value.code == B.DBSA_ERR_BAD_SELECTION
+    res = np.nonzero(page_start >= 0)[0]
+    if len(res) >= 2:
+        clash = page_start.copy()
+        clash[res[1]] = clash[res[0]]
+        lens = [pool.sink_len] + [int(gb[g + 1] - gb[g]) for g in range(pool.n_groups)]
+        if lens[res[0]] > 0 and lens[res[1]] > 0:
+            with pytest.raises(B.DbsaError) as ei:
+                B.dbsa_layout_build(pool.sink_len, pool.demo_offsets, pool.group_demo_offsets, page_start=clash, **kw)
+            assert ei.value.code == B.DBSA_ERR_BAD_BOUNDS
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_append_layout_is_the_tail_of_the_full_layout(seed):
     """Sec. 2.1: an added group attends the anchor, its window and itself, and nothing encoded
