@@ -84,7 +84,7 @@ def extra_setting(torch, B, pc, qc, workload: str, bm_pre: int, bm_query: int, i
     lay_app = B.dbsa_layout_build_append(p.sink_len, p.demo_offsets, p.group_demo_offsets, w, p.n_groups - 1,
                                          block_m=bm_pre, block_n=64)
     calls = (lambda: B.dbsa_preencode_attn(lay, q, k, v, pc.scale, out=o),
-             lambda: B.dbsa_query_attn(layq, qs, ks, vs, k, v, pc.scale, out=oq),
+             lambda: B.dbsa_query_attn(layq, qs, ks, vs, k, v, pc.scale, out=oq, workspace=ws),
              lambda: B.dbsa_decode_attn(layq, dq[0], kc, vc, self_len, k, v, pc.scale, out=od, workspace=ws),
              lambda: B.dbsa_preencode_attn(lay_app, q, k, v, pc.scale, out=o))
     ms = []
@@ -135,7 +135,7 @@ def repositioned_stage(torch, B, pc, qc, k, v, qs, ks, vs, oq, dq, kc, vc, self_
     torch.cuda.synchronize()
     rotate_pool_ms = e0.elapsed_time(e1)
     ws = torch.empty(max(16, layq.workspace_bytes(pc.n_q_heads, d)), dtype=torch.uint8, device="cuda")
-    calls = (lambda: B.dbsa_query_attn_rope(layq, qs, ks, vs, k, v, tab, pc.scale, out=oq),
+    calls = (lambda: B.dbsa_query_attn_rope(layq, qs, ks, vs, k, v, tab, pc.scale, out=oq, workspace=ws),
              lambda: B.dbsa_decode_attn_rope(layq, dq[0], kc, vc, self_len, k, v, tab, pc.scale, out=od, workspace=ws))
     ms = []
     for fn, n in zip(calls, (iters, 5 * iters)):
@@ -257,7 +257,7 @@ def main() -> int:
         B.dbsa_preencode_attn(lay, q, k, v, pc.scale, out=o)                                        # a2
         if ev: ev[1].record()
         if ev: ev[2].record()
-        B.dbsa_query_attn(layq, qs, ks, vs, k, v, pc.scale, out=oq)                                 # a4
+        B.dbsa_query_attn(layq, qs, ks, vs, k, v, pc.scale, out=oq, workspace=ws_holder["t"])     # a4
         if ev: ev[3].record()
         for s in range(qc.n_decode):                                                                # a5 + a6
             B.dbsa_decode_attn(layq, dq[s], kc, vc, self_lens[s], k, v, pc.scale, out=od, workspace=ws_holder["t"])

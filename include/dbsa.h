@@ -212,10 +212,13 @@ int dbsa_layout_export_order(const dbsa_layout* layout, const int32_t** order, i
 void dbsa_layout_destroy(dbsa_layout* layout);
 
 /*
- * Bytes of device workspace dbsa_decode_attn needs for this layout: one partial softmax
- * state of (head_dim + 4) floats per query head and slot, for the larger of the two
- * decode schedules (B * n_split slots, or slot_ptr[B] slots).  The pre-encode and query
- * calls need none.  Returns 0 for a pre-encode layout.
+ * Bytes of device workspace the query-stage calls use for this layout: one partial softmax
+ * state of (head_dim + 4) floats per query head and slot.  dbsa_decode_attn needs the larger
+ * of its two schedules (B * n_split slots, or slot_ptr[B] slots).  dbsa_query_attn may use up
+ * to 4 slots per query token when the layout has so few Q tiles that the launch would leave
+ * compute units idle; it then cuts every KV list into runs and merges their partial states
+ * (without a workspace it runs every list in one pass: same result up to summation order).
+ * The pre-encode call needs none.  Returns 0 for a pre-encode layout.
  */
 size_t dbsa_workspace_bytes(const dbsa_layout* layout, int32_t n_q_heads, int32_t head_dim);
 
@@ -255,6 +258,8 @@ int dbsa_preencode_attn(const dbsa_layout* layout, dbsa_tensor q, dbsa_tensor k,
  *   k_self, v_self         : [sum T, n_kv_heads, D].
  *   k_pool, v_pool         : [N, n_kv_heads, D].
  *   lse                    : optional device float [n_q_heads][sum T].
+ *   workspace              : optional (NULL / 0): device memory, 16-byte aligned, of
+ *                            dbsa_workspace_bytes(); see there.  A smaller one is ignored.
  * Same dtype / tile-size rules and errors as dbsa_preencode_attn.
  */
 int dbsa_query_attn(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_tensor k_self, dbsa_tensor v_self,

@@ -295,14 +295,27 @@ def dbsa_preencode_attn(layout: Layout, q, k, v, scale: float, out=None, lse=Non
     return o
 
 
-def dbsa_query_attn(layout: Layout, q_self, k_self, v_self, k_pool, v_pool, scale: float, out=None, lse=None):
-    """Stage-2 prefill of the packed queries; returns O [sum T, Hq, D]."""
+def _workspace(layout: Layout, q, workspace):
+    """(pointer, bytes) of the caller's workspace, or of a fresh one of dbsa_workspace_bytes()."""
+    import torch
+    if workspace is None:
+        workspace = torch.empty(max(layout.workspace_bytes(q.shape[1], q.shape[2]), 16), dtype=torch.uint8,
+                                device=q.device)
+    return workspace, C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def dbsa_query_attn(layout: Layout, q_self, k_self, v_self, k_pool, v_pool, scale: float, out=None, lse=None,
+                    workspace=None):
+    """Stage-2 prefill of the packed queries; returns O [sum T, Hq, D].  ``workspace`` (uint8 device
+    tensor of dbsa_workspace_bytes(), allocated here when omitted; False = none) lets launches with few
+    Q tiles split their KV lists."""
     import torch
     o = torch.empty_like(q_self) if out is None else out
+    ws, ws_ptr, ws_bytes = (None, None, 0) if workspace is False else _workspace(layout, q_self, workspace)
     rc = lib().dbsa_query_attn(layout.handle, _tensor(q_self), _tensor(k_self), _tensor(v_self), _tensor(k_pool),
                                _tensor(v_pool), _tensor(o), C.c_void_p(lse.data_ptr() if lse is not None else None),
                                _dtype_code(q_self), q_self.shape[1], k_pool.shape[1], q_self.shape[2], float(scale),
-                               None, 0, C.c_void_p(_stream()))
+                               ws_ptr, ws_bytes, C.c_void_p(_stream()))
     _check(rc, "dbsa_query_attn")
     return o
 
@@ -353,14 +366,16 @@ def dbsa_rope_apply(x, table, positions=None, first_id: int = 0, out=None):
     return o
 
 
-def dbsa_query_attn_rope(layout: Layout, q_self, k_self, v_self, k_pool, v_pool, table, scale: float, out=None):
+def dbsa_query_attn_rope(layout: Layout, q_self, k_self, v_self, k_pool, v_pool, table, scale: float, out=None,
+                         workspace=None):
     """Stage-2 prefill with re-positioning: q_self un-rotated, keys rotated at their encoding ids."""
     import torch
     o = torch.empty_like(q_self) if out is None else out
+    ws, ws_ptr, ws_bytes = (None, None, 0) if workspace is False else _workspace(layout, q_self, workspace)
     rc = lib().dbsa_query_attn_rope(layout.handle, _tensor(q_self), _tensor(k_self), _tensor(v_self), _tensor(k_pool),
                                     _tensor(v_pool), _tensor(o), None, C.c_void_p(table.data_ptr()), table.shape[0],
                                     _dtype_code(q_self), q_self.shape[1], k_pool.shape[1], q_self.shape[2],
-                                    float(scale), None, 0, C.c_void_p(_stream()))
+                                    float(scale), ws_ptr, ws_bytes, C.c_void_p(_stream()))
     _check(rc, "dbsa_query_attn_rope")
     return o
 

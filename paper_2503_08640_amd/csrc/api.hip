@@ -153,6 +153,12 @@ int pick_heads_per_block(int r, int block_m) {
   return best;
 }
 
+// split query prefill: workgroups the chip holds at two per compute unit, most runs per list,
+// fewest tiles per run
+constexpr int64_t kWorkgroupSlots = 512;
+constexpr int64_t kMaxQuerySplit = 4;
+constexpr int64_t kMinRun = 16;
+
 bool mfma_tile_sizes_ok(const dbsa_layout* L) {
   const int bm = L->block_m;
   return L->block_n == 64 && (bm == 32 || bm == 64 || bm == 128 || bm == 256);
@@ -184,7 +190,7 @@ void fill_lists(AttnParams& p, const dbsa_layout* L) {
 int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, dbsa_tensor k_self, dbsa_tensor v_self,
                    dbsa_tensor k_pool, dbsa_tensor v_pool, dbsa_tensor o, float* lse, int32_t dtype, int32_t hq,
                    int32_t hkv, int32_t d, float scale, void* stream, const float* rope_table = nullptr,
-                   int32_t rope_n_pos = 0) {
+                   int32_t rope_n_pos = 0, void* workspace = nullptr, size_t workspace_bytes = 0) {
   if (!L || !L->on_device || L->query_stage != want_query_stage) return DBSA_ERR_INVALID_ARG;
   if (int rc = check_shapes(dtype, hq, hkv, d, scale)) return rc;
   if (!tensor_ok(q, dtype) || !tensor_ok(k_pool, dtype) || !tensor_ok(v_pool, dtype) || !tensor_ok(o, dtype))
@@ -216,6 +222,25 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
                                         std::max(p.k_self.stride_tok, p.v_self.stride_tok));
     // only the pipelined kernel re-positions
     if (rope_table && !(d == 128 && max_stride < (int64_t{1} << 24))) return DBSA_ERR_UNSUPPORTED;
+    // A query prefill with fewer workgroups than the chip holds (two per compute unit) cuts every
+    // list into runs of at least kMinRun tiles, up to kMaxQuerySplit of them, if the caller gave the workspace.
+    p.n_rows = L->n_query_tokens;
+    p.q_split = 1;
+    if (want_query_stage && d == 128 && workspace && reinterpret_cast<uintptr_t>(workspace) % 16 == 0) {
+      const int64_t wgs = L->n_qtiles() * (hq / p.heads_per_block);
+      int64_t shortest = INT64_MAX;
+      for (int64_t t = 0; t < L->n_qtiles(); ++t) shortest = std::min(shortest, L->list_ptr[t + 1] - L->list_ptr[t]);
+      // eight-wave workgroups (112 KiB of LDS) sit alone on a compute unit, smaller ones in pairs
+      const int64_t slots = p.heads_per_block * (L->block_m / 32) == 8 ? kWorkgroupSlots / 2 : kWorkgroupSlots;
+      int64_t split = wgs > 0 ? std::min<int64_t>(kMaxQuerySplit, (slots + wgs - 1) / wgs) : 1;
+      split = std::min(split, shortest / kMinRun);
+      const size_t need = static_cast<size_t>(L->n_query_tokens) * hq * static_cast<size_t>(std::max<int64_t>(split, 1)) *
+                          (d + kPartialPad) * sizeof(float);
+      if (wgs < slots && split > 1 && workspace_bytes >= need) {
+        p.q_split = static_cast<int32_t>(split);
+        p.partial = static_cast<float*>(workspace);
+      }
+    }
     e = (d == 128 && max_stride < (int64_t{1} << 24))
             ? launch_prefill_pipelined(p, static_cast<hipStream_t>(stream))
             : launch_prefill_mfma(p, d, static_cast<hipStream_t>(stream));
@@ -352,8 +377,11 @@ void dbsa_layout_destroy(dbsa_layout* L) {
 
 size_t dbsa_workspace_bytes(const dbsa_layout* L, int32_t n_q_heads, int32_t head_dim) {
   if (!L || !L->query_stage || n_q_heads <= 0 || head_dim <= 0) return 0;
-  const size_t slots = std::max<size_t>(static_cast<size_t>(L->n_queries) * L->n_split,
-                                        L->gm_slot_ptr.empty() ? 0 : static_cast<size_t>(L->gm_slot_ptr.back()));
+  size_t slots = std::max<size_t>(static_cast<size_t>(L->n_queries) * L->n_split,
+                                  L->gm_slot_ptr.empty() ? 0 : static_cast<size_t>(L->gm_slot_ptr.back()));
+  // a split query prefill keeps up to kMaxQuerySplit partial states per row; it is only used when
+  // the launch has fewer workgroups than the chip holds, which bounds the number of Q tiles
+  if (L->n_qtiles() < kWorkgroupSlots) slots = std::max<size_t>(slots, static_cast<size_t>(L->n_query_tokens) * kMaxQuerySplit);
   return slots * n_q_heads * (head_dim + kPartialPad) * sizeof(float);
 }
 
@@ -366,10 +394,10 @@ int dbsa_preencode_attn(const dbsa_layout* layout, dbsa_tensor q, dbsa_tensor k,
 
 int dbsa_query_attn(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_tensor k_self, dbsa_tensor v_self,
                     dbsa_tensor k_pool, dbsa_tensor v_pool, dbsa_tensor o, float* lse, int32_t dtype,
-                    int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale, void* /*workspace*/,
-                    size_t /*workspace_bytes*/, void* stream) {
+                    int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale, void* workspace,
+                    size_t workspace_bytes, void* stream) {
   return prefill_common(layout, true, q_self, k_self, v_self, k_pool, v_pool, o, lse, dtype, n_q_heads, n_kv_heads,
-                        head_dim, softmax_scale, stream);
+                        head_dim, softmax_scale, stream, nullptr, 0, workspace, workspace_bytes);
 }
 
 int dbsa_decode_attn(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
@@ -404,7 +432,7 @@ int dbsa_rope_apply(dbsa_tensor x, dbsa_tensor out, int32_t n_tokens, int32_t n_
 int dbsa_query_attn_rope(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_tensor k_self, dbsa_tensor v_self,
                          dbsa_tensor k_pool, dbsa_tensor v_pool, dbsa_tensor o, float* lse, const float* rope_table,
                          int32_t rope_n_pos, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
-                         float softmax_scale, void* /*workspace*/, size_t /*workspace_bytes*/, void* stream) {
+                         float softmax_scale, void* workspace, size_t workspace_bytes, void* stream) {
   if (!rope_table || rope_n_pos < 1 || !layout || !layout->query_stage) return DBSA_ERR_INVALID_ARG;
   // the largest id any row will look up must be inside the table
   int64_t need = 0;
@@ -413,7 +441,7 @@ int dbsa_query_attn_rope(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_ten
       need = std::max<int64_t>(need, static_cast<int64_t>(layout->list_shift[e]) + layout->qtile_tab[4 * t + 1]);
   if (need > rope_n_pos) return DBSA_ERR_INVALID_ARG;
   return prefill_common(layout, true, q_self, k_self, v_self, k_pool, v_pool, o, lse, dtype, n_q_heads, n_kv_heads,
-                        head_dim, softmax_scale, stream, rope_table, rope_n_pos);
+                        head_dim, softmax_scale, stream, rope_table, rope_n_pos, workspace, workspace_bytes);
 }
 
 int dbsa_decode_attn_rope(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,

@@ -160,9 +160,18 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   const int row_tok = q_start + min(row_local, q_len - 1);
   const int q_pos = q_start + row_local;
   const int hk = (blockIdx.x * p.heads_per_block) / r;
-  const int e0 = __builtin_amdgcn_readfirstlane(static_cast<int>(p.list_ptr[tile]));
-  const int n_tiles = __builtin_amdgcn_readfirstlane(static_cast<int>(p.list_ptr[tile + 1])) - e0;
-  if (n_tiles == 0) return;  // cannot happen for a well-formed layout: every row sees itself
+  // gridDim.z > 1: the list is cut into gridDim.z runs of entries, one workgroup each, whose
+  // un-normalised results a second kernel merges (launches with fewer Q tiles than the chip has
+  // room for workgroups)
+  int e0 = __builtin_amdgcn_readfirstlane(static_cast<int>(p.list_ptr[tile]));
+  int n_tiles = __builtin_amdgcn_readfirstlane(static_cast<int>(p.list_ptr[tile + 1])) - e0;
+  if (gridDim.z > 1) {
+    const int lo = static_cast<int>(static_cast<int64_t>(n_tiles) * blockIdx.z / gridDim.z);
+    const int hi = static_cast<int>(static_cast<int64_t>(n_tiles) * (blockIdx.z + 1) / gridDim.z);
+    e0 += lo;
+    n_tiles = hi - lo;
+  }
+  if (n_tiles == 0) return;  // cannot happen: every row sees itself, and the host only cuts lists into non-empty runs
   const const_words ent = (const_words)(reinterpret_cast<uintptr_t>(p.list_ent + 2 * static_cast<int64_t>(e0)));
 
   // byte addresses of this KV head's first token
@@ -527,6 +536,21 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   {
     const float l_tot = half_swap_sum(l_run);
     if (!row_valid) return;
+    if (gridDim.z > 1) {
+      float* part = p.partial + ((static_cast<int64_t>(row_tok) * p.n_q_heads + head) * gridDim.z + blockIdx.z) *
+                                    (kD + kPartialPad);
+#pragma unroll
+      for (int ob = 0; ob < kD / 32; ++ob)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<floatx4*>(part + 32 * ob + 8 * g + 4 * half) =
+              floatx4{o[ob][4 * g], o[ob][4 * g + 1], o[ob][4 * g + 2], o[ob][4 * g + 3]};
+      if (half == 0) {
+        part[kD] = m_run;
+        part[kD + 1] = l_tot;
+      }
+      return;
+    }
     const float inv = 1.f / l_tot;
     __bf16* op = static_cast<__bf16*>(const_cast<void*>(p.o.ptr)) + static_cast<int64_t>(row_tok) * p.o.stride_tok +
                  static_cast<int64_t>(head) * p.o.stride_head + 4 * half;
@@ -547,6 +571,26 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   }
 }
 
+// Merge of the gridDim.z partial states of one (row, head): thread d owns channel d.
+// o = sum_z 2^(m_z - m*) acc_z / sum_z 2^(m_z - m*) l_z, statistics in the log2 domain.
+__global__ __launch_bounds__(kD) void prefill_merge_kernel(AttnParams p, int n_rows, int n_split) {
+  const int row = blockIdx.x / p.n_q_heads, head = blockIdx.x % p.n_q_heads, d = threadIdx.x;
+  if (row >= n_rows) return;
+  const float* part = p.partial + (static_cast<int64_t>(row) * p.n_q_heads + head) * n_split * (kD + kPartialPad);
+  float m_star = -1.0e30f;
+  for (int z = 0; z < n_split; ++z) m_star = fmaxf(m_star, part[z * (kD + kPartialPad) + kD]);
+  float l = 0.f, acc = 0.f;
+  for (int z = 0; z < n_split; ++z) {
+    const float w = __builtin_amdgcn_exp2f(part[z * (kD + kPartialPad) + kD] - m_star);
+    l = fmaf(part[z * (kD + kPartialPad) + kD + 1], w, l);
+    acc = fmaf(part[z * (kD + kPartialPad) + d], w, acc);
+  }
+  __bf16* o = static_cast<__bf16*>(const_cast<void*>(p.o.ptr));
+  o[static_cast<int64_t>(row) * p.o.stride_tok + static_cast<int64_t>(head) * p.o.stride_head + d] =
+      static_cast<__bf16>(acc / l);
+  if (p.lse && d == 0) p.lse[static_cast<int64_t>(head) * p.lse_stride + row] = (m_star + __log2f(l)) * 0.69314718055994531f;
+}
+
 template <int NW, int SL, bool SELF, bool ROPE = false>
 hipError_t launch_cfg(const AttnParams& p, hipStream_t stream) {
   constexpr int lds_bytes = (3 + 2 * SL) * kTileBytes;
@@ -557,8 +601,12 @@ hipError_t launch_cfg(const AttnParams& p, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid(p.n_q_heads / p.heads_per_block, p.n_qtiles), block(NW * 64);
+  const int n_split = p.q_split > 1 ? p.q_split : 1;
+  dim3 grid(p.n_q_heads / p.heads_per_block, p.n_qtiles, n_split), block(NW * 64);
   attn_prefill_kernel<NW, SL, SELF, ROPE><<<grid, block, lds_bytes, stream>>>(p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || n_split == 1) return e;
+  prefill_merge_kernel<<<dim3(p.n_rows * p.n_q_heads), dim3(kD), 0, stream>>>(p, p.n_rows, n_split);
   return hipGetLastError();
 }
 

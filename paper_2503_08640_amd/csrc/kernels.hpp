@@ -41,7 +41,10 @@ struct AttnParams {
   const int32_t* self_len;    // decode only, device [B]
   float* lse;                 // optional [Hq][n_rows]
   int64_t lse_stride;         // rows per head in lse
-  float* partial;             // decode: [slot][Hq][D + kPartialPad]; per-query splits use slot = u*n_split + s
+  float* partial;             // decode: [slot][Hq][D + kPartialPad]; per-query splits use slot = u*n_split + s;
+                              // split prefill: [row][Hq][q_split][D + kPartialPad]
+  int32_t q_split;            // prefill: runs each Q tile's list is cut into (1 = no split, no merge pass)
+  int32_t n_rows;             // prefill: rows of q / o
   // shapes
   int32_t n_q_heads, n_kv_heads, block_m, block_n;
   int32_t heads_per_block;    // query heads handled by one workgroup (divides Hq/Hkv)

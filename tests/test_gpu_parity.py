@@ -198,6 +198,26 @@ def test_query_and_decode_bf16_head_ratios(hq, hkv, block_m):
     _run_decode_steps(pc, qc, lay, kp, vp, range(2), f"Hq={hq} Hkv={hkv}")
 
 
+def test_query_prefill_with_split_lists_agrees_with_the_single_pass():
+    """Few Q tiles: with a workspace every list is cut into runs whose partial states are merged;
+    without one the same call runs each list in one pass.  Both must match the oracle, and each
+    other's log-sum-exp."""
+    pc = small_pool_case("splitpool", 2070, hq=8, hkv=2, pool_tokens=9000, groups=4, lens=(32, 200), sigma=0.5)
+    qc = synth.make_query_case("qs", 2071, pc, n_queries=3, q_len=[64, 50, 7], selections=[[0, 1, 2, 3], [2], [3, 1]])
+    ref = _oracle_query(pc, qc)
+    for bm in (32, 64):
+        lay, kp, vp = _query_setup(pc, qc, bm, 0)
+        qs, ks, vs = to_dev(qc.q), to_dev(qc.k), to_dev(qc.v)
+        lse_a = torch.zeros(pc.n_q_heads, qs.shape[0], device="cuda")
+        lse_b = torch.zeros_like(lse_a)
+        one = B.dbsa_query_attn(lay, qs, ks, vs, kp, vp, pc.scale, lse=lse_a, workspace=False)
+        cut = B.dbsa_query_attn(lay, qs, ks, vs, kp, vp, pc.scale, lse=lse_b)
+        assert_close(to_f64(one), ref, f"single pass bm={bm}")
+        assert_close(to_f64(cut), ref, f"split lists bm={bm}")
+        assert not torch.equal(one, cut), "the workspace did not switch the split path on"
+        assert (lse_a - lse_b).abs().max().item() <= 1e-3
+
+
 def test_all_groups_selected_matches_dense_causal_oracle_and_order_is_irrelevant():
     pc = small_pool_case("full", 2030, hq=4, hkv=1, pool_tokens=3000, groups=4, lens=(32, 128))
     outs = []
