@@ -305,7 +305,9 @@ def test_empty_selection_and_same_group_in_two_queries_are_valid():
 
 def test_host_only_layout_cannot_run_attention_and_workspace_size():
     lay = _build(sel_kw=dict(cu_qlens=[0, 4, 9], sel_ptr=[0, 0, 1], sel_idx=[1], n_split=3))
-    assert lay.workspace_bytes(32, 128) == max(2 * 3, int(lay.export_decode_groups(2, 2)['slot_ptr'][-1])) * 32 * 132 * 4
+    # decode: one slot per (query, split) or per schedule slot; a split query prefill: up to 4 per query token
+    slots = max(2 * 3, int(lay.export_decode_groups(2, 2)['slot_ptr'][-1]), 9 * 4)
+    assert lay.workspace_bytes(32, 128) == slots * 32 * 132 * 4
     pre = _build()
     assert pre.workspace_bytes(32, 128) == 0
     t = B.Tensor(16, 8, 8)
