@@ -178,8 +178,7 @@ void fill_lists(AttnParams& p, const dbsa_layout* L) {
   p.list_shift = L->dev.list_shift;
   p.gm_qshift = L->dev.gm_qshift;
   p.n_gm_items = static_cast<int32_t>(L->gm_items.size() / 4);
-  p.gm_max_queries = 1;
-  for (size_t i = 3; i < L->gm_items.size(); i += 4) p.gm_max_queries = std::max(p.gm_max_queries, L->gm_items[i]);
+  p.gm_max_queries = L->gm_max_queries;
   p.n_qtiles = static_cast<int32_t>(L->n_qtiles());
   p.n_split = L->n_split;
   p.n_queries = L->n_queries;
@@ -228,12 +227,10 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
     p.q_split = 1;
     if (want_query_stage && d == 128 && workspace && reinterpret_cast<uintptr_t>(workspace) % 16 == 0) {
       const int64_t wgs = L->n_qtiles() * (hq / p.heads_per_block);
-      int64_t shortest = INT64_MAX;
-      for (int64_t t = 0; t < L->n_qtiles(); ++t) shortest = std::min(shortest, L->list_ptr[t + 1] - L->list_ptr[t]);
       // eight-wave workgroups (112 KiB of LDS) sit alone on a compute unit, smaller ones in pairs
       const int64_t slots = p.heads_per_block * (L->block_m / 32) == 8 ? kWorkgroupSlots / 2 : kWorkgroupSlots;
       int64_t split = wgs > 0 ? std::min<int64_t>(kMaxQuerySplit, (slots + wgs - 1) / wgs) : 1;
-      split = std::min(split, shortest / kMinRun);
+      split = std::min(split, L->shortest_list / kMinRun);
       const size_t need = static_cast<size_t>(L->n_query_tokens) * hq * static_cast<size_t>(std::max<int64_t>(split, 1)) *
                           (d + kPartialPad) * sizeof(float);
       if (wgs < slots && split > 1 && workspace_bytes >= need) {
@@ -435,11 +432,7 @@ int dbsa_query_attn_rope(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_ten
                          float softmax_scale, void* workspace, size_t workspace_bytes, void* stream) {
   if (!rope_table || rope_n_pos < 1 || !layout || !layout->query_stage) return DBSA_ERR_INVALID_ARG;
   // the largest id any row will look up must be inside the table
-  int64_t need = 0;
-  for (int64_t t = 0; t < layout->n_qtiles(); ++t)
-    for (int64_t e = layout->list_ptr[t]; e < layout->list_ptr[t + 1]; ++e)
-      need = std::max<int64_t>(need, static_cast<int64_t>(layout->list_shift[e]) + layout->qtile_tab[4 * t + 1]);
-  if (need > rope_n_pos) return DBSA_ERR_INVALID_ARG;
+  if (layout->max_rotation_id >= rope_n_pos) return DBSA_ERR_INVALID_ARG;
   return prefill_common(layout, true, q_self, k_self, v_self, k_pool, v_pool, o, lse, dtype, n_q_heads, n_kv_heads,
                         head_dim, softmax_scale, stream, rope_table, rope_n_pos, workspace, workspace_bytes);
 }

@@ -284,6 +284,17 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
     }
   }
 
+  for (size_t i = 3; i < L->gm_items.size(); i += 4) L->gm_max_queries = std::max(L->gm_max_queries, L->gm_items[i]);
+  L->shortest_list = INT64_MAX;
+  for (int64_t t = 0; t < L->n_qtiles(); ++t) {
+    L->shortest_list = std::min(L->shortest_list, L->list_ptr[t + 1] - L->list_ptr[t]);
+    if (!L->list_shift.empty())
+      for (int64_t e = L->list_ptr[t]; e < L->list_ptr[t + 1]; ++e)
+        L->max_rotation_id = std::max<int64_t>(L->max_rotation_id,
+                                               static_cast<int64_t>(L->list_shift[e]) + L->qtile_tab[4 * t + 1] - 1);
+  }
+  if (L->n_qtiles() == 0) L->shortest_list = 0;
+
   // launch order: owner by owner (a group at pre-encoding, a query at the query stage), the
   // longest list of an owner first.  Q tiles of one owner walk the same KV, so keeping them
   // adjacent keeps that KV in the L2 of the XCD that runs them.

@@ -57,6 +57,10 @@ struct dbsa_layout {
   std::vector<int32_t> list_shift;  // [n_ent]
   std::vector<int32_t> gm_qshift;   // [n_qrefs]
   std::vector<int32_t> cache_len;   // [B]: |D'| of query u = sink + its selected groups
+  // figures the attention calls need on every launch, taken once at build time
+  int32_t gm_max_queries = 1;       // most queries any schedule item serves
+  int64_t shortest_list = 0;        // fewest entries any Q tile lists
+  int64_t max_rotation_id = -1;     // largest id a prefill row looks up: max(list_shift[e] + rows of the tile) - 1
 
   dbsa_device_lists dev;
 

@@ -341,3 +341,27 @@ def test_group_major_schedule_batches_users_and_defaults_to_a_bounded_chunk():
     own = got["slot_ptr"][1:] - 1
     assert np.array_equal(np.sort(np.concatenate([slots, own])), np.arange(got["slot_ptr"][-1]))
     assert lay.workspace_bytes(4, 64) == int(got["slot_ptr"][-1]) * 4 * 68 * 4
+
+
+def test_rotary_calls_reject_bad_arguments_before_touching_the_device():
+    import ctypes as C
+    L = B.lib()
+    f = (C.c_double * 64)(*([1.0] * 64))
+    assert L.dbsa_rope_table(None, 128, 16, C.c_void_p(16), None) == B.DBSA_ERR_INVALID_ARG
+    assert L.dbsa_rope_table(f, 128, 16, None, None) == B.DBSA_ERR_INVALID_ARG
+    assert L.dbsa_rope_table(f, 128, 0, C.c_void_p(16), None) == B.DBSA_ERR_INVALID_ARG
+    assert L.dbsa_rope_table(f, 130, 16, C.c_void_p(16), None) == B.DBSA_ERR_INVALID_ARG     # more pairs than the table argument holds
+    t = B.Tensor(16, 256, 128)
+    assert L.dbsa_rope_apply(t, t, 4, 2, 128, 7, None, 0, C.c_void_p(16), 8, None) == B.DBSA_ERR_UNSUPPORTED   # dtype
+    assert L.dbsa_rope_apply(t, t, 4, 2, 24, B.DBSA_BF16, None, 0, C.c_void_p(16), 8, None) == B.DBSA_ERR_UNSUPPORTED
+    assert L.dbsa_rope_apply(t, t, 4, 2, 128, B.DBSA_BF16, None, 0, None, 8, None) == B.DBSA_ERR_INVALID_ARG
+    assert L.dbsa_rope_apply(B.Tensor(None, 256, 128), t, 4, 2, 128, B.DBSA_BF16, None, 0, C.c_void_p(16), 8, None) == \
+        B.DBSA_ERR_INVALID_ARG
+    # a host-only layout has no device lists: the re-positioning calls refuse it like the plain ones
+    lay = _build(sel_kw=dict(cu_qlens=[0, 4, 9], sel_ptr=[0, 0, 1], sel_idx=[1]))
+    tail = (B.DBSA_BF16, 4, 2, 128, C.c_float(0.1), None, 0, None)
+    assert L.dbsa_query_attn_rope(lay.handle, t, t, t, t, t, t, None, C.c_void_p(16), 100000, *tail) == B.DBSA_ERR_INVALID_ARG
+    assert L.dbsa_query_attn_rope(lay.handle, t, t, t, t, t, t, None, None, 100000, *tail) == B.DBSA_ERR_INVALID_ARG
+    assert L.dbsa_decode_attn_rope(lay.handle, t, t, t, C.c_void_p(16), 1024, t, t, t, None, 0, *tail) == \
+        B.DBSA_ERR_INVALID_ARG
+
