@@ -237,7 +237,7 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
       tile_batches += t * ((static_cast<int64_t>(users[s].size()) + kItemQueries - 1) / kItemQueries);
     }
     int64_t chunk = sel->n_split > 0 ? (max_tiles + sel->n_split - 1) / sel->n_split
-                                     : std::min<int64_t>(16, (tile_batches + 191) / 192);
+                                     : std::min<int64_t>(16, (tile_batches + 143) / 144);
     chunk = std::max<int64_t>(1, chunk);
     L->gm_chunk_tiles = static_cast<int32_t>(chunk);
     // displacement of segment s for user u, as in list_shift but without a tile offset
