@@ -64,13 +64,13 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   const size_t b_tab = L->qtile_tab.size() * sizeof(int32_t), b_ptr = L->list_ptr.size() * sizeof(int64_t),
                b_ent = L->list_ent.size() * sizeof(int32_t), b_ord = L->order.size() * sizeof(int32_t),
                b_dec = L->dec_ent.size() * sizeof(int32_t), b_spl = L->split_ptr.size() * sizeof(int64_t),
-               b_gse = L->gm_seg_ent.size() * sizeof(int32_t), b_git = L->gm_items.size() * sizeof(int32_t),
-               b_gqr = L->gm_qrefs.size() * sizeof(int32_t), b_gsp = L->gm_slot_ptr.size() * sizeof(int64_t),
-               b_lsh = L->list_shift.size() * sizeof(int32_t), b_gqs = L->gm_qshift.size() * sizeof(int32_t);
+               b_gsp = L->gm_slot_ptr.size() * sizeof(int64_t),
+               b_lsh = L->list_shift.size() * sizeof(int32_t), b_gir = L->gm_item_run.size() * sizeof(int32_t),
+               b_grp = L->gm_ref_pad.size() * sizeof(int32_t);
   const size_t o_tab = 0, o_ptr = o_tab + pad(b_tab), o_ent = o_ptr + pad(b_ptr), o_ord = o_ent + pad(b_ent),
-               o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), o_gse = o_spl + pad(b_spl),
-               o_git = o_gse + pad(b_gse), o_gqr = o_git + pad(b_git), o_gsp = o_gqr + pad(b_gqr),
-               o_lsh = o_gsp + pad(b_gsp), o_gqs = o_lsh + pad(b_lsh), total = o_gqs + pad(b_gqs) + 256;
+               o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), o_gsp = o_spl + pad(b_spl),
+               o_lsh = o_gsp + pad(b_gsp), o_gir = o_lsh + pad(b_lsh), o_grp = o_gir + pad(b_gir),
+               total = o_grp + pad(b_grp) + 256;
   ListBlock blk{};
   hipError_t e = acquire_block(total, &blk);
   if (e != hipSuccess) return e;
@@ -84,12 +84,10 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   put(o_ord, L->order.data(), b_ord);
   put(o_dec, L->dec_ent.data(), b_dec);
   put(o_spl, L->split_ptr.data(), b_spl);
-  put(o_gse, L->gm_seg_ent.data(), b_gse);
-  put(o_git, L->gm_items.data(), b_git);
-  put(o_gqr, L->gm_qrefs.data(), b_gqr);
   put(o_gsp, L->gm_slot_ptr.data(), b_gsp);
   put(o_lsh, L->list_shift.data(), b_lsh);
-  put(o_gqs, L->gm_qshift.data(), b_gqs);
+  put(o_gir, L->gm_item_run.data(), b_gir);
+  put(o_grp, L->gm_ref_pad.data(), b_grp);
   e = hipMemcpyAsync(blk.dev, blk.pinned, total, hipMemcpyHostToDevice, stream);
   if (e == hipSuccess) e = hipStreamSynchronize(stream);  // the staging twin may be reused after return
   if (e != hipSuccess) {
@@ -107,12 +105,10 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   L->dev.order = reinterpret_cast<int32_t*>(b + o_ord);
   L->dev.dec_ent = reinterpret_cast<int32_t*>(b + o_dec);
   L->dev.split_ptr = reinterpret_cast<int64_t*>(b + o_spl);
-  L->dev.gm_seg_ent = reinterpret_cast<int32_t*>(b + o_gse);
-  L->dev.gm_items = reinterpret_cast<int32_t*>(b + o_git);
-  L->dev.gm_qrefs = reinterpret_cast<int32_t*>(b + o_gqr);
   L->dev.gm_slot_ptr = reinterpret_cast<int64_t*>(b + o_gsp);
   L->dev.list_shift = reinterpret_cast<int32_t*>(b + o_lsh);
-  L->dev.gm_qshift = reinterpret_cast<int32_t*>(b + o_gqs);
+  L->dev.gm_item_run = reinterpret_cast<int32_t*>(b + o_gir);
+  L->dev.gm_ref_pad = reinterpret_cast<int32_t*>(b + o_grp);
   return hipSuccess;
 }
 
@@ -171,12 +167,10 @@ void fill_lists(AttnParams& p, const dbsa_layout* L) {
   p.order = L->dev.order;
   p.dec_ent = L->dev.dec_ent;
   p.split_ptr = L->dev.split_ptr;
-  p.gm_seg_ent = L->dev.gm_seg_ent;
-  p.gm_items = L->dev.gm_items;
-  p.gm_qrefs = L->dev.gm_qrefs;
   p.gm_slot_ptr = L->dev.gm_slot_ptr;
   p.list_shift = L->dev.list_shift;
-  p.gm_qshift = L->dev.gm_qshift;
+  p.gm_item_run = L->dev.gm_item_run;
+  p.gm_ref_pad = L->dev.gm_ref_pad;
   p.n_gm_items = static_cast<int32_t>(L->gm_items.size() / 4);
   p.gm_max_queries = L->gm_max_queries;
   p.n_qtiles = static_cast<int32_t>(L->n_qtiles());

@@ -80,7 +80,7 @@ __device__ inline void wait_vmcnt() {
 }
 
 // ROPE: the query row is un-rotated and is rotated here at the id that stands for the new
-// in-order position of the item's keys (Sec. 2.2), see AttnParams::gm_qshift.
+// in-order position of the item's keys (Sec. 2.2), see AttnParams::gm_ref_pad.
 template <bool ROPE>
 __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -95,18 +95,16 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   const bool self_item = item >= p.n_gm_items;
   // (the schedule lists are read-only while a kernel runs: scalar loads through the constant path)
   typedef const __attribute__((address_space(4))) int32_t* const_words;
-  const const_words items = (const_words)(reinterpret_cast<uintptr_t>(p.gm_items));
-  const const_words seg_ent = (const_words)(reinterpret_cast<uintptr_t>(p.gm_seg_ent));
-  // the run is a stretch of consecutive tokens: first_key .. first_key + n_keys
-  int n_q = 1, qref_begin = 0, n_half = 0, first_key = 0, n_keys = 0, self_u = 0;
+  const const_words runs = (const_words)(reinterpret_cast<uintptr_t>(p.gm_item_run));
+  // the run is a stretch of consecutive key rows: first_key .. first_key + n_keys.  Everything
+  // the first loads need (the run, the query references) is one load away from the item index:
+  // all workgroups of a step start together, and every further dependent load at their start is
+  // a microsecond or two in which no tile data moves.
+  int n_q = 1, n_half = 0, first_key = 0, n_keys = 0, self_u = 0;
   if (!self_item) {
-    const int ent_begin = items[4 * item + 0];
-    const int ent_count = items[4 * item + 1];
-    qref_begin = items[4 * item + 2];
-    n_q = items[4 * item + 3];
-    // tiles of one segment follow each other without gaps and all but the last are full
-    first_key = seg_ent[2 * ent_begin];
-    n_keys = 64 * (ent_count - 1) + (seg_ent[2 * (ent_begin + ent_count - 1) + 1] & 0xFFFF);
+    first_key = runs[4 * item + 0];
+    n_keys = runs[4 * item + 1];
+    n_q = runs[4 * item + 2];
   } else {
     self_u = item - p.n_gm_items;
     n_keys = __builtin_amdgcn_readfirstlane(p.self_len[self_u]);
@@ -197,16 +195,18 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   if (pass >= n_pass) return;
   {
     // ---- this lane's column: query and head ----
-    const int q_local = pass * qpw + l32 / r;  // index into the item's query list
+    const int q_local = pass * qpw + l32 / r;  // index into the item's query list (< 32)
     const bool col_valid = q_local < n_q;
     int u = self_u, slot, rot_id = 0;
     if (self_item) {
       slot = static_cast<int>(p.gm_slot_ptr[self_u + 1]) - 1;
     } else {
-      const int qi = qref_begin + min(q_local, n_q - 1);
-      u = p.gm_qrefs[2 * qi];
-      slot = p.gm_qrefs[2 * qi + 1];
-      if (ROPE) rot_id = p.gm_qshift[qi];
+      // (query, slot, shift, 0); references past the item's last one repeat it
+      typedef int intx4 __attribute__((ext_vector_type(4)));
+      const intx4 ref = *reinterpret_cast<const intx4*>(p.gm_ref_pad + (static_cast<int64_t>(item) * 32 + q_local) * 4);
+      u = ref[0];
+      slot = ref[1];
+      if (ROPE) rot_id = ref[2];
     }
     const int head = hk * r + l32 % r;
     // table row of this column: 16 floats (cos, sin of 8 channel pairs) per (chunk c < 4, half)

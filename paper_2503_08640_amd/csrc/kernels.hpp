@@ -26,9 +26,6 @@ struct AttnParams {
   const int32_t* order;      // [n_qtiles]
   const int32_t* dec_ent;    // [n_dec_ent][2]
   const int64_t* split_ptr;  // [B][n_split+1]
-  const int32_t* gm_seg_ent;   // group-major decode: tiles of the sink and of every group
-  const int32_t* gm_items;     // [n_gm_items][4]
-  const int32_t* gm_qrefs;     // [..][2]
   const int64_t* gm_slot_ptr;  // [B+1]
   int32_t n_gm_items;
   int32_t gm_max_queries;      // most queries any group-major item serves
@@ -53,7 +50,9 @@ struct AttnParams {
   const float* rope_table;    // [rope_n_pos][D/2][2] fp32 (cos, sin) of id * inv_freq
   int32_t rope_n_pos;
   const int32_t* list_shift;  // [n_ent]: rotation id of row i of a Q tile for entry e = list_shift[e] + i
-  const int32_t* gm_qshift;   // [n_qrefs]: rotation id of a decode row = gm_qshift[ref] + self_len - 1
+  const int32_t* gm_item_run; // group-major decode: [n_gm_items][4] = (first key row, keys, queries, 0)
+  const int32_t* gm_ref_pad;  // [n_gm_items][32][4] = (query, slot, shift, 0), tail repeats the last reference;
+                              // rotation id of a decode row = shift + self_len - 1
   float scale;                // softmax scale
   float scale_log2e;          // scale * log2(e)
 };

@@ -285,6 +285,28 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
   }
 
   for (size_t i = 3; i < L->gm_items.size(); i += 4) L->gm_max_queries = std::max(L->gm_max_queries, L->gm_items[i]);
+  {
+    const size_t n_items = L->gm_items.size() / 4;
+    L->gm_item_run.resize(n_items * 4);
+    L->gm_ref_pad.resize(n_items * 32 * 4);
+    for (size_t it = 0; it < n_items; ++it) {
+      const int32_t ent_begin = L->gm_items[4 * it], ent_count = L->gm_items[4 * it + 1];
+      const int32_t ref_begin = L->gm_items[4 * it + 2], n_q = L->gm_items[4 * it + 3];
+      // tiles of one segment follow each other without gaps and all but the last are full
+      L->gm_item_run[4 * it + 0] = L->gm_seg_ent[2 * ent_begin];
+      L->gm_item_run[4 * it + 1] = block_n * (ent_count - 1) + (L->gm_seg_ent[2 * (ent_begin + ent_count - 1) + 1] & 0xFFFF);
+      L->gm_item_run[4 * it + 2] = n_q;
+      L->gm_item_run[4 * it + 3] = 0;
+      for (int32_t j = 0; j < 32; ++j) {
+        const int32_t ref = ref_begin + std::min(j, n_q - 1);
+        int32_t* dst = &L->gm_ref_pad[(it * 32 + j) * 4];
+        dst[0] = L->gm_qrefs[2 * ref];
+        dst[1] = L->gm_qrefs[2 * ref + 1];
+        dst[2] = L->gm_qshift[ref];
+        dst[3] = 0;
+      }
+    }
+  }
   L->shortest_list = INT64_MAX;
   for (int64_t t = 0; t < L->n_qtiles(); ++t) {
     L->shortest_list = std::min(L->shortest_list, L->list_ptr[t + 1] - L->list_ptr[t]);

@@ -18,12 +18,10 @@ struct dbsa_device_lists {
   int32_t* order = nullptr;       // [n_qtiles]
   int32_t* dec_ent = nullptr;     // [n_dec_ent][2]
   int64_t* split_ptr = nullptr;   // [B][n_split+1]
-  int32_t* gm_seg_ent = nullptr;  // [n_seg_ent][2]
-  int32_t* gm_items = nullptr;    // [n_items][4]
-  int32_t* gm_qrefs = nullptr;    // [n_qrefs][2]
   int64_t* gm_slot_ptr = nullptr; // [B+1]
   int32_t* list_shift = nullptr;  // [n_ent]
-  int32_t* gm_qshift = nullptr;   // [n_qrefs]
+  int32_t* gm_item_run = nullptr; // [n_items][4]
+  int32_t* gm_ref_pad = nullptr;  // [n_items][32][4]
 };
 
 struct dbsa_layout {
@@ -57,6 +55,11 @@ struct dbsa_layout {
   std::vector<int32_t> list_shift;  // [n_ent]
   std::vector<int32_t> gm_qshift;   // [n_qrefs]
   std::vector<int32_t> cache_len;   // [B]: |D'| of query u = sink + its selected groups
+  // what the decode kernel reads, flattened so that nothing it needs first hangs off another load:
+  // per item (first key row, keys, queries, 0) and 32 references (query, slot, shift, 0), the
+  // tail repeating the last real reference
+  std::vector<int32_t> gm_item_run; // [n_items][4]
+  std::vector<int32_t> gm_ref_pad;  // [n_items][32][4]
   // figures the attention calls need on every launch, taken once at build time
   int32_t gm_max_queries = 1;       // most queries any schedule item serves
   int64_t shortest_list = 0;        // fewest entries any Q tile lists
