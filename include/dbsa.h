@@ -281,6 +281,12 @@ int dbsa_query_attn(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_tensor k
  *   workspace               : device memory of >= dbsa_workspace_bytes() bytes,
  *                             16-byte aligned; contents are overwritten.
  * Same dtype rules; block_n == 64 for DBSA_BF16.  Errors add WORKSPACE.
+ *
+ * Successive calls on one layout alternate the direction in which every run of keys is walked
+ * (front to back, back to front): a step reads the same selected keys as the step before, more
+ * of them than the last-level cache holds, and what the previous step read last is still there.
+ * The two directions differ by fp32 summation order only.  Calls on one layout from several
+ * threads are safe; they merely share that alternation.
  */
 int dbsa_decode_attn(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
                      const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool, dbsa_tensor v_pool,

@@ -206,6 +206,7 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
   p.scale_log2e = scale * 1.4426950408889634f;
   p.rope_table = rope_table;
   p.rope_n_pos = rope_n_pos;
+  L->last_walk_reversed.store(0);  // prefill-shaped calls walk their lists front to back
   hipError_t e;
   if (dtype == DBSA_BF16) {
     if (!mfma_tile_sizes_ok(L)) return DBSA_ERR_UNSUPPORTED;
@@ -473,6 +474,11 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
   p.scale_log2e = softmax_scale * 1.4426950408889634f;
   p.rope_table = rope_table;
   p.rope_n_pos = rope_n_pos;
+  // Every step reads the same selected keys, more of them than the last-level cache holds, so a
+  // step that walks them in the order of the step before finds none of them cached.  Successive
+  // calls on one layout therefore alternate the direction in which each run of keys is walked
+  // (the query prefill walks forward): what the previous call read last is read first.
+  p.decode_reverse = L->last_walk_reversed.fetch_xor(1) ^ 1;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (dtype == DBSA_BF16) {

@@ -120,9 +120,11 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   const int v_stride = static_cast<int>(self_item ? p.v_self.stride_tok : p.v_pool.stride_tok);
 
   // half tile hh -> (first token, number of valid keys)
+  // (walked from the far end when p.decode_reverse is set, see there)
   auto half_ref = [&](int hh, int& start, int& len) {
-    start = first_key + hh * kHalf;
-    len = min(kHalf, n_keys - hh * kHalf);
+    const int pos = p.decode_reverse ? n_half - 1 - hh : hh;
+    start = first_key + pos * kHalf;
+    len = min(kHalf, n_keys - pos * kHalf);
   };
 
   // ---- loads: 8 K blocks and 8 V blocks of 1 KiB per half tile ----

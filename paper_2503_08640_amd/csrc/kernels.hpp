@@ -40,6 +40,7 @@ struct AttnParams {
   int64_t lse_stride;         // rows per head in lse
   float* partial;             // decode: [slot][Hq][D + kPartialPad]; per-query splits use slot = u*n_split + s;
                               // split prefill: [row][Hq][q_split][D + kPartialPad]
+  int32_t decode_reverse;     // decode: walk every run of keys from its last half tile to its first
   int32_t q_split;            // prefill: runs each Q tile's list is cut into (1 = no split, no merge pass)
   int32_t n_rows;             // prefill: rows of q / o
   // shapes

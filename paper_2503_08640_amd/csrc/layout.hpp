@@ -2,6 +2,7 @@
 // layout.cpp and their device mirrors filled in by api.hip.
 #pragma once
 
+#include <atomic>
 #include <cstdint>
 #include <vector>
 
@@ -66,6 +67,9 @@ struct dbsa_layout {
   int64_t max_rotation_id = -1;     // largest id a prefill row looks up: max(list_shift[e] + rows of the tile) - 1
 
   dbsa_device_lists dev;
+  // direction of the last walk over the pool's keys by an attention call on this layout (the
+  // decode call alternates it); not part of the lists, hence mutable
+  mutable std::atomic<int> last_walk_reversed{0};
 
   int64_t n_qtiles() const { return static_cast<int64_t>(qtile_tab.size() / 4); }
   int64_t n_ent() const { return static_cast<int64_t>(list_ent.size() / 2); }
