@@ -347,6 +347,23 @@ int dbsa_decode_attn_rope(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_te
                           int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                           float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * dbsa_decode_attn over a pool whose keys and values are stored as 8-bit floats (Sec. 6 names
+ * KV-cache quantisation as compatible with the method; the decode step is bound by the bytes
+ * of the selected caches, Sec. 4).  k_pool8 / v_pool8: device bytes [N, n_kv_heads, D] in the
+ * OCP e4m3 format (1-4-3, bias 7, no infinities), strides in bytes and multiples of 16;
+ * the value of an element is byte * k_scale[kv head] (v_scale likewise), scales: device float
+ * [n_kv_heads].  Quantising is the caller's business; the result is defined on the
+ * de-quantised values.  q_step, the self caches (the query's own keys, never quantised) and o
+ * are bf16.  head_dim 128, block_n 64, 32 % (n_q_heads / n_kv_heads) == 0 (else UNSUPPORTED).
+ * Everything else (workspace, alternating walk direction, errors) as dbsa_decode_attn.
+ */
+int dbsa_decode_attn_kv8(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_tensor k_selfcache,
+                         dbsa_tensor v_selfcache, const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool8,
+                         dbsa_tensor v_pool8, const float* k_scale, const float* v_scale, dbsa_tensor o,
+                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

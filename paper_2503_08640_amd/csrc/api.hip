@@ -400,6 +400,50 @@ int dbsa_decode_attn(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_sel
                        n_q_heads, n_kv_heads, head_dim, softmax_scale, workspace, workspace_bytes, stream, nullptr, 0);
 }
 
+int dbsa_decode_attn_kv8(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
+                         const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool8, dbsa_tensor v_pool8,
+                         const float* k_scale, const float* v_scale, dbsa_tensor o, int32_t n_q_heads,
+                         int32_t n_kv_heads, int32_t head_dim, float softmax_scale, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  if (!L || !L->on_device || !L->query_stage || !self_len || !k_scale || !v_scale) return DBSA_ERR_INVALID_ARG;
+  if (int rc = check_shapes(DBSA_BF16, n_q_heads, n_kv_heads, head_dim, softmax_scale)) return rc;
+  if (!tensor_ok(q_step, DBSA_BF16) || !tensor_ok(k_selfcache, DBSA_BF16) || !tensor_ok(v_selfcache, DBSA_BF16) ||
+      !tensor_ok(o, DBSA_BF16))
+    return DBSA_ERR_INVALID_ARG;
+  for (const dbsa_tensor* t : {&k_pool8, &v_pool8})
+    if (!t->ptr || reinterpret_cast<uintptr_t>(t->ptr) % 16 != 0 || t->stride_tok <= 0 || t->stride_head <= 0 ||
+        t->stride_tok % 16 != 0 || t->stride_head % 16 != 0)
+      return DBSA_ERR_INVALID_ARG;
+  if (stride_query <= 0 || stride_query % 8 != 0) return DBSA_ERR_INVALID_ARG;
+  const int r = n_q_heads / n_kv_heads;
+  const int64_t max_stride = std::max(std::max(k_pool8.stride_tok, v_pool8.stride_tok),
+                                      std::max(k_selfcache.stride_tok, v_selfcache.stride_tok));
+  if (head_dim != 128 || L->block_n != 64 || r > 32 || 32 % r != 0 || max_stride >= (int64_t{1} << 24))
+    return DBSA_ERR_UNSUPPORTED;
+  const size_t need = dbsa_workspace_bytes(L, n_q_heads, head_dim);
+  if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
+    return DBSA_ERR_WORKSPACE;
+  AttnParams p{};
+  fill_lists(p, L);
+  p.q = view(q_step);
+  p.o = view(o);
+  p.k_pool = view(k_pool8);
+  p.v_pool = view(v_pool8);
+  p.k_self = view(k_selfcache);
+  p.v_self = view(v_selfcache);
+  p.stride_query = stride_query;
+  p.self_len = self_len;
+  p.n_q_heads = n_q_heads;
+  p.n_kv_heads = n_kv_heads;
+  p.scale = softmax_scale;
+  p.scale_log2e = softmax_scale * 1.4426950408889634f;
+  p.k_scale8 = k_scale;
+  p.v_scale8 = v_scale;
+  p.partial = static_cast<float*>(workspace);
+  p.decode_reverse = L->last_walk_reversed.fetch_xor(1) ^ 1;
+  return launch_decode_group_kv8(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;
+}
+
 int dbsa_rope_table(const double* inv_freq, int32_t head_dim, int32_t n_pos, float* table, void* stream) {
   if (!inv_freq || !table || n_pos < 1 || head_dim < 2 || head_dim > 128 || head_dim % 2 != 0)
     return DBSA_ERR_INVALID_ARG;

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   const int hk = blockIdx.y;
 
   // ---- the item: a run of pool tiles for several queries, or one query's own cache ----
-  const int item = blockIdx.x;
+  const int item = blockIdx.x + p.item_offset;
   const bool self_item = item >= p.n_gm_items;
   // (the schedule lists are read-only while a kernel runs: scalar loads through the constant path)
   typedef const __attribute__((address_space(4))) int32_t* const_words;
@@ -365,6 +365,234 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Pool items over an fp8 (e4m3) pool: half the bytes per key.  Same work decomposition as
+// decode_group_kernel (one wave per (item, KV head, query batch)).  A half tile of 32 keys
+// arrives as 4 KiB of K bytes and 4 KiB of V bytes in a ring of four 4-KiB slots (K(h), V(h),
+// K(h+1), V(h+1)).  K fragments are read from the staged bytes directly and widened to bf16 in
+// registers; V is widened into one bf16 working tile (the transposed fragment reads need 16-bit
+// elements), same swizzle as the bf16 kernel.  24 KiB of LDS per wave keeps six waves per CU.
+// The per-head scales ride on Q (keys) and on the partial accumulators (values), so no key or
+// value is ever multiplied.
+constexpr int kSlot8 = 4096;
+constexpr int kLds8 = 4 * kSlot8 + kHalfBytes;  // 24 KiB per wave
+constexpr int kLoads8 = 4;                      // load instructions per group (the K or the V bytes of a half tile)
+
+__device__ inline bf16x8 widen8(unsigned w0, unsigned w1) {
+  union {
+    bf16x8 v;
+    bf16x2 p2[4];
+  } out;
+  out.p2[0] = __builtin_convertvector(__builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w0), false), bf16x2);
+  out.p2[1] = __builtin_convertvector(__builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w0), true), bf16x2);
+  out.p2[2] = __builtin_convertvector(__builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w1), false), bf16x2);
+  out.p2[3] = __builtin_convertvector(__builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w1), true), bf16x2);
+  return out.v;
+}
+
+__global__ __launch_bounds__(64, 2) void decode_group_kv8_kernel(AttnParams p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  lds_byte* lds = (lds_byte*)smem;
+  lds_byte* work_v = lds + 4 * kSlot8;
+  const int lane = threadIdx.x, l32 = lane % 32, half = lane / 32;
+  const int r = p.n_q_heads / p.n_kv_heads;
+  const int qpw = 32 / r;
+  const int hk = blockIdx.y;
+  const int item = blockIdx.x;  // pool items only: 0 .. n_gm_items-1
+  typedef const __attribute__((address_space(4))) int32_t* const_words;
+  const const_words runs = (const_words)(reinterpret_cast<uintptr_t>(p.gm_item_run));
+  const int first_key = runs[4 * item + 0], n_keys = runs[4 * item + 1], n_q = runs[4 * item + 2];
+  const int n_half = (n_keys + kHalf - 1) / kHalf;
+  const int pass = blockIdx.z;
+  if (pass >= (n_q + qpw - 1) / qpw) return;
+
+  const unsigned char* kbase = static_cast<const unsigned char*>(p.k_pool.ptr) + hk * p.k_pool.stride_head;
+  const unsigned char* vbase = static_cast<const unsigned char*>(p.v_pool.ptr) + hk * p.v_pool.stride_head;
+  const int k_stride = static_cast<int>(p.k_pool.stride_tok), v_stride = static_cast<int>(p.v_pool.stride_tok);
+  auto half_ref = [&](int hh, int& start, int& len) {
+    const int pos = p.decode_reverse ? n_half - 1 - hh : hh;
+    start = first_key + pos * kHalf;
+    len = min(kHalf, n_keys - pos * kHalf);
+  };
+  // Load instruction j fills rows 8j .. 8j+7 of a staged operand (128-byte rows; lane -> row
+  // 8j + lane/8, 16-byte slot lane%8); rows past the tail repeat the last key.  K slots are
+  // swizzled by row % 8 (= lane/8) for the 64-bit fragment reads: 32 rows x one 8-byte piece
+  // would otherwise sit 16 deep on the same banks.
+  auto issue_k = [&](int hh) {
+    int start, len;
+    half_ref(hh, start, len);
+    lds_byte* stage = lds + ((2 * hh) % 4) * kSlot8;
+    const unsigned char* kb = kbase + static_cast<int64_t>(start) * k_stride;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row = min(8 * j + lane / 8, len - 1);
+      dma16(kb, static_cast<unsigned>(row * k_stride + (((lane % 8) ^ (lane / 8)) * 16)), stage + j * 1024);
+    }
+  };
+  auto issue_v = [&](int hh) {
+    int start, len;
+    half_ref(hh, start, len);
+    lds_byte* stage = lds + ((2 * hh + 1) % 4) * kSlot8;
+    const unsigned char* vb = vbase + static_cast<int64_t>(start) * v_stride;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row = min(8 * j + lane / 8, len - 1);
+      dma16(vb, static_cast<unsigned>(row * v_stride + (lane % 8) * 16), stage + j * 1024);
+    }
+  };
+  auto wait_groups = [&](int groups) {  // at most `groups` load groups (0..3) still in flight
+    if (groups >= 3) wait_vmcnt<3 * kLoads8>();
+    else if (groups == 2) wait_vmcnt<2 * kLoads8>();
+    else if (groups == 1) wait_vmcnt<kLoads8>();
+    else wait_vmcnt<0>();
+  };
+
+  // K fragment c of key row l32: channels 16c + 8*half .. +7 = 8 bytes of slot c ^ (l32 % 8)
+  const int k8_base = l32 * 128 + 8 * half;
+  const int k8_swz = l32 % 8;
+  const int v_base = (4 * half + (lane % 16) / 4) * kRowBytes +
+                     (((2 * (l32 / 16) + (lane % 4) / 2) ^ (4 * ((lane % 16) / 4))) * 16) + (lane % 2) * 8;
+
+  // ---- this lane's column ----
+  const int q_local = pass * qpw + l32 / r;
+  const bool col_valid = q_local < n_q;
+  typedef int intx4 __attribute__((ext_vector_type(4)));
+  const intx4 ref = *reinterpret_cast<const intx4*>(p.gm_ref_pad + (static_cast<int64_t>(item) * 32 + q_local) * 4);
+  const int u = ref[0], slot = ref[1];
+  const int head = hk * r + l32 % r;
+  const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
+                     static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
+  asm volatile("" : "+v"(qp));
+  issue_k(0);
+  issue_v(0);
+  if (1 < n_half) {
+    issue_k(1);
+    issue_v(1);
+  }
+  const float c2 = p.scale_log2e * p.k_scale8[hk];
+  const float v_scale = p.v_scale8[hk];
+  bf16x8 qf[kD / 16];
+#pragma unroll
+  for (int c = 0; c < kD / 16; ++c) {
+    const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
+    union {
+      bf16x8 v;
+      bf16x2 p2[4];
+    } sc;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      sc.p2[e] = __builtin_convertvector(
+          floatx2{static_cast<float>(raw[2 * e]) * c2, static_cast<float>(raw[2 * e + 1]) * c2}, bf16x2);
+    qf[c] = sc.v;
+  }
+  floatx16 o[kD / 32];
+#pragma unroll
+  for (int ob = 0; ob < kD / 32; ++ob)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[ob][i] = 0.f;
+  float m_run = -1.0e30f, l_run = 0.f;
+
+  for (int hh = 0; hh < n_half; ++hh) {
+    const bool more = hh + 1 < n_half;
+    // K(hh) has landed once only the groups issued after it are outstanding: V(hh), K(hh+1), V(hh+1)
+    wait_groups(more ? 3 : 1);
+    int start, len;
+    half_ref(hh, start, len);
+    const lds_byte* ks = lds + ((2 * hh) % 4) * kSlot8;
+    const lds_byte* vs = lds + ((2 * hh + 1) % 4) * kSlot8;
+
+    floatx16 s, s2;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = 0.f, s2[i] = 0.f;
+#pragma unroll
+    for (int c = 0; c < kD / 16; c += 2) {
+      typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
+      const uintx2 w = *reinterpret_cast<const __attribute__((address_space(3))) uintx2*>(ks + k8_base + ((c ^ k8_swz) * 16));
+      const uintx2 w2 =
+          *reinterpret_cast<const __attribute__((address_space(3))) uintx2*>(ks + k8_base + (((c + 1) ^ k8_swz) * 16));
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(w[0], w[1]), qf[c], s, 0, 0, 0);
+      s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen8(w2[0], w2[1]), qf[c + 1], s2, 0, 0, 0);
+    }
+    s += s2;
+    // the K slot is free (its bytes are in registers): it takes the K bytes two half tiles on
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (hh + 2 < n_half) issue_k(hh + 2);
+    if (len < kHalf) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key_local = 8 * (i / 4) + 4 * half + (i % 4);
+        s[i] = key_local < len ? s[i] : -INFINITY;
+      }
+    }
+    float mx = s[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+    mx = half_swap_max(mx);
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int ob = 0; ob < kD / 32; ++ob) o[ob] *= alpha;
+    }
+    union {
+      bf16x8 v[2];
+      bf16x2 p2[8];
+    } pf;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float p0 = __builtin_amdgcn_exp2f(s[2 * i] - m_run);
+      const float p1 = __builtin_amdgcn_exp2f(s[2 * i + 1] - m_run);
+      pf.p2[i] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);
+      l_run += p0 + p1;
+    }
+    // V(hh) has landed once only K(hh+1), V(hh+1) and K(hh+2) are outstanding
+    wait_groups((more ? 2 : 0) + (hh + 2 < n_half ? 1 : 0));
+    // staged V bytes -> the swizzled bf16 working tile
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+      typedef __attribute__((address_space(3))) bf16x8* tile_ptr;
+      const int row = 8 * j + lane / 8, s0 = 2 * (lane % 8);
+      const uintx4 vx = *reinterpret_cast<const __attribute__((address_space(3))) uintx4*>(vs + j * 1024 + lane * 16);
+      *(tile_ptr)(work_v + row * kRowBytes + ((s0 ^ (4 * (row % 4))) * 16)) = widen8(vx[0], vx[1]);
+      *(tile_ptr)(work_v + row * kRowBytes + (((s0 + 1) ^ (4 * (row % 4))) * 16)) = widen8(vx[2], vx[3]);
+    }
+    // the V slot is free: it takes the V bytes two half tiles on
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (hh + 2 < n_half) issue_v(hh + 2);
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+      for (int ob = 0; ob < kD / 32; ++ob) {
+        const lds_byte* vp = work_v + (v_base ^ (64 * ob)) + 16 * ch * kRowBytes;
+        const bf16x4 lo = lds_read_tr(vp);
+        const bf16x4 hi = lds_read_tr(vp + 8 * kRowBytes);
+        const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf.v[ch], o[ob], 0, 0, 0);
+      }
+    // the working tile is rewritten in the next round: its reads must have returned
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  }
+
+  const float l_tot = half_swap_sum(l_run);
+  if (col_valid) {
+    float* part = p.partial + (static_cast<int64_t>(slot) * p.n_q_heads + head) * (kD + kPartialPad);
+#pragma unroll
+    for (int ob = 0; ob < kD / 32; ++ob)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<floatx4*>(part + 32 * ob + 8 * g + 4 * half) =
+            floatx4{o[ob][4 * g] * v_scale, o[ob][4 * g + 1] * v_scale, o[ob][4 * g + 2] * v_scale,
+                    o[ob][4 * g + 3] * v_scale};
+    if (half == 0) {
+      part[kD] = m_run;
+      part[kD + 1] = l_tot;
+    }
+  }
+}
+
 // Merge the partial states of one (query, head): slots [slot_ptr[u], slot_ptr[u+1]).
 // Thread d owns output channel d.  The per-slot maxima and sums are read with one slot per
 // thread (not one after the other by everyone), the weights 2^(m_s - m*) go through LDS, and
@@ -422,6 +650,34 @@ __global__ __launch_bounds__(kD) void decode_group_merge_kernel(AttnParams p) {
 }
 
 }  // namespace
+
+hipError_t launch_decode_group_kv8(const AttnParams& p_in, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_kv8_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds8);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_kernel<false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  AttnParams p = p_in;
+  const int qpw = 32 / (p.n_q_heads / p.n_kv_heads);
+  if (p.n_gm_items > 0) {
+    dim3 grid(p.n_gm_items, p.n_kv_heads, (p.gm_max_queries + qpw - 1) / qpw);
+    decode_group_kv8_kernel<<<grid, dim3(64), kLds8, stream>>>(p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  // every query's own (bf16) cache: the self items of the ordinary kernel
+  p.item_offset = p.n_gm_items;
+  decode_group_kernel<false><<<dim3(p.n_queries, p.n_kv_heads, 1), dim3(64), kLdsBytes, stream>>>(p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  decode_group_merge_kernel<<<dim3(p.n_queries * p.n_q_heads), dim3(kD), 0, stream>>>(p);
+  return hipGetLastError();
+}
 
 hipError_t launch_decode_group(const AttnParams& p, hipStream_t stream) {
   static bool attr_set = false;

@@ -40,6 +40,9 @@ struct AttnParams {
   int64_t lse_stride;         // rows per head in lse
   float* partial;             // decode: [slot][Hq][D + kPartialPad]; per-query splits use slot = u*n_split + s;
                               // split prefill: [row][Hq][q_split][D + kPartialPad]
+  int32_t item_offset;        // decode: first work item of the launch (blockIdx.x counts from it)
+  const float* k_scale8;      // decode over an fp8 pool: k = k8 * k_scale8[kv head], v = v8 * v_scale8[kv head]
+  const float* v_scale8;
   int32_t decode_reverse;     // decode: walk every run of keys from its last half tile to its first
   int32_t q_split;            // prefill: runs each Q tile's list is cut into (1 = no split, no merge pass)
   int32_t n_rows;             // prefill: rows of q / o
@@ -64,6 +67,8 @@ hipError_t launch_prefill_mfma(const AttnParams& p, int head_dim, hipStream_t st
 hipError_t launch_prefill_pipelined(const AttnParams& p, hipStream_t stream);
 // group-major split-KV decode + merge for head_dim 128 (attn_decode.hip)
 hipError_t launch_decode_group(const AttnParams& p, hipStream_t stream);
+// the same with pool K/V stored as fp8 (e4m3) bytes and per-KV-head scales
+hipError_t launch_decode_group_kv8(const AttnParams& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const AttnParams& p, int head_dim, hipStream_t stream);
 hipError_t launch_decode_merge(const AttnParams& p, int head_dim, bool out_bf16, hipStream_t stream);
 

@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     header = open(os.path.join(root, "include", "dbsa.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(dbsa_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(dbsa_[a-z0-9_]+)\s*\(", header))
     assert declared == set(B.EXPORTED_SYMBOLS)
     L = B.lib()
     for name in declared:
