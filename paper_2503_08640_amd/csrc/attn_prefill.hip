@@ -571,23 +571,33 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   }
 }
 
-// Merge of the gridDim.z partial states of one (row, head): thread d owns channel d.
+// Merge of the n_split partial states of a (row, head): 32 threads per pair, four channels each.
 // o = sum_z 2^(m_z - m*) acc_z / sum_z 2^(m_z - m*) l_z, statistics in the log2 domain.
-__global__ __launch_bounds__(kD) void prefill_merge_kernel(AttnParams p, int n_rows, int n_split) {
-  const int row = blockIdx.x / p.n_q_heads, head = blockIdx.x % p.n_q_heads, d = threadIdx.x;
-  if (row >= n_rows) return;
-  const float* part = p.partial + (static_cast<int64_t>(row) * p.n_q_heads + head) * n_split * (kD + kPartialPad);
+constexpr int kMergePairs = 8;  // (row, head) pairs per workgroup of 256 threads
+__global__ __launch_bounds__(32 * kMergePairs) void prefill_merge_kernel(AttnParams p, int n_rows, int n_split) {
+  const int64_t pair = static_cast<int64_t>(blockIdx.x) * kMergePairs + threadIdx.x / 32;
+  if (pair >= static_cast<int64_t>(n_rows) * p.n_q_heads) return;
+  const int row = static_cast<int>(pair / p.n_q_heads), head = static_cast<int>(pair % p.n_q_heads);
+  const int d = 4 * (threadIdx.x % 32);
+  const float* part = p.partial + pair * n_split * (kD + kPartialPad);
   float m_star = -1.0e30f;
   for (int z = 0; z < n_split; ++z) m_star = fmaxf(m_star, part[z * (kD + kPartialPad) + kD]);
-  float l = 0.f, acc = 0.f;
+  float l = 0.f;
+  floatx4 acc = {0.f, 0.f, 0.f, 0.f};
   for (int z = 0; z < n_split; ++z) {
     const float w = __builtin_amdgcn_exp2f(part[z * (kD + kPartialPad) + kD] - m_star);
     l = fmaf(part[z * (kD + kPartialPad) + kD + 1], w, l);
-    acc = fmaf(part[z * (kD + kPartialPad) + d], w, acc);
+    acc += *reinterpret_cast<const floatx4*>(part + z * (kD + kPartialPad) + d) * w;
   }
+  const float inv = 1.f / l;
+  union {
+    bf16x4 v;
+    bf16x2 p2[2];
+  } w;
+  w.p2[0] = __builtin_convertvector(floatx2{acc[0] * inv, acc[1] * inv}, bf16x2);
+  w.p2[1] = __builtin_convertvector(floatx2{acc[2] * inv, acc[3] * inv}, bf16x2);
   __bf16* o = static_cast<__bf16*>(const_cast<void*>(p.o.ptr));
-  o[static_cast<int64_t>(row) * p.o.stride_tok + static_cast<int64_t>(head) * p.o.stride_head + d] =
-      static_cast<__bf16>(acc / l);
+  *reinterpret_cast<bf16x4*>(o + static_cast<int64_t>(row) * p.o.stride_tok + static_cast<int64_t>(head) * p.o.stride_head + d) = w.v;
   if (p.lse && d == 0) p.lse[static_cast<int64_t>(head) * p.lse_stride + row] = (m_star + __log2f(l)) * 0.69314718055994531f;
 }
 
@@ -606,7 +616,9 @@ hipError_t launch_cfg(const AttnParams& p, hipStream_t stream) {
   attn_prefill_kernel<NW, SL, SELF, ROPE><<<grid, block, lds_bytes, stream>>>(p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_split == 1) return e;
-  prefill_merge_kernel<<<dim3(p.n_rows * p.n_q_heads), dim3(kD), 0, stream>>>(p, p.n_rows, n_split);
+  const int64_t pairs = static_cast<int64_t>(p.n_rows) * p.n_q_heads;
+  prefill_merge_kernel<<<dim3(static_cast<unsigned>((pairs + kMergePairs - 1) / kMergePairs)), dim3(32 * kMergePairs), 0,
+                         stream>>>(p, p.n_rows, n_split);
   return hipGetLastError();
 }
 
