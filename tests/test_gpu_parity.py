@@ -198,6 +198,45 @@ def test_query_and_decode_bf16_head_ratios(hq, hkv, block_m):
     _run_decode_steps(pc, qc, lay, kp, vp, range(2), f"Hq={hq} Hkv={hkv}")
 
 
+@pytest.mark.parametrize("hq,hkv,d,n_split", [(4, 2, 64, 0), (6, 2, 128, 3), (6, 2, 64, 2)])
+def test_query_and_decode_bf16_fallback_kernels(hq, hkv, d, n_split):
+    """head_dim 64 and head ratios that do not divide 32 take the non-pipelined MFMA kernels and
+    the per-(query, split) decode with its own merge."""
+    pc = small_pool_case("fb", 2080 + hq + d, hq=hq, hkv=hkv, d=d, sink=20, pool_tokens=3000, groups=4, lens=(32, 150))
+    qc = synth.make_query_case("qfb", 2081, pc, n_queries=4, q_len=[64, 37, 70, 1], selections=[[3, 0], [], [2, 1, 0, 3], [2]],
+                               n_decode=2)
+    lay, kp, vp = _query_setup(pc, qc, 64, n_split)
+    oq = B.dbsa_query_attn(lay, to_dev(qc.q), to_dev(qc.k), to_dev(qc.v), kp, vp, pc.scale)
+    assert_close(to_f64(oq), _oracle_query(pc, qc), f"fallback query Hq={hq} Hkv={hkv} D={d}")
+    _run_decode_steps(pc, qc, lay, kp, vp, range(2), f"fallback Hq={hq} Hkv={hkv} D={d} ns={n_split}")
+
+
+def test_token_strides_beyond_the_pipelined_kernels_reach_take_the_fallback():
+    """The pipelined kernels address a tile's rows with 32-bit byte offsets (token stride < 2^24
+    elements); a pool viewed with a larger stride must still give the right answer."""
+    pc = small_pool_case("wide", 2090, hq=4, hkv=2, sink=8, pool_tokens=200, groups=2, lens=(16, 60))
+    p = pc.pool
+    stride = (1 << 24) + 256
+    n = p.n_tokens
+
+    def widen(x):                      # [N, H, D] -> the same values at a token stride of `stride` elements
+        flat = torch.zeros(n * stride, dtype=x.dtype, device="cuda")
+        view = flat.as_strided((n, x.shape[1], x.shape[2]), (stride, x.shape[2], 1))
+        view.copy_(x)
+        return view
+
+    k, v = widen(to_dev(pc.k)), widen(to_dev(pc.v))
+    lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, 0, block_m=64, block_n=64)
+    o = B.dbsa_preencode_attn(lay, to_dev(pc.q), k, v, pc.scale)
+    assert_close(to_f64(o), oracle_preencode(pc), "pre-encode, token stride 2^24 + 256")
+    qc = synth.make_query_case("qwide", 2091, pc, n_queries=2, q_len=[40, 3], selections=[[1], [0, 1]], n_decode=1)
+    layq = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, cu_qlens=qc.cu_qlens,
+                               sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, n_split=2, block_m=64, block_n=64)
+    oq = B.dbsa_query_attn(layq, to_dev(qc.q), to_dev(qc.k), to_dev(qc.v), k, v, pc.scale)
+    assert_close(to_f64(oq), _oracle_query(pc, qc), "query prefill, token stride 2^24 + 256")
+    _run_decode_steps(pc, qc, layq, k, v, range(1), "token stride 2^24 + 256")
+
+
 def test_query_prefill_with_split_lists_agrees_with_the_single_pass():
     """Few Q tiles: with a workspace every list is cut into runs whose partial states are merged;
     without one the same call runs each list in one pass.  Both must match the oracle, and each
