@@ -66,11 +66,11 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
                b_dec = L->dec_ent.size() * sizeof(int32_t), b_spl = L->split_ptr.size() * sizeof(int64_t),
                b_gsp = L->gm_slot_ptr.size() * sizeof(int64_t),
                b_lsh = L->list_shift.size() * sizeof(int32_t), b_gir = L->gm_item_run.size() * sizeof(int32_t),
-               b_grp = L->gm_ref_pad.size() * sizeof(int32_t);
+               b_grp = L->gm_ref_pad.size() * sizeof(int32_t), b_grw = L->gm_rows.size() * sizeof(int32_t);
   const size_t o_tab = 0, o_ptr = o_tab + pad(b_tab), o_ent = o_ptr + pad(b_ptr), o_ord = o_ent + pad(b_ent),
                o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), o_gsp = o_spl + pad(b_spl),
                o_lsh = o_gsp + pad(b_gsp), o_gir = o_lsh + pad(b_lsh), o_grp = o_gir + pad(b_gir),
-               total = o_grp + pad(b_grp) + 256;
+               o_grw = o_grp + pad(b_grp), total = o_grw + pad(b_grw) + 256;
   ListBlock blk{};
   hipError_t e = acquire_block(total, &blk);
   if (e != hipSuccess) return e;
@@ -88,6 +88,7 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   put(o_lsh, L->list_shift.data(), b_lsh);
   put(o_gir, L->gm_item_run.data(), b_gir);
   put(o_grp, L->gm_ref_pad.data(), b_grp);
+  put(o_grw, L->gm_rows.data(), b_grw);
   e = hipMemcpyAsync(blk.dev, blk.pinned, total, hipMemcpyHostToDevice, stream);
   if (e == hipSuccess) e = hipStreamSynchronize(stream);  // the staging twin may be reused after return
   if (e != hipSuccess) {
@@ -109,6 +110,7 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   L->dev.list_shift = reinterpret_cast<int32_t*>(b + o_lsh);
   L->dev.gm_item_run = reinterpret_cast<int32_t*>(b + o_gir);
   L->dev.gm_ref_pad = reinterpret_cast<int32_t*>(b + o_grp);
+  L->dev.gm_rows = reinterpret_cast<int32_t*>(b + o_grw);
   return hipSuccess;
 }
 
@@ -160,6 +162,15 @@ bool mfma_tile_sizes_ok(const dbsa_layout* L) {
   return L->block_n == 64 && (bm == 32 || bm == 64 || bm == 128 || bm == 256);
 }
 
+// launch rows of the group-major decode for r query heads per KV head (32 % r == 0)
+void fill_decode_rows(AttnParams& p, const dbsa_layout* L, int r) {
+  int k = 0;
+  while ((32 >> k) > 32 / r) ++k;  // a wave takes 32 / r queries
+  p.gm_rows = L->dev.gm_rows + L->gm_rows_off[k];
+  p.gm_n_rows = L->gm_rows_off[k + 1] - L->gm_rows_off[k];
+  p.gm_pool_rows = L->gm_pool_rows[k];
+}
+
 void fill_lists(AttnParams& p, const dbsa_layout* L) {
   p.qtile_tab = L->dev.qtile_tab;
   p.list_ptr = L->dev.list_ptr;
@@ -173,6 +184,7 @@ void fill_lists(AttnParams& p, const dbsa_layout* L) {
   p.gm_ref_pad = L->dev.gm_ref_pad;
   p.n_gm_items = static_cast<int32_t>(L->gm_items.size() / 4);
   p.gm_max_queries = L->gm_max_queries;
+  p.n_pool_blocks = (p.n_gm_items + 7) / 8;
   p.n_qtiles = static_cast<int32_t>(L->n_qtiles());
   p.n_split = L->n_split;
   p.n_queries = L->n_queries;
@@ -441,6 +453,7 @@ int dbsa_decode_attn_kv8(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k
   p.v_scale8 = v_scale;
   p.partial = static_cast<float*>(workspace);
   p.decode_reverse = L->last_walk_reversed.fetch_xor(1) ^ 1;
+  fill_decode_rows(p, L, r);
   return launch_decode_group_kv8(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;
 }
 
@@ -536,6 +549,7 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
                                         std::max(p.k_self.stride_tok, p.v_self.stride_tok));
     if (head_dim == 128 && 32 % r == 0 && max_stride < (int64_t{1} << 24)) {
       // every KV run is walked once for all the queries that selected it
+      fill_decode_rows(p, L, r);
       e = launch_decode_group(p, s);
     } else {
       if (rope_table) return DBSA_ERR_UNSUPPORTED;  // only the group-major kernel re-positions

@@ -88,13 +88,22 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   const int lane = threadIdx.x, l32 = lane % 32, half = lane / 32;
   const int r = p.n_q_heads / p.n_kv_heads;
   const int qpw = 32 / r;  // queries per wave
-  const int hk = blockIdx.y;
+  // Workgroup id -> (KV head, launch row, item in the row's block of 8), the item fastest.  A row
+  // is (block, query batch); the rows of one block follow each other, so the workgroups that walk
+  // one item's keys for different query batches have ids 8 apart: they start together AND on the
+  // same XCD (ids are dealt to the 8 XCDs in turn), and all but the first find the keys in that
+  // XCD's L2.  Rows exist only for batches some item of the block has.
+  const int in_block = blockIdx.x % 8;
+  const int row_id = (blockIdx.x / 8) % p.launch_rows, hk = (blockIdx.x / 8) / p.launch_rows;
+  typedef const __attribute__((address_space(4))) int32_t* const_words;
+  const int row = ((const_words)(reinterpret_cast<uintptr_t>(p.gm_rows)))[p.row_offset + row_id];
+  const int pass = row & 0xFF, block = row >> 8;
 
   // ---- the item: a run of pool tiles for several queries, or one query's own cache ----
-  const int item = blockIdx.x + p.item_offset;
-  const bool self_item = item >= p.n_gm_items;
+  const bool self_item = block >= p.n_pool_blocks;
+  const int item = self_item ? p.n_gm_items + 8 * (block - p.n_pool_blocks) + in_block : 8 * block + in_block;
+  if (item >= (self_item ? p.n_gm_items + p.n_queries : p.n_gm_items)) return;
   // (the schedule lists are read-only while a kernel runs: scalar loads through the constant path)
-  typedef const __attribute__((address_space(4))) int32_t* const_words;
   const const_words runs = (const_words)(reinterpret_cast<uintptr_t>(p.gm_item_run));
   // the run is a stretch of consecutive key rows: first_key .. first_key + n_keys.  Everything
   // the first loads need (the run, the query references) is one load away from the item index:
@@ -190,10 +199,9 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   const float c2 = p.scale_log2e;
   const int n_pass = (n_q + qpw - 1) / qpw;
 
-  // One workgroup per batch of 32 / r queries of the item (blockIdx.z): an item that serves more
-  // queries than one wave has columns is walked by several workgroups side by side instead of by
-  // one workgroup several times, which would make it the last to finish.
-  const int pass = blockIdx.z;
+  // One workgroup per batch of 32 / r queries of the item: an item that serves more queries than
+  // one wave has columns is walked by several workgroups side by side instead of by one workgroup
+  // several times, which would make it the last to finish.
   if (pass >= n_pass) return;
   {
     // ---- this lane's column: query and head ----
@@ -397,13 +405,17 @@ __global__ __launch_bounds__(64, 2) void decode_group_kv8_kernel(AttnParams p) {
   const int lane = threadIdx.x, l32 = lane % 32, half = lane / 32;
   const int r = p.n_q_heads / p.n_kv_heads;
   const int qpw = 32 / r;
-  const int hk = blockIdx.y;
-  const int item = blockIdx.x;  // pool items only: 0 .. n_gm_items-1
+  // same id mapping as decode_group_kernel; this launch covers the rows of pool items only
+  const int in_block = blockIdx.x % 8;
+  const int row_id = (blockIdx.x / 8) % p.launch_rows, hk = (blockIdx.x / 8) / p.launch_rows;
   typedef const __attribute__((address_space(4))) int32_t* const_words;
+  const int row = ((const_words)(reinterpret_cast<uintptr_t>(p.gm_rows)))[p.row_offset + row_id];
+  const int pass = row & 0xFF;
+  const int item = 8 * (row >> 8) + in_block;
+  if (item >= p.n_gm_items) return;
   const const_words runs = (const_words)(reinterpret_cast<uintptr_t>(p.gm_item_run));
   const int first_key = runs[4 * item + 0], n_keys = runs[4 * item + 1], n_q = runs[4 * item + 2];
   const int n_half = (n_keys + kHalf - 1) / kHalf;
-  const int pass = blockIdx.z;
   if (pass >= (n_q + qpw - 1) / qpw) return;
 
   const unsigned char* kbase = static_cast<const unsigned char*>(p.k_pool.ptr) + hk * p.k_pool.stride_head;
@@ -651,6 +663,11 @@ __global__ __launch_bounds__(kD) void decode_group_merge_kernel(AttnParams p) {
 
 }  // namespace
 
+namespace {
+// one workgroup per (KV head, launch row, item of the row's block)
+dim3 decode_grid(const AttnParams& p) { return dim3(static_cast<unsigned>(p.n_kv_heads) * p.launch_rows * 8); }
+}  // namespace
+
 hipError_t launch_decode_group_kv8(const AttnParams& p_in, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
@@ -665,21 +682,24 @@ hipError_t launch_decode_group_kv8(const AttnParams& p_in, hipStream_t stream) {
   AttnParams p = p_in;
   const int qpw = 32 / (p.n_q_heads / p.n_kv_heads);
   if (p.n_gm_items > 0) {
-    dim3 grid(p.n_gm_items, p.n_kv_heads, (p.gm_max_queries + qpw - 1) / qpw);
-    decode_group_kv8_kernel<<<grid, dim3(64), kLds8, stream>>>(p);
+    p.row_offset = 0;
+    p.launch_rows = p.gm_pool_rows;
+    decode_group_kv8_kernel<<<decode_grid(p), dim3(64), kLds8, stream>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   // every query's own (bf16) cache: the self items of the ordinary kernel
-  p.item_offset = p.n_gm_items;
-  decode_group_kernel<false><<<dim3(p.n_queries, p.n_kv_heads, 1), dim3(64), kLdsBytes, stream>>>(p);
+  p.row_offset = p.gm_pool_rows;
+  p.launch_rows = p.gm_n_rows - p.gm_pool_rows;
+  decode_group_kernel<false><<<decode_grid(p), dim3(64), kLdsBytes, stream>>>(p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   decode_group_merge_kernel<<<dim3(p.n_queries * p.n_q_heads), dim3(kD), 0, stream>>>(p);
   return hipGetLastError();
 }
 
-hipError_t launch_decode_group(const AttnParams& p, hipStream_t stream) {
+hipError_t launch_decode_group(const AttnParams& p_in, hipStream_t stream) {
+  AttnParams p = p_in;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_kernel<false>),
@@ -691,7 +711,9 @@ hipError_t launch_decode_group(const AttnParams& p, hipStream_t stream) {
     attr_set = true;
   }
   const int qpw = 32 / (p.n_q_heads / p.n_kv_heads);
-  dim3 grid(p.n_gm_items + p.n_queries, p.n_kv_heads, (p.gm_max_queries + qpw - 1) / qpw), block(64);
+  p.row_offset = 0;
+  p.launch_rows = p.gm_n_rows;
+  const dim3 grid = decode_grid(p), block(64);
   if (p.rope_table)
     decode_group_kernel<true><<<grid, block, kLdsBytes, stream>>>(p);
   else

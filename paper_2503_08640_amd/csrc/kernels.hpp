@@ -40,7 +40,13 @@ struct AttnParams {
   int64_t lse_stride;         // rows per head in lse
   float* partial;             // decode: [slot][Hq][D + kPartialPad]; per-query splits use slot = u*n_split + s;
                               // split prefill: [row][Hq][q_split][D + kPartialPad]
-  int32_t item_offset;        // decode: first work item of the launch (blockIdx.x counts from it)
+  // group-major decode launch: workgroup id -> row (id / 8) % launch_rows of gm_rows + row_offset,
+  // KV head (id / 8) / launch_rows, item 8 * block + id % 8 of the row's block; blocks below
+  // n_pool_blocks hold pool items, the others self items (one per query)
+  const int32_t* gm_rows;     // (block << 8 | query batch), pool rows first
+  int32_t gm_n_rows, gm_pool_rows;
+  int32_t n_pool_blocks;
+  int32_t row_offset, launch_rows;
   const float* k_scale8;      // decode over an fp8 pool: k = k8 * k_scale8[kv head], v = v8 * v_scale8[kv head]
   const float* v_scale8;
   int32_t decode_reverse;     // decode: walk every run of keys from its last half tile to its first

@@ -307,6 +307,22 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
       }
     }
   }
+  if (L->query_stage) {
+    const int32_t n_items = static_cast<int32_t>(L->gm_items.size() / 4);
+    const int32_t pool_blocks = (n_items + 7) / 8, self_blocks = (L->n_queries + 7) / 8;
+    for (int k = 0; k < 6; ++k) {
+      const int32_t per_wave = 32 >> k;
+      L->gm_rows_off[k] = static_cast<int32_t>(L->gm_rows.size());
+      for (int32_t b = 0; b < pool_blocks; ++b) {
+        int32_t most = 0;
+        for (int32_t it = 8 * b; it < std::min(n_items, 8 * b + 8); ++it) most = std::max(most, L->gm_items[4 * it + 3]);
+        for (int32_t z = 0; z * per_wave < most; ++z) L->gm_rows.push_back((b << 8) | z);
+      }
+      L->gm_pool_rows[k] = static_cast<int32_t>(L->gm_rows.size()) - L->gm_rows_off[k];
+      for (int32_t b = 0; b < self_blocks; ++b) L->gm_rows.push_back((pool_blocks + b) << 8);
+    }
+    L->gm_rows_off[6] = static_cast<int32_t>(L->gm_rows.size());
+  }
   L->shortest_list = INT64_MAX;
   for (int64_t t = 0; t < L->n_qtiles(); ++t) {
     L->shortest_list = std::min(L->shortest_list, L->list_ptr[t + 1] - L->list_ptr[t]);

@@ -23,6 +23,7 @@ struct dbsa_device_lists {
   int32_t* list_shift = nullptr;  // [n_ent]
   int32_t* gm_item_run = nullptr; // [n_items][4]
   int32_t* gm_ref_pad = nullptr;  // [n_items][32][4]
+  int32_t* gm_rows = nullptr;
 };
 
 struct dbsa_layout {
@@ -61,6 +62,12 @@ struct dbsa_layout {
   // tail repeating the last real reference
   std::vector<int32_t> gm_item_run; // [n_items][4]
   std::vector<int32_t> gm_ref_pad;  // [n_items][32][4]
+  // launch rows of the decode kernel, one table per number of queries a wave takes (32 >> k,
+  // k = 0..5): a row is (block of 8 work items) << 8 | query batch, listed only where some item of
+  // the block has that many queries; blocks of pool items first, then blocks of self items
+  std::vector<int32_t> gm_rows;
+  int32_t gm_rows_off[7] = {0, 0, 0, 0, 0, 0, 0};   // table k is gm_rows[off[k] .. off[k+1])
+  int32_t gm_pool_rows[6] = {0, 0, 0, 0, 0, 0};     // rows of table k that belong to pool items
   // figures the attention calls need on every launch, taken once at build time
   int32_t gm_max_queries = 1;       // most queries any schedule item serves
   int64_t shortest_list = 0;        // fewest entries any Q tile lists
