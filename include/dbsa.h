@@ -116,9 +116,12 @@ typedef struct dbsa_layout dbsa_layout; /* opaque; owns host and device copies o
  *
  * flags: 0 or DBSA_LAYOUT_HOST_ONLY.  Without HOST_ONLY the lists are copied to
  * the current device with hipMemcpyAsync on `stream` (a hipStream_t, may be
- * NULL) and the stream is synchronised before returning.  The device block and its
- * pinned staging twin come from a process-wide free list that dbsa_layout_destroy
- * refills (blocks are kept until the process ends).
+ * NULL); the call does not wait for the copy.  An attention call on another
+ * stream is ordered behind the copy by the library (one hipStreamWaitEvent at
+ * the layout's first call on that stream).  The device block and its pinned
+ * staging twin come from a process-wide pool that dbsa_layout_destroy refills
+ * (at most 16 blocks are in flight before a build waits for the oldest one;
+ * blocks are kept until the process ends).
  * On success *out receives a layout to be released with dbsa_layout_destroy.
  * Errors: INVALID_ARG, BAD_BOUNDS, BAD_SELECTION, HIP; *out is untouched then.
  */
@@ -208,7 +211,12 @@ int dbsa_layout_export_decode_groups(const dbsa_layout* layout, const int64_t** 
  * of an owner first. */
 int dbsa_layout_export_order(const dbsa_layout* layout, const int32_t** order, int64_t* n_order);
 
-/* NULL is allowed.  Synchronises the device first (kernels may still be reading the lists). */
+/* NULL is allowed.  Does not wait for the device: it may be called right after the last launch
+ * that uses the layout.  The device lists stay intact until every stream the layout was used on
+ * has passed the point of this call (one event per such stream is recorded here, so those
+ * streams must still exist and must not be under graph capture); only then does a later
+ * dbsa_layout_build reuse the block.  If an event cannot be recorded the call falls back to
+ * hipDeviceSynchronize. */
 void dbsa_layout_destroy(dbsa_layout* layout);
 
 /*

@@ -16,17 +16,33 @@
 namespace {
 
 // Device blocks (with a pinned staging twin) are recycled between layouts: allocation
-// calls, not the copied bytes, dominate the cost of a layout build.  A block goes back to
-// the free list when its layout is destroyed, after a device synchronisation, so that no
-// kernel can still be reading the lists when the next layout overwrites them.
+// calls, not the copied bytes, dominate the cost of a layout build.  Nothing here waits for
+// the GPU: a destroyed layout's block goes back to the pool together with one event per stream
+// that read its lists (recorded at the destroy call), and is handed out again only once all of
+// them have completed, so a layout can be built, used and destroyed while earlier work is
+// still running.
 struct ListBlock {
   void* dev;
   void* pinned;
   size_t capacity;
   int device;
+  std::vector<hipEvent_t> busy;  // all complete => nothing reads dev or pinned any more
 };
 std::mutex g_pool_mutex;
-std::vector<ListBlock> g_free_blocks;
+std::vector<ListBlock> g_pool_blocks;
+// blocks kept per process before a build waits for the oldest busy one instead of allocating
+constexpr size_t kMaxPoolBlocks = 16;
+
+bool block_idle(ListBlock& blk) {
+  for (hipEvent_t ev : blk.busy)
+    if (hipEventQuery(ev) != hipSuccess) {
+      (void)hipGetLastError();  // "not ready" is an answer, not an error to leave behind for the caller
+      return false;
+    }
+  for (hipEvent_t ev : blk.busy) (void)hipEventDestroy(ev);
+  blk.busy.clear();
+  return true;
+}
 
 hipError_t acquire_block(size_t bytes, ListBlock* out) {
   int device = 0;
@@ -34,14 +50,30 @@ hipError_t acquire_block(size_t bytes, ListBlock* out) {
   if (e != hipSuccess) return e;
   {
     std::lock_guard<std::mutex> lock(g_pool_mutex);
-    for (size_t i = 0; i < g_free_blocks.size(); ++i)
-      if (g_free_blocks[i].device == device && g_free_blocks[i].capacity >= bytes) {
-        *out = g_free_blocks[i];
-        g_free_blocks.erase(g_free_blocks.begin() + static_cast<std::ptrdiff_t>(i));
-        return hipSuccess;
+    auto take = [&](size_t i) {
+      *out = g_pool_blocks[i];
+      g_pool_blocks.erase(g_pool_blocks.begin() + static_cast<std::ptrdiff_t>(i));
+    };
+    size_t fits = g_pool_blocks.size();
+    for (size_t i = 0; i < g_pool_blocks.size(); ++i)
+      if (g_pool_blocks[i].device == device && g_pool_blocks[i].capacity >= bytes) {
+        if (block_idle(g_pool_blocks[i])) {
+          take(i);
+          return hipSuccess;
+        }
+        if (fits == g_pool_blocks.size()) fits = i;  // the one destroyed first
       }
+    if (g_pool_blocks.size() >= kMaxPoolBlocks && fits < g_pool_blocks.size()) {
+      for (hipEvent_t ev : g_pool_blocks[fits].busy) {
+        e = hipEventSynchronize(ev);
+        if (e != hipSuccess) return e;
+      }
+      (void)block_idle(g_pool_blocks[fits]);
+      take(fits);
+      return hipSuccess;
+    }
   }
-  ListBlock blk{nullptr, nullptr, (bytes + bytes / 2 + 65535) / 65536 * 65536, device};
+  ListBlock blk{nullptr, nullptr, (bytes + bytes / 2 + 65535) / 65536 * 65536, device, {}};
   e = hipMalloc(&blk.dev, blk.capacity);
   if (e != hipSuccess) return e;
   e = hipHostMalloc(&blk.pinned, blk.capacity, hipHostMallocDefault);
@@ -55,7 +87,7 @@ hipError_t acquire_block(size_t bytes, ListBlock* out) {
 
 void release_block(const ListBlock& blk) {
   std::lock_guard<std::mutex> lock(g_pool_mutex);
-  g_free_blocks.push_back(blk);
+  g_pool_blocks.push_back(blk);
 }
 
 // Copy every list into ONE device block with a single asynchronous copy from pinned memory.
@@ -89,12 +121,24 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   put(o_gir, L->gm_item_run.data(), b_gir);
   put(o_grp, L->gm_ref_pad.data(), b_grp);
   put(o_grw, L->gm_rows.data(), b_grw);
-  e = hipMemcpyAsync(blk.dev, blk.pinned, total, hipMemcpyHostToDevice, stream);
-  if (e == hipSuccess) e = hipStreamSynchronize(stream);  // the staging twin may be reused after return
+  // the staging twin stays with the block, so nothing has to wait for the copy here; calls on
+  // other streams are ordered behind it through the event
+  hipEvent_t uploaded = nullptr;
+  e = hipEventCreateWithFlags(&uploaded, hipEventDisableTiming);
+  if (e == hipSuccess) {
+    e = hipMemcpyAsync(blk.dev, blk.pinned, total, hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess) e = hipEventRecord(uploaded, stream);
+    if (e != hipSuccess) {
+      (void)hipStreamSynchronize(stream);  // the copy may have been queued: the block must not be reused under it
+      (void)hipEventDestroy(uploaded);
+    }
+  }
   if (e != hipSuccess) {
     release_block(blk);
     return e;
   }
+  L->dev.upload_stream = stream;
+  L->dev.uploaded = uploaded;
   unsigned char* b = static_cast<unsigned char*>(blk.dev);
   L->dev.base = blk.dev;
   L->dev.staging = blk.pinned;
@@ -114,12 +158,58 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   return hipSuccess;
 }
 
-void free_device_lists(dbsa_device_lists& d) {
+// Hand the block back without waiting: one event per stream that read the lists, recorded now.
+void free_device_lists(dbsa_layout* L) {
+  dbsa_device_lists& d = L->dev;
   if (d.base) {
-    (void)hipDeviceSynchronize();  // nothing may still be reading the lists
-    release_block(ListBlock{d.base, d.staging, d.capacity, d.device});
+    int current = d.device;
+    (void)hipGetDevice(&current);
+    if (current != d.device) (void)hipSetDevice(d.device);
+    ListBlock blk{d.base, d.staging, d.capacity, d.device, {}};
+    std::vector<void*> streams;
+    {
+      std::lock_guard<std::mutex> lock(L->use_mutex);
+      streams = L->used_streams;
+    }
+    if (std::find(streams.begin(), streams.end(), d.upload_stream) == streams.end()) streams.push_back(d.upload_stream);
+    bool recorded = true;
+    for (void* s : streams) {
+      hipEvent_t ev = nullptr;
+      if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
+        recorded = false;
+        break;
+      }
+      blk.busy.push_back(ev);
+      if (hipEventRecord(ev, static_cast<hipStream_t>(s)) != hipSuccess) {
+        recorded = false;
+        break;
+      }
+    }
+    if (!recorded) {  // e.g. a stream that no longer exists: fall back to waiting for everything
+      (void)hipGetLastError();
+      (void)hipDeviceSynchronize();
+      for (hipEvent_t ev : blk.busy) (void)hipEventDestroy(ev);
+      blk.busy.clear();
+    }
+    if (d.uploaded) (void)hipEventDestroy(static_cast<hipEvent_t>(d.uploaded));
+    release_block(blk);
+    if (current != d.device) (void)hipSetDevice(current);
   }
   d = dbsa_device_lists{};
+}
+
+// First call of a layout on a stream other than the one its lists were copied on: order the
+// stream behind the copy.  Every stream is remembered for the destroy call.
+hipError_t order_behind_upload(const dbsa_layout* L, hipStream_t stream) {
+  std::lock_guard<std::mutex> lock(L->use_mutex);
+  void* s = stream;
+  if (std::find(L->used_streams.begin(), L->used_streams.end(), s) != L->used_streams.end()) return hipSuccess;
+  if (s != L->dev.upload_stream) {
+    const hipError_t e = hipStreamWaitEvent(stream, static_cast<hipEvent_t>(L->dev.uploaded), 0);
+    if (e != hipSuccess) return e;
+  }
+  L->used_streams.push_back(s);
+  return hipSuccess;
 }
 
 bool tensor_ok(const dbsa_tensor& t, int dtype) {
@@ -219,7 +309,8 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
   p.rope_table = rope_table;
   p.rope_n_pos = rope_n_pos;
   L->last_walk_reversed.store(0);  // prefill-shaped calls walk their lists front to back
-  hipError_t e;
+  hipError_t e = order_behind_upload(L, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return DBSA_ERR_HIP;
   if (dtype == DBSA_BF16) {
     if (!mfma_tile_sizes_ok(L)) return DBSA_ERR_UNSUPPORTED;
     p.heads_per_block = pick_heads_per_block(hq / hkv, L->block_m);
@@ -375,7 +466,7 @@ int dbsa_layout_export_order(const dbsa_layout* L, const int32_t** order, int64_
 
 void dbsa_layout_destroy(dbsa_layout* L) {
   if (!L) return;
-  if (L->on_device) free_device_lists(L->dev);
+  if (L->on_device) free_device_lists(L);
   delete L;
 }
 
@@ -454,6 +545,7 @@ int dbsa_decode_attn_kv8(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k
   p.partial = static_cast<float*>(workspace);
   p.decode_reverse = L->last_walk_reversed.fetch_xor(1) ^ 1;
   fill_decode_rows(p, L, r);
+  if (order_behind_upload(L, static_cast<hipStream_t>(stream)) != hipSuccess) return DBSA_ERR_HIP;
   return launch_decode_group_kv8(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;
 }
 
@@ -537,7 +629,8 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
   // (the query prefill walks forward): what the previous call read last is read first.
   p.decode_reverse = L->last_walk_reversed.fetch_xor(1) ^ 1;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e;
+  hipError_t e = order_behind_upload(L, s);
+  if (e != hipSuccess) return DBSA_ERR_HIP;
   if (dtype == DBSA_BF16) {
     if (L->block_n != 64 || n_q_heads / n_kv_heads > 32) return DBSA_ERR_UNSUPPORTED;
     const size_t need = dbsa_workspace_bytes(L, n_q_heads, head_dim);

@@ -4,6 +4,7 @@
 
 #include <atomic>
 #include <cstdint>
+#include <mutex>
 #include <vector>
 
 #include "../../include/dbsa.h"
@@ -24,6 +25,10 @@ struct dbsa_device_lists {
   int32_t* gm_item_run = nullptr; // [n_items][4]
   int32_t* gm_ref_pad = nullptr;  // [n_items][32][4]
   int32_t* gm_rows = nullptr;
+  // ordering of the asynchronous upload against the calls that read the lists (HIP handles kept
+  // as plain pointers so that host-only code can include this header)
+  void* upload_stream = nullptr;  // stream the lists were copied on
+  void* uploaded = nullptr;       // event recorded behind that copy
 };
 
 struct dbsa_layout {
@@ -77,6 +82,10 @@ struct dbsa_layout {
   // direction of the last walk over the pool's keys by an attention call on this layout (the
   // decode call alternates it); not part of the lists, hence mutable
   mutable std::atomic<int> last_walk_reversed{0};
+  // streams that attention calls have read the device lists on; the block that holds the lists
+  // is handed to another layout only when all of them have passed the point of the destroy call
+  mutable std::mutex use_mutex;
+  mutable std::vector<void*> used_streams;
 
   int64_t n_qtiles() const { return static_cast<int64_t>(qtile_tab.size() / 4); }
   int64_t n_ent() const { return static_cast<int64_t>(list_ent.size() / 2); }
