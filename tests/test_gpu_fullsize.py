@@ -70,8 +70,10 @@ def preencode_fullsize(pc, block_m, what):
     assert np.abs(oz[:, :, 2] - want[:, None]).max() <= 2 ** -8
 
 
-def test_config1_preencode_full_size():
-    preencode_fullsize(synth.config1_pool(), 256, "cfg1 pre-encode")
+@pytest.mark.parametrize("block_m", [128, 256])
+def test_config1_preencode_full_size(block_m):
+    """MHA: one head per workgroup, 4 or 8 row blocks of 32 tokens (two / one workgroup per CU)."""
+    preencode_fullsize(synth.config1_pool(), block_m, "cfg1 pre-encode")
 
 
 def test_config2_preencode_full_size():
