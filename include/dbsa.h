@@ -193,14 +193,15 @@ int dbsa_layout_export_positions(const dbsa_layout* layout, const int32_t** list
  *               (segment g+1) in seg_ent.
  *   seg_ent   : int32 [n_seg_ent][2], same encoding as list_ent, kinds all FULL.
  *   items     : int32 [n_items][4] = (ent_begin, ent_count, qref_begin, n_q).  Order:
- *               segments ascending (those with a user), runs of chunk_tiles tiles
- *               ascending, users in ascending query order in batches of 32.  The sink's
- *               users are all queries.
+ *               segments ascending (those with a user), runs ascending (a segment of t
+ *               tiles is cut into n = ceil(t / chunk_tiles) runs of equal length to within
+ *               one tile, run i = tiles [i t / n, (i+1) t / n)), users in ascending query
+ *               order in batches of 32.  The sink's users are all queries.
  *   qrefs     : int32 [n_qrefs][2] = (query, slot).
  *   slot_ptr  : int64 [B+1]: slots of query u are slot_ptr[u] .. slot_ptr[u+1]-1, numbered
  *               in item order; the last one is the own-cache slot.
- *   chunk_tiles: tiles per run: ceil(longest segment with a user / n_split) when the
- *               caller gave n_split > 0, else chosen by the library.
+ *   chunk_tiles: most tiles per run: ceil(longest segment with a user / n_split) when the
+ *               caller gave n_split > 0, else chosen by the library (at most 32).
  */
 int dbsa_layout_export_decode_groups(const dbsa_layout* layout, const int64_t** seg_ptr, const int32_t** seg_ent,
                                      int64_t* n_seg_ent, const int32_t** items, int64_t* n_items,

@@ -127,9 +127,10 @@ def decode_layout(sink_len, demo_offsets, group_demo_offsets, n_queries, sel_ptr
 def decode_group_schedule(sink_len, demo_offsets, group_demo_offsets, n_queries, sel_ptr, sel_idx, block_n,
                           chunk_tiles, item_queries=32):
     """Group-major decode schedule derived from the visibility predicate: a segment (the
-    sink, a group) is used by the queries that see its keys; every run of ``chunk_tiles`` KV
-    tiles of a used segment is one item per batch of ``item_queries`` users (ascending query
-    order); every (item, user) pair takes the user's next slot; a query's last slot is for
+    sink, a group) is used by the queries that see its keys; the t KV tiles of a used segment are
+    cut into ceil(t / chunk_tiles) runs of equal length to within one tile (run i = tiles
+    [i t / n, (i+1) t / n)), and every run is one item per batch of ``item_queries`` users
+    (ascending query order); every (item, user) pair takes the user's next slot; a query's last slot is for
     its own cached keys.  -> dict like the library's export."""
     _, group_of = orc.token_maps(sink_len, demo_offsets, group_demo_offsets)
     segs = _segments(sink_len, demo_offsets, group_demo_offsets)
@@ -144,8 +145,11 @@ def decode_group_schedule(sink_len, demo_offsets, group_demo_offsets, n_queries,
         users = [u for u in range(n_queries) if b > a and vis[u][a:b].any()]
         for u in users:
             assert vis[u][a:b].all()
-        for c0 in range(seg_ptr[s], seg_ptr[s + 1], chunk_tiles):
-            cn = min(chunk_tiles, seg_ptr[s + 1] - c0)
+        t0, t = seg_ptr[s], seg_ptr[s + 1] - seg_ptr[s]
+        n_runs = -(-t // chunk_tiles)
+        for run in range(n_runs):
+            c0, c1 = t0 + (run * t) // n_runs, t0 + ((run + 1) * t) // n_runs
+            cn = c1 - c0
             for b0 in range(0, len(users), item_queries):
                 uses.append((c0, cn, users[b0:b0 + item_queries]))
                 for u in users[b0:b0 + item_queries]:

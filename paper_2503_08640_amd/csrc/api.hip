@@ -642,7 +642,18 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
                                         std::max(p.k_self.stride_tok, p.v_self.stride_tok));
     if (head_dim == 128 && 32 % r == 0 && max_stride < (int64_t{1} << 24)) {
       // every KV run is walked once for all the queries that selected it
-      fill_decode_rows(p, L, r);
+      // Items that serve several batches of 32 / r queries: the batches of one item run as waves
+      // of ONE workgroup that share its tiles in LDS, once a key is walked often enough for that
+      // to outweigh the barrier per half tile (measured: 2 waves from ~2 walks per key on, 4 from 2.5).
+      p.decode_waves = 1;
+      {
+        int k = 0;
+        while ((32 >> k) > 32 / r) ++k;
+        const float walks = L->gm_walks_per_key[k];
+        if (r % 4 == 0 && walks >= 2.5f) p.decode_waves = 4;
+        else if (r % 2 == 0 && walks >= 1.9f) p.decode_waves = 2;
+      }
+      fill_decode_rows(p, L, r / p.decode_waves);
       e = launch_decode_group(p, s);
     } else {
       if (rope_table) return DBSA_ERR_UNSUPPORTED;  // only the group-major kernel re-positions

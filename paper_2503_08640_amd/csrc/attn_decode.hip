@@ -79,6 +79,52 @@ __device__ inline void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
+// The 8 B-operand fragments of one score column: the query row (qp points at this lane's first
+// channel, 8 * half), pre-multiplied by scale * log2 e.  ROPE: the row is stored un-rotated and is
+// rotated here with the table row `rot` (16 floats = cos, sin of 8 channel pairs per (chunk, half)).
+template <bool ROPE>
+__device__ inline void load_query_fragments(const __bf16* qp, const float* rot, float c2, bf16x8 (&qf)[kD / 16]) {
+  if (ROPE) {
+    // channel d < 64 of chunk c pairs with channel d + 64 of chunk c + 4, both held by this lane
+#pragma unroll
+    for (int c = 0; c < kD / 32; ++c) {
+      const bf16x8 lo = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
+      const bf16x8 hi = *reinterpret_cast<const bf16x8*>(qp + 16 * (c + kD / 32));
+      floatx4 cs[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) cs[j] = *reinterpret_cast<const floatx4*>(rot + 32 * c + 4 * j);
+      union {
+        bf16x8 v;
+        bf16x2 p2[4];
+      } a, b;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float x0 = static_cast<float>(lo[2 * e]), y0 = static_cast<float>(hi[2 * e]);
+        const float x1 = static_cast<float>(lo[2 * e + 1]), y1 = static_cast<float>(hi[2 * e + 1]);
+        const float c0 = cs[e][0] * c2, s0 = cs[e][1] * c2, c1 = cs[e][2] * c2, s1 = cs[e][3] * c2;
+        a.p2[e] = __builtin_convertvector(floatx2{x0 * c0 - y0 * s0, x1 * c1 - y1 * s1}, bf16x2);
+        b.p2[e] = __builtin_convertvector(floatx2{y0 * c0 + x0 * s0, y1 * c1 + x1 * s1}, bf16x2);
+      }
+      qf[c] = a.v;
+      qf[c + kD / 32] = b.v;
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < kD / 16; ++c) {
+      const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
+      union {
+        bf16x8 v;
+        bf16x2 p2[4];
+      } sc;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        sc.p2[e] = __builtin_convertvector(
+            floatx2{static_cast<float>(raw[2 * e]) * c2, static_cast<float>(raw[2 * e + 1]) * c2}, bf16x2);
+      qf[c] = sc.v;
+    }
+  }
+}
+
 // ROPE: the query row is un-rotated and is rotated here at the id that stands for the new
 // in-order position of the item's keys (Sec. 2.2), see AttnParams::gm_ref_pad.
 template <bool ROPE>
@@ -240,45 +286,7 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
     issue_v(0);
     if (1 < n_half) issue_k(1);
     bf16x8 qf[kD / 16];
-    if (ROPE) {
-      // channel d < 64 of chunk c pairs with channel d + 64 of chunk c + 4, both held by this lane
-#pragma unroll
-      for (int c = 0; c < kD / 32; ++c) {
-        const bf16x8 lo = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
-        const bf16x8 hi = *reinterpret_cast<const bf16x8*>(qp + 16 * (c + kD / 32));
-        floatx4 cs[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) cs[j] = *reinterpret_cast<const floatx4*>(rot + 32 * c + 4 * j);
-        union {
-          bf16x8 v;
-          bf16x2 p2[4];
-        } a, b;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float x0 = static_cast<float>(lo[2 * e]), y0 = static_cast<float>(hi[2 * e]);
-          const float x1 = static_cast<float>(lo[2 * e + 1]), y1 = static_cast<float>(hi[2 * e + 1]);
-          const float c0 = cs[e][0] * c2, s0 = cs[e][1] * c2, c1 = cs[e][2] * c2, s1 = cs[e][3] * c2;
-          a.p2[e] = __builtin_convertvector(floatx2{x0 * c0 - y0 * s0, x1 * c1 - y1 * s1}, bf16x2);
-          b.p2[e] = __builtin_convertvector(floatx2{y0 * c0 + x0 * s0, y1 * c1 + x1 * s1}, bf16x2);
-        }
-        qf[c] = a.v;
-        qf[c + kD / 32] = b.v;
-      }
-    } else {
-#pragma unroll
-      for (int c = 0; c < kD / 16; ++c) {
-        const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
-        union {
-          bf16x8 v;
-          bf16x2 p2[4];
-        } sc;
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          sc.p2[e] = __builtin_convertvector(
-              floatx2{static_cast<float>(raw[2 * e]) * c2, static_cast<float>(raw[2 * e + 1]) * c2}, bf16x2);
-        qf[c] = sc.v;
-      }
-    }
+    load_query_fragments<ROPE>(qp, rot, c2, qf);
     floatx16 o[kD / 32];
 #pragma unroll
     for (int ob = 0; ob < kD / 32; ++ob)
@@ -369,6 +377,240 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
         part[kD] = m_run;
         part[kD + 1] = l_tot;
       }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same walk for layouts whose items serve MORE queries than one wave has columns (many
+// concurrent queries, high retrieval ratios): the W waves of a workgroup take W consecutive query
+// batches of one item and share every half tile in LDS, so the keys travel from L2 to LDS once
+// per W batches instead of once per batch.  Each wave issues 1/W of a tile's load instructions
+// and waits for its own; ONE barrier per half tile then makes the tile visible to all waves and
+// tells that every wave is done with the tile before, whose slot takes the loads of the tile two
+// places on.  Ring of three (K, V) pairs of half tiles: two pairs in flight while one is used.
+constexpr int kPairs = 3;
+constexpr int kPairBytes = 2 * kHalfBytes;       // 16 KiB
+constexpr int kLdsShared = kPairs * kPairBytes;  // 48 KiB per workgroup: three workgroups per CU
+
+template <int W, bool ROPE>
+__global__ __launch_bounds__(64 * W) void decode_group_shared_kernel(AttnParams p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  lds_byte* lds = (lds_byte*)smem;
+  constexpr int kPerWave = kLoadsPerGroup / W;  // load instructions per wave per K or V half tile
+  static_assert(kLoadsPerGroup % W == 0, "waves share the load instructions evenly");
+  const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) / 64);
+  const int lane = threadIdx.x % 64, l32 = lane % 32, half = lane / 32;
+  const int r = p.n_q_heads / p.n_kv_heads;
+  const int qpw = 32 / r;  // queries per wave
+  // workgroup id -> (KV head, launch row, item of the row's block of 8) as in decode_group_kernel;
+  // a row's batch counts batches of W * qpw queries here
+  const int in_block = blockIdx.x % 8;
+  const int row_id = (blockIdx.x / 8) % p.launch_rows, hk = (blockIdx.x / 8) / p.launch_rows;
+  typedef const __attribute__((address_space(4))) int32_t* const_words;
+  const int row = ((const_words)(reinterpret_cast<uintptr_t>(p.gm_rows)))[p.row_offset + row_id];
+  const int wg_batch = row & 0xFF, block = row >> 8;
+  const bool self_item = block >= p.n_pool_blocks;
+  const int item = self_item ? p.n_gm_items + 8 * (block - p.n_pool_blocks) + in_block : 8 * block + in_block;
+  if (item >= (self_item ? p.n_gm_items + p.n_queries : p.n_gm_items)) return;
+  const const_words runs = (const_words)(reinterpret_cast<uintptr_t>(p.gm_item_run));
+  int n_q = 1, first_key = 0, n_keys = 0, self_u = 0;
+  if (!self_item) {
+    first_key = runs[4 * item + 0];
+    n_keys = runs[4 * item + 1];
+    n_q = runs[4 * item + 2];
+  } else {
+    self_u = item - p.n_gm_items;
+    n_keys = __builtin_amdgcn_readfirstlane(p.self_len[self_u]);
+  }
+  const int n_half = (n_keys + kHalf - 1) / kHalf;
+  const int n_pass = (n_q + qpw - 1) / qpw;
+  // (everything up to here is the same for all waves: the workgroup leaves as one)
+  if (wg_batch * W >= n_pass) return;
+  const int pass = wg_batch * W + wave;
+  const bool active = pass < n_pass;  // a wave without a batch still loads its share and keeps the barriers
+
+  const __bf16* kbase = self_item ? static_cast<const __bf16*>(p.k_self.ptr) + self_u * p.stride_query +
+                                        hk * p.k_self.stride_head
+                                  : static_cast<const __bf16*>(p.k_pool.ptr) + hk * p.k_pool.stride_head;
+  const __bf16* vbase = self_item ? static_cast<const __bf16*>(p.v_self.ptr) + self_u * p.stride_query +
+                                        hk * p.v_self.stride_head
+                                  : static_cast<const __bf16*>(p.v_pool.ptr) + hk * p.v_pool.stride_head;
+  const int k_stride = static_cast<int>(self_item ? p.k_self.stride_tok : p.k_pool.stride_tok);
+  const int v_stride = static_cast<int>(self_item ? p.v_self.stride_tok : p.v_pool.stride_tok);
+  auto half_ref = [&](int hh, int& start, int& len) {
+    const int pos = p.decode_reverse ? n_half - 1 - hh : hh;
+    start = first_key + pos * kHalf;
+    len = min(kHalf, n_keys - pos * kHalf);
+  };
+
+  // this wave's load instructions of a half tile are the 1-KiB blocks b = wave + W * j (rows
+  // 4b .. 4b+3; lane -> row 4b + lane/16, 16-byte slot lane%16, swizzled as in decode_group_kernel)
+  unsigned k_lane_off[kPerWave];
+#pragma unroll
+  for (int j = 0; j < kPerWave; ++j)
+    k_lane_off[j] = static_cast<unsigned>((lane / 16) * k_stride +
+                                          (((lane % 16) ^ (4 * ((wave + W * j) % 4) + lane / 16)) * 8)) * 2u;
+  const unsigned v_lane_off =
+      static_cast<unsigned>((lane / 16) * v_stride + (((lane % 16) ^ (4 * ((lane / 16) % 4))) * 8)) * 2u;
+  auto issue_pair = [&](int hh) {
+    int start, len;
+    half_ref(hh, start, len);
+    lds_byte* k_stage = lds + (hh % kPairs) * kPairBytes;
+    lds_byte* v_stage = k_stage + kHalfBytes;
+    const __bf16* kb = kbase + static_cast<int64_t>(start) * k_stride;
+    const __bf16* vb = vbase + static_cast<int64_t>(start) * v_stride;
+    if (len == kHalf) {
+#pragma unroll
+      for (int j = 0; j < kPerWave; ++j) {
+        const int b = wave + W * j;
+        dma16(kb + static_cast<int64_t>(4 * b) * k_stride, k_lane_off[j], k_stage + b * 1024);
+      }
+#pragma unroll
+      for (int j = 0; j < kPerWave; ++j) {
+        const int b = wave + W * j;
+        dma16(vb + static_cast<int64_t>(4 * b) * v_stride, v_lane_off, v_stage + b * 1024);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < kPerWave; ++j) {
+        const int b = wave + W * j;
+        const int row_in = 4 * b + lane / 16;
+        const int row_k = min(row_in, len - 1);  // rows past the tail repeat the last key
+        dma16(kb, static_cast<unsigned>(row_k * k_stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u,
+              k_stage + b * 1024);
+      }
+#pragma unroll
+      for (int j = 0; j < kPerWave; ++j) {
+        const int b = wave + W * j;
+        const int row_in = 4 * b + lane / 16;
+        const int row_v = min(row_in, len - 1);
+        dma16(vb, static_cast<unsigned>(row_v * v_stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u,
+              v_stage + b * 1024);
+      }
+    }
+  };
+
+  const int k_base = l32 * kRowBytes + ((half ^ (l32 % 16)) * 16);
+  const int v_base = (4 * half + (lane % 16) / 4) * kRowBytes +
+                     (((2 * (l32 / 16) + (lane % 4) / 2) ^ (4 * ((lane % 16) / 4))) * 16) + (lane % 2) * 8;
+  const float c2 = p.scale_log2e;
+
+  // ---- this lane's column: query and head ----
+  const int q_local = pass * qpw + l32 / r;  // index into the item's query list (< 32 also without a batch)
+  const bool col_valid = active && q_local < n_q;
+  int u = self_u, slot, rot_id = 0;
+  if (self_item) {
+    slot = static_cast<int>(p.gm_slot_ptr[self_u + 1]) - 1;
+  } else {
+    typedef int intx4 __attribute__((ext_vector_type(4)));
+    const intx4 ref = *reinterpret_cast<const intx4*>(p.gm_ref_pad + (static_cast<int64_t>(item) * 32 + q_local) * 4);
+    u = ref[0];
+    slot = ref[1];
+    if (ROPE) rot_id = ref[2];
+  }
+  const int head = hk * r + l32 % r;
+  const float* rot = nullptr;
+  if (ROPE) {
+    rot_id = min(max(rot_id + p.self_len[u] - 1, 0), p.rope_n_pos - 1);
+    rot = p.rope_table + static_cast<int64_t>(rot_id) * kD + 16 * half;
+    asm volatile("" : "+v"(rot));
+  }
+  const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
+                     static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
+  asm volatile("" : "+v"(qp));
+
+  issue_pair(0);
+  if (1 < n_half) issue_pair(1);
+  bf16x8 qf[kD / 16];
+  load_query_fragments<ROPE>(qp, rot, c2, qf);
+  floatx16 o[kD / 32];
+#pragma unroll
+  for (int ob = 0; ob < kD / 32; ++ob)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[ob][i] = 0.f;
+  float m_run = -1.0e30f, l_run = 0.f;
+
+  for (int hh = 0; hh < n_half; ++hh) {
+    // this wave's part of pair hh has landed once only its part of pair hh+1 is outstanding
+    if (hh + 1 < n_half) wait_vmcnt<2 * kPerWave>();
+    else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    // every wave is past pair hh-1: its slot takes pair hh+2
+    if (hh + 2 < n_half) issue_pair(hh + 2);
+    if (!active) continue;
+    int start, len;
+    half_ref(hh, start, len);
+    const lds_byte* ks = lds + (hh % kPairs) * kPairBytes;
+    const lds_byte* vs = ks + kHalfBytes;
+
+    floatx16 s, s2;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = 0.f, s2[i] = 0.f;
+#pragma unroll
+    for (int c = 0; c < kD / 16; c += 2) {
+      const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * c)));
+      const bf16x8 a2 =
+          *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * (c + 1))));
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[c], s, 0, 0, 0);
+      s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, qf[c + 1], s2, 0, 0, 0);
+    }
+    s += s2;
+    if (len < kHalf) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key_local = 8 * (i / 4) + 4 * half + (i % 4);
+        s[i] = key_local < len ? s[i] : -INFINITY;
+      }
+    }
+    float mx = s[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+    mx = half_swap_max(mx);
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int ob = 0; ob < kD / 32; ++ob) o[ob] *= alpha;
+    }
+    union {
+      bf16x8 v[2];
+      bf16x2 p2[8];
+    } pf;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float p0 = __builtin_amdgcn_exp2f(s[2 * i] - m_run);
+      const float p1 = __builtin_amdgcn_exp2f(s[2 * i + 1] - m_run);
+      pf.p2[i] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);
+      l_run += p0 + p1;
+    }
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+      for (int ob = 0; ob < kD / 32; ++ob) {
+        const lds_byte* vp = vs + (v_base ^ (64 * ob)) + 16 * ch * kRowBytes;
+        const bf16x4 lo = lds_read_tr(vp);
+        const bf16x4 hi = lds_read_tr(vp + 8 * kRowBytes);
+        const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf.v[ch], o[ob], 0, 0, 0);
+      }
+  }
+
+  // ---- partial state of every valid column ----
+  const float l_tot = half_swap_sum(l_run);
+  if (col_valid) {
+    float* part = p.partial + (static_cast<int64_t>(slot) * p.n_q_heads + head) * (kD + kPartialPad);
+#pragma unroll
+    for (int ob = 0; ob < kD / 32; ++ob)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<floatx4*>(part + 32 * ob + 8 * g + 4 * half) =
+            floatx4{o[ob][4 * g], o[ob][4 * g + 1], o[ob][4 * g + 2], o[ob][4 * g + 3]};
+    if (half == 0) {
+      part[kD] = m_run;
+      part[kD + 1] = l_tot;
     }
   }
 }
@@ -680,7 +922,6 @@ hipError_t launch_decode_group_kv8(const AttnParams& p_in, hipStream_t stream) {
     attr_set = true;
   }
   AttnParams p = p_in;
-  const int qpw = 32 / (p.n_q_heads / p.n_kv_heads);
   if (p.n_gm_items > 0) {
     p.row_offset = 0;
     p.launch_rows = p.gm_pool_rows;
@@ -698,6 +939,30 @@ hipError_t launch_decode_group_kv8(const AttnParams& p_in, hipStream_t stream) {
   return hipGetLastError();
 }
 
+namespace {
+template <int W>
+hipError_t launch_shared(const AttnParams& p, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_shared_kernel<W, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsShared);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_shared_kernel<W, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsShared);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const dim3 grid = decode_grid(p), block(64 * W);
+  if (p.rope_table)
+    decode_group_shared_kernel<W, true><<<grid, block, kLdsShared, stream>>>(p);
+  else
+    decode_group_shared_kernel<W, false><<<grid, block, kLdsShared, stream>>>(p);
+  return hipGetLastError();
+}
+}  // namespace
+
+// p.decode_waves = waves per workgroup (1, 2 or 4; the launch rows in p are those of batches of
+// decode_waves * 32 / r queries)
 hipError_t launch_decode_group(const AttnParams& p_in, hipStream_t stream) {
   AttnParams p = p_in;
   static bool attr_set = false;
@@ -710,15 +975,21 @@ hipError_t launch_decode_group(const AttnParams& p_in, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int qpw = 32 / (p.n_q_heads / p.n_kv_heads);
   p.row_offset = 0;
   p.launch_rows = p.gm_n_rows;
-  const dim3 grid = decode_grid(p), block(64);
-  if (p.rope_table)
-    decode_group_kernel<true><<<grid, block, kLdsBytes, stream>>>(p);
-  else
-    decode_group_kernel<false><<<grid, block, kLdsBytes, stream>>>(p);
-  hipError_t e = hipGetLastError();
+  hipError_t e;
+  if (p.decode_waves == 4) {
+    e = launch_shared<4>(p, stream);
+  } else if (p.decode_waves == 2) {
+    e = launch_shared<2>(p, stream);
+  } else {
+    const dim3 grid = decode_grid(p), block(64);
+    if (p.rope_table)
+      decode_group_kernel<true><<<grid, block, kLdsBytes, stream>>>(p);
+    else
+      decode_group_kernel<false><<<grid, block, kLdsBytes, stream>>>(p);
+    e = hipGetLastError();
+  }
   if (e != hipSuccess) return e;
   decode_group_merge_kernel<<<dim3(p.n_queries * p.n_q_heads), dim3(kD), 0, stream>>>(p);
   return hipGetLastError();

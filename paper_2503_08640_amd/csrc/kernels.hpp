@@ -50,6 +50,7 @@ struct AttnParams {
   const float* k_scale8;      // decode over an fp8 pool: k = k8 * k_scale8[kv head], v = v8 * v_scale8[kv head]
   const float* v_scale8;
   int32_t decode_reverse;     // decode: walk every run of keys from its last half tile to its first
+  int32_t decode_waves;       // decode: waves per workgroup that share an item's tiles (1, 2 or 4)
   int32_t q_split;            // prefill: runs each Q tile's list is cut into (1 = no split, no merge pass)
   int32_t n_rows;             // prefill: rows of q / o
   // shapes

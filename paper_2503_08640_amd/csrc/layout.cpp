@@ -237,7 +237,7 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
       tile_batches += t * ((static_cast<int64_t>(users[s].size()) + kItemQueries - 1) / kItemQueries);
     }
     int64_t chunk = sel->n_split > 0 ? (max_tiles + sel->n_split - 1) / sel->n_split
-                                     : std::min<int64_t>(16, (tile_batches + 143) / 144);
+                                     : std::min<int64_t>(32, (tile_batches + 143) / 144);
     chunk = std::max<int64_t>(1, chunk);
     L->gm_chunk_tiles = static_cast<int32_t>(chunk);
     // displacement of segment s for user u, as in list_shift but without a tile offset
@@ -262,12 +262,16 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
       for (int32_t s = 0; s <= G; ++s) {
         const int64_t t0 = L->gm_seg_ptr[s], t1 = L->gm_seg_ptr[s + 1];
         if (users[s].empty()) continue;
-        for (int64_t c0 = t0; c0 < t1; c0 += chunk)
+        // the segment's tiles are cut into ceil(tiles / chunk) runs of equal length (to within one
+        // tile): a short last run would leave its workgroup idle while the full ones finish
+        const int64_t n_runs = (t1 - t0 + chunk - 1) / chunk;
+        for (int64_t run = 0; run < n_runs; ++run) {
+          const int64_t c0 = t0 + run * (t1 - t0) / n_runs, c1 = t0 + (run + 1) * (t1 - t0) / n_runs;
           for (size_t b0 = 0; b0 < users[s].size(); b0 += kItemQueries) {
             const size_t b1 = std::min(users[s].size(), b0 + kItemQueries);
             if (pass == 1)
               L->gm_items.insert(L->gm_items.end(),
-                                 {static_cast<int32_t>(c0), static_cast<int32_t>(std::min(chunk, t1 - c0)),
+                                 {static_cast<int32_t>(c0), static_cast<int32_t>(c1 - c0),
                                   static_cast<int32_t>(L->gm_qrefs.size() / 2), static_cast<int32_t>(b1 - b0)});
             for (size_t k = b0; k < b1; ++k) {
               const int32_t u = users[s][k];
@@ -280,6 +284,7 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
               }
             }
           }
+        }
       }
     }
   }
@@ -319,6 +324,14 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
         for (int32_t z = 0; z * per_wave < most; ++z) L->gm_rows.push_back((b << 8) | z);
       }
       L->gm_pool_rows[k] = static_cast<int32_t>(L->gm_rows.size()) - L->gm_rows_off[k];
+      // how often a key of the pool items is walked when a wave takes per_wave queries
+      double keys = 0.0, walked = 0.0;
+      for (int32_t it = 0; it < n_items; ++it) {
+        const double n = L->gm_item_run[4 * it + 1];
+        keys += n;
+        walked += n * ((L->gm_item_run[4 * it + 2] + per_wave - 1) / per_wave);
+      }
+      L->gm_walks_per_key[k] = keys > 0.0 ? static_cast<float>(walked / keys) : 1.f;
       for (int32_t b = 0; b < self_blocks; ++b) L->gm_rows.push_back((pool_blocks + b) << 8);
     }
     L->gm_rows_off[6] = static_cast<int32_t>(L->gm_rows.size());

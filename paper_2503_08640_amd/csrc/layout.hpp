@@ -73,6 +73,7 @@ struct dbsa_layout {
   std::vector<int32_t> gm_rows;
   int32_t gm_rows_off[7] = {0, 0, 0, 0, 0, 0, 0};   // table k is gm_rows[off[k] .. off[k+1])
   int32_t gm_pool_rows[6] = {0, 0, 0, 0, 0, 0};     // rows of table k that belong to pool items
+  float gm_walks_per_key[6] = {1, 1, 1, 1, 1, 1};   // batches per pool item at 32 >> k queries per wave, weighted by keys
   // figures the attention calls need on every launch, taken once at build time
   int32_t gm_max_queries = 1;       // most queries any schedule item serves
   int64_t shortest_list = 0;        // fewest entries any Q tile lists

@@ -94,6 +94,17 @@ def test_repositioned_query_and_decode_small(hq, hkv, block_m, base):
     _repositioned_case(pc, qc, block_m, base, decode_steps=range(3), what=f"Hq={hq} Hkv={hkv}")
 
 
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 2), (16, 2)])
+def test_repositioned_decode_with_many_queries_per_group(hq, hkv):
+    """40 queries on 3 groups: every group serves several batches of 32 / r queries, so the
+    decode step runs the kernel whose waves share an item's tiles (2 or 4 waves per workgroup)."""
+    pc = synth.make_pool_case("ropemany", 4020 + hq, dtype="bf16", n_q_heads=hq, n_kv_heads=hkv, head_dim=128,
+                              sink_len=40, pool_tokens=2500, demo_len_range=(30, 120), n_groups=3,
+                              k_channel_sigma=0.5)
+    qc = synth.make_query_case("ropemanyq", 4021, pc, n_queries=40, q_len=9, n_select=2, n_decode=2)
+    _repositioned_case(pc, qc, 32, 10000.0, decode_steps=range(2), what=f"many queries Hq={hq} Hkv={hkv}")
+
+
 def test_repositioned_stage_matches_the_position_free_stage_when_ids_do_not_move():
     """All groups in pool order: new ids = encoding ids, so the re-positioned calls must agree
     with the position-free calls on explicitly rotated inputs (same kernels, other code path)."""

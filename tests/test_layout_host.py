@@ -213,6 +213,22 @@ def test_query_and_decode_lists_match_oracle_on_random_inputs(seed):
                                     bn, got["chunk_tiles"])
     for key in ("seg_ptr", "seg_ent", "items", "qrefs", "slot_ptr"):
         assert got[key].dtype == want[key].dtype and np.array_equal(got[key], want[key]), key
+    # what any valid schedule must satisfy, whatever the cutting rule: every (used segment, user)
+    # pair sees each tile of the segment exactly once, runs stay inside a segment, hold at most
+    # chunk_tiles tiles, are as few as that allows and differ by at most one tile within a segment
+    seen = {}
+    for (c0, cn, r0, nu) in got["items"].tolist():
+        s = int(np.searchsorted(got["seg_ptr"], c0, side="right")) - 1
+        assert got["seg_ptr"][s] <= c0 and c0 + cn <= got["seg_ptr"][s + 1] and 1 <= cn <= got["chunk_tiles"]
+        for (u, _) in got["qrefs"][r0:r0 + nu].tolist():
+            seen.setdefault((s, u), []).append((c0, cn))
+    for u in range(nq):
+        mine = [0] * (pool.sink_len > 0) + [int(g) + 1 for g in sels[u]]
+        assert sorted(s for (s, v) in seen if v == u) == sorted(s for s in mine if segs[s] > 0)
+    for (s, u), runs in seen.items():
+        assert [c0 for c0, _ in runs] == list(np.cumsum([got["seg_ptr"][s]] + [cn for _, cn in runs[:-1]]))
+        assert sum(cn for _, cn in runs) == segs[s] and len(runs) == -(-int(segs[s]) // got["chunk_tiles"])
+        assert max(cn for _, cn in runs) - min(cn for _, cn in runs) <= 1
 
 
 def test_config0_lists_match_oracle_and_counts():
@@ -335,7 +351,7 @@ def test_group_major_schedule_batches_users_and_defaults_to_a_bounded_chunk():
                                     got["chunk_tiles"])
     for key in ("seg_ptr", "seg_ent", "items", "qrefs", "slot_ptr"):
         assert np.array_equal(got[key], want[key]), key
-    assert 1 <= got["chunk_tiles"] <= 16
+    assert 1 <= got["chunk_tiles"] <= 32
     assert sorted(got["items"][:, 3].tolist()) == [8, 8, 8, 32, 32, 32]  # the sink tile and the two tiles of group 1
     slots = np.sort(got["qrefs"][:, 1])
     own = got["slot_ptr"][1:] - 1
