@@ -373,6 +373,19 @@ int dbsa_decode_attn_kv8(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_ten
                          int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, float softmax_scale,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * dbsa_decode_attn_kv8 with re-positioning (Sec. 2.2), as dbsa_decode_attn_rope: q_step is
+ * UN-rotated, the pool keys were rotated at their encoding ids BEFORE they were quantised, the
+ * self caches hold bf16 keys rotated at their index inside the query; rope_table / rope_n_pos
+ * as there.  Errors as both.
+ */
+int dbsa_decode_attn_kv8_rope(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_tensor k_selfcache,
+                              dbsa_tensor v_selfcache, const int32_t* self_len, int64_t stride_query,
+                              dbsa_tensor k_pool8, dbsa_tensor v_pool8, const float* k_scale, const float* v_scale,
+                              dbsa_tensor o, const float* rope_table, int32_t rope_n_pos, int32_t n_q_heads,
+                              int32_t n_kv_heads, int32_t head_dim, float softmax_scale, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

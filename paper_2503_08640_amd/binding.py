@@ -38,7 +38,7 @@ EXPORTED_SYMBOLS = (
     "dbsa_strerror", "dbsa_layout_build", "dbsa_layout_build_append", "dbsa_layout_export", "dbsa_layout_export_decode",
     "dbsa_layout_export_decode_groups", "dbsa_layout_export_order", "dbsa_layout_export_positions", "dbsa_layout_destroy", "dbsa_workspace_bytes", "dbsa_preencode_attn",
     "dbsa_query_attn", "dbsa_decode_attn", "dbsa_rope_table", "dbsa_rope_apply", "dbsa_query_attn_rope",
-    "dbsa_decode_attn_rope", "dbsa_decode_attn_kv8",
+    "dbsa_decode_attn_rope", "dbsa_decode_attn_kv8", "dbsa_decode_attn_kv8_rope",
 )
 
 
@@ -125,6 +125,10 @@ def lib() -> C.CDLL:
     L.dbsa_decode_attn.restype = C.c_int
     L.dbsa_decode_attn.argtypes = [C.c_void_p, Tensor, Tensor, Tensor, C.c_void_p, C.c_int64, Tensor, Tensor,
                                    Tensor] + tail
+    L.dbsa_decode_attn_kv8_rope.restype = C.c_int
+    L.dbsa_decode_attn_kv8_rope.argtypes = [C.c_void_p, Tensor, Tensor, Tensor, C.c_void_p, C.c_int64, Tensor, Tensor,
+                                            C.c_void_p, C.c_void_p, Tensor, C.c_void_p, C.c_int32, C.c_int32,
+                                            C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
     _lib = L
     return L
 
@@ -406,9 +410,11 @@ def dbsa_decode_attn_rope(layout: Layout, q_step, k_cache, v_cache, self_len, k_
 
 
 def dbsa_decode_attn_kv8(layout: Layout, q_step, k_cache, v_cache, self_len, k_pool8, v_pool8, k_scale, v_scale,
-                         scale: float, out=None, workspace=None):
+                         scale: float, out=None, workspace=None, rope_table=None):
     """One decode step over an fp8 (e4m3) pool: k_pool8 / v_pool8 are [N, Hkv, D] float8_e4m3fn (or uint8)
-    device tensors, k_scale / v_scale float32 [Hkv] on the device; everything else as dbsa_decode_attn."""
+    device tensors, k_scale / v_scale float32 [Hkv] on the device; everything else as dbsa_decode_attn.
+    With ``rope_table`` the step re-positions (dbsa_decode_attn_kv8_rope): q_step un-rotated, pool keys
+    rotated at their encoding ids before quantisation."""
     import torch
     assert k_cache.dim() == 4 and k_cache.stride(3) == 1 and v_cache.stride() == k_cache.stride()
     assert k_pool8.element_size() == 1 and k_pool8.dim() == 3 and k_pool8.stride(2) == 1
@@ -416,6 +422,15 @@ def dbsa_decode_attn_kv8(layout: Layout, q_step, k_cache, v_cache, self_len, k_p
     ws, ws_ptr, ws_bytes = _workspace(layout, q_step, workspace)
     kc = Tensor(k_cache.data_ptr(), k_cache.stride(1), k_cache.stride(2))
     vc = Tensor(v_cache.data_ptr(), v_cache.stride(1), v_cache.stride(2))
+    if rope_table is not None:
+        rc = lib().dbsa_decode_attn_kv8_rope(layout.handle, _tensor(q_step), kc, vc, C.c_void_p(self_len.data_ptr()),
+                                             k_cache.stride(0), _tensor(k_pool8), _tensor(v_pool8),
+                                             C.c_void_p(k_scale.data_ptr()), C.c_void_p(v_scale.data_ptr()),
+                                             _tensor(o), C.c_void_p(rope_table.data_ptr()), rope_table.shape[0],
+                                             q_step.shape[1], k_pool8.shape[1], q_step.shape[2], float(scale),
+                                             ws_ptr, ws_bytes, C.c_void_p(_stream()))
+        _check(rc, "dbsa_decode_attn_kv8_rope")
+        return o
     rc = lib().dbsa_decode_attn_kv8(layout.handle, _tensor(q_step), kc, vc, C.c_void_p(self_len.data_ptr()),
                                     k_cache.stride(0), _tensor(k_pool8), _tensor(v_pool8),
                                     C.c_void_p(k_scale.data_ptr()), C.c_void_p(v_scale.data_ptr()), _tensor(o),

@@ -503,11 +503,12 @@ int dbsa_decode_attn(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_sel
                        n_q_heads, n_kv_heads, head_dim, softmax_scale, workspace, workspace_bytes, stream, nullptr, 0);
 }
 
-int dbsa_decode_attn_kv8(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
-                         const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool8, dbsa_tensor v_pool8,
-                         const float* k_scale, const float* v_scale, dbsa_tensor o, int32_t n_q_heads,
-                         int32_t n_kv_heads, int32_t head_dim, float softmax_scale, void* workspace,
-                         size_t workspace_bytes, void* stream) {
+namespace {
+int decode_kv8_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
+                      const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool8, dbsa_tensor v_pool8,
+                      const float* k_scale, const float* v_scale, dbsa_tensor o, const float* rope_table,
+                      int32_t rope_n_pos, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                      float softmax_scale, void* workspace, size_t workspace_bytes, void* stream) {
   if (!L || !L->on_device || !L->query_stage || !self_len || !k_scale || !v_scale) return DBSA_ERR_INVALID_ARG;
   if (int rc = check_shapes(DBSA_BF16, n_q_heads, n_kv_heads, head_dim, softmax_scale)) return rc;
   if (!tensor_ok(q_step, DBSA_BF16) || !tensor_ok(k_selfcache, DBSA_BF16) || !tensor_ok(v_selfcache, DBSA_BF16) ||
@@ -542,11 +543,36 @@ int dbsa_decode_attn_kv8(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k
   p.scale_log2e = softmax_scale * 1.4426950408889634f;
   p.k_scale8 = k_scale;
   p.v_scale8 = v_scale;
+  p.rope_table = rope_table;
+  p.rope_n_pos = rope_n_pos;
   p.partial = static_cast<float*>(workspace);
   p.decode_reverse = L->last_walk_reversed.fetch_xor(1) ^ 1;
   fill_decode_rows(p, L, r);
   if (order_behind_upload(L, static_cast<hipStream_t>(stream)) != hipSuccess) return DBSA_ERR_HIP;
   return launch_decode_group_kv8(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;
+}
+}  // namespace
+
+int dbsa_decode_attn_kv8(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
+                         const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool8, dbsa_tensor v_pool8,
+                         const float* k_scale, const float* v_scale, dbsa_tensor o, int32_t n_q_heads,
+                         int32_t n_kv_heads, int32_t head_dim, float softmax_scale, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  return decode_kv8_common(L, q_step, k_selfcache, v_selfcache, self_len, stride_query, k_pool8, v_pool8, k_scale,
+                           v_scale, o, nullptr, 0, n_q_heads, n_kv_heads, head_dim, softmax_scale, workspace,
+                           workspace_bytes, stream);
+}
+
+int dbsa_decode_attn_kv8_rope(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache,
+                              dbsa_tensor v_selfcache, const int32_t* self_len, int64_t stride_query,
+                              dbsa_tensor k_pool8, dbsa_tensor v_pool8, const float* k_scale, const float* v_scale,
+                              dbsa_tensor o, const float* rope_table, int32_t rope_n_pos, int32_t n_q_heads,
+                              int32_t n_kv_heads, int32_t head_dim, float softmax_scale, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  if (!rope_table || rope_n_pos < 1) return DBSA_ERR_INVALID_ARG;
+  return decode_kv8_common(L, q_step, k_selfcache, v_selfcache, self_len, stride_query, k_pool8, v_pool8, k_scale,
+                           v_scale, o, rope_table, rope_n_pos, n_q_heads, n_kv_heads, head_dim, softmax_scale,
+                           workspace, workspace_bytes, stream);
 }
 
 int dbsa_rope_table(const double* inv_freq, int32_t head_dim, int32_t n_pos, float* table, void* stream) {

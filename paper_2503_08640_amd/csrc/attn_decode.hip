@@ -17,6 +17,7 @@
 // single-wave workgroups per CU (24 KiB of LDS each) keep enough bytes outstanding to cover
 // HBM latency.  What matters most for the speed of a step is that its workgroups fit the
 // chip in ONE round: a half-filled second round costs a whole item time.
+#include <atomic>
 #include <cstdint>
 
 #include "kernels.hpp"
@@ -640,6 +641,7 @@ __device__ inline bf16x8 widen8(unsigned w0, unsigned w1) {
   return out.v;
 }
 
+template <bool ROPE>
 __global__ __launch_bounds__(64, 2) void decode_group_kv8_kernel(AttnParams p) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   lds_byte* lds = (lds_byte*)smem;
@@ -714,6 +716,12 @@ __global__ __launch_bounds__(64, 2) void decode_group_kv8_kernel(AttnParams p) {
   const intx4 ref = *reinterpret_cast<const intx4*>(p.gm_ref_pad + (static_cast<int64_t>(item) * 32 + q_local) * 4);
   const int u = ref[0], slot = ref[1];
   const int head = hk * r + l32 % r;
+  const float* rot = nullptr;
+  if (ROPE) {  // as in decode_group_kernel: the stored keys keep their encoding-time rotation
+    const int rot_id = min(max(ref[2] + p.self_len[u] - 1, 0), p.rope_n_pos - 1);
+    rot = p.rope_table + static_cast<int64_t>(rot_id) * kD + 16 * half;
+    asm volatile("" : "+v"(rot));
+  }
   const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
                      static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
   asm volatile("" : "+v"(qp));
@@ -726,19 +734,7 @@ __global__ __launch_bounds__(64, 2) void decode_group_kv8_kernel(AttnParams p) {
   const float c2 = p.scale_log2e * p.k_scale8[hk];
   const float v_scale = p.v_scale8[hk];
   bf16x8 qf[kD / 16];
-#pragma unroll
-  for (int c = 0; c < kD / 16; ++c) {
-    const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
-    union {
-      bf16x8 v;
-      bf16x2 p2[4];
-    } sc;
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      sc.p2[e] = __builtin_convertvector(
-          floatx2{static_cast<float>(raw[2 * e]) * c2, static_cast<float>(raw[2 * e + 1]) * c2}, bf16x2);
-    qf[c] = sc.v;
-  }
+  load_query_fragments<ROPE>(qp, rot, c2, qf);
   floatx16 o[kD / 32];
 #pragma unroll
   for (int ob = 0; ob < kD / 32; ++ob)
@@ -911,28 +907,38 @@ dim3 decode_grid(const AttnParams& p) { return dim3(static_cast<unsigned>(p.n_kv
 }  // namespace
 
 hipError_t launch_decode_group_kv8(const AttnParams& p_in, hipStream_t stream) {
-  static bool attr_set = false;
+  static std::atomic<bool> attr_set{false};  // setting it twice from two threads is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_kv8_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds8);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_kernel<false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
+    for (const void* f : {reinterpret_cast<const void*>(decode_group_kv8_kernel<false>),
+                          reinterpret_cast<const void*>(decode_group_kv8_kernel<true>)}) {
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLds8);
+      if (e != hipSuccess) return e;
+    }
+    for (const void* f : {reinterpret_cast<const void*>(decode_group_kernel<false>),
+                          reinterpret_cast<const void*>(decode_group_kernel<true>)}) {
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+      if (e != hipSuccess) return e;
+    }
     attr_set = true;
   }
   AttnParams p = p_in;
   if (p.n_gm_items > 0) {
     p.row_offset = 0;
     p.launch_rows = p.gm_pool_rows;
-    decode_group_kv8_kernel<<<decode_grid(p), dim3(64), kLds8, stream>>>(p);
+    if (p.rope_table)
+      decode_group_kv8_kernel<true><<<decode_grid(p), dim3(64), kLds8, stream>>>(p);
+    else
+      decode_group_kv8_kernel<false><<<decode_grid(p), dim3(64), kLds8, stream>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   // every query's own (bf16) cache: the self items of the ordinary kernel
   p.row_offset = p.gm_pool_rows;
   p.launch_rows = p.gm_n_rows - p.gm_pool_rows;
-  decode_group_kernel<false><<<decode_grid(p), dim3(64), kLdsBytes, stream>>>(p);
+  if (p.rope_table)
+    decode_group_kernel<true><<<decode_grid(p), dim3(64), kLdsBytes, stream>>>(p);
+  else
+    decode_group_kernel<false><<<decode_grid(p), dim3(64), kLdsBytes, stream>>>(p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   decode_group_merge_kernel<<<dim3(p.n_queries * p.n_q_heads), dim3(kD), 0, stream>>>(p);
@@ -942,7 +948,7 @@ hipError_t launch_decode_group_kv8(const AttnParams& p_in, hipStream_t stream) {
 namespace {
 template <int W>
 hipError_t launch_shared(const AttnParams& p, hipStream_t stream) {
-  static bool attr_set = false;
+  static std::atomic<bool> attr_set{false};  // setting it twice from two threads is harmless
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_shared_kernel<W, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsShared);
@@ -965,7 +971,7 @@ hipError_t launch_shared(const AttnParams& p, hipStream_t stream) {
 // decode_waves * 32 / r queries)
 hipError_t launch_decode_group(const AttnParams& p_in, hipStream_t stream) {
   AttnParams p = p_in;
-  static bool attr_set = false;
+  static std::atomic<bool> attr_set{false};  // setting it twice from two threads is harmless
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_group_kernel<false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);

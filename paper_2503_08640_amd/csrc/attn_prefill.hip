@@ -31,6 +31,7 @@
 //   * the running maximum may lag the true maximum by kRescaleSlack (weights then reach
 //     2^slack at most, harmless in fp32/bf16): accumulators are rescaled only when some
 //     row of the wave outgrows it, which is rare once a few tiles have been seen.
+#include <atomic>
 #include <cstdint>
 #include <type_traits>
 #include <utility>
@@ -604,7 +605,7 @@ __global__ __launch_bounds__(32 * kMergePairs) void prefill_merge_kernel(AttnPar
 template <int NW, int SL, bool SELF, bool ROPE = false>
 hipError_t launch_cfg(const AttnParams& p, hipStream_t stream) {
   constexpr int lds_bytes = (3 + 2 * SL) * kTileBytes;
-  static bool attr_set = false;
+  static std::atomic<bool> attr_set{false};  // setting it twice from two threads is harmless
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_kernel<NW, SL, SELF, ROPE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);

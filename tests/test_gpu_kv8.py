@@ -77,3 +77,40 @@ def test_decode_over_an_fp8_pool_config3_full_size():
     pc = synth.config2_pool()
     qc = synth.config3_query(pc)
     _decode_case(pc, qc, (0, 31), queries=(0, 7, 15), what="cfg3")
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4)])
+def test_repositioned_decode_over_an_fp8_pool(hq, hkv):
+    """Re-positioning (Sec. 2.2) over a quantised pool: the keys are rotated at their encoding
+    ids, THEN quantised.  The oracle gets the de-quantised keys rotated back in fp64 (a rotation
+    is undone by the opposite angle), i.e. the un-rotated keys whose encoding-time rotation
+    gives exactly the stored values, and rotates them at the new in-order ids itself."""
+    from oracle import rope_oracle as ro
+    pc = synth.make_pool_case("kv8rope", 6020 + hq, dtype="bf16", n_q_heads=hq, n_kv_heads=hkv, head_dim=128,
+                              sink_len=70, pool_tokens=4000, demo_len_range=(30, 200), n_groups=5,
+                              k_channel_sigma=0.5)
+    sels = [[3, 0], [], [4, 1, 2, 0, 3], [2]] + [[4, 1]] * 20
+    qc = synth.make_query_case("kv8ropeq", 6021, pc, n_queries=24, q_len=[64, 37, 100, 1] + [9] * 20, selections=sels,
+                               n_decode=2)
+    p = pc.pool
+    f = ro.inv_freq(500000.0, 128)
+    lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, cu_qlens=qc.cu_qlens,
+                              sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, n_split=0, block_m=32, block_n=64)
+    tab = B.dbsa_rope_table(f, 2 * p.n_tokens + 200)
+    k8, ks = quantise_per_head(B.dbsa_rope_apply(to_dev(pc.k), tab, first_id=0))
+    v8, vs = quantise_per_head(to_dev(pc.v))
+    k_unrot = ro.rope(dequantise(k8, ks), -np.arange(p.n_tokens), f)
+    vq = dequantise(v8, vs)
+    shp = qc.k_cache.shape
+    cache_pos = torch.from_numpy(np.tile(np.arange(shp[1], dtype=np.int32), shp[0])).cuda()
+    kc = B.dbsa_rope_apply(to_dev(qc.k_cache.reshape(-1, shp[2], shp[3])), tab, positions=cache_pos).view(shp)
+    vc = to_dev(qc.v_cache.reshape(-1, shp[2], shp[3])).view(shp)
+    lens = np.diff(qc.cu_qlens)
+    for s in range(2):
+        self_len = (lens + s + 1).astype(np.int32)
+        od = B.dbsa_decode_attn_kv8(lay, to_dev(qc.dec_q[s]), kc, vc, torch.from_numpy(self_len).cuda(), k8, v8, ks, vs,
+                                    pc.scale, rope_table=tab)
+        ref = ro.decode_attn_repositioned(synth.as_f64(qc.dec_q[s]), synth.as_f64(qc.k_cache), synth.as_f64(qc.v_cache),
+                                          self_len, k_unrot, vq, p.sink_len, p.demo_offsets, p.group_demo_offsets,
+                                          qc.sel_ptr, qc.sel_idx, f, pc.scale)
+        assert_close(to_f64(od), ref, f"Hq={hq} Hkv={hkv} re-positioned fp8-pool decode step {s}")
