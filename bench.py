@@ -114,6 +114,57 @@ def extra_setting(torch, B, pc, qc, workload: str, bm_pre: int, bm_query: int, i
     }
 
 
+def config4_sweep(torch, B, pc, k, v, iters: int = 20):
+    """Config 4: 128 concurrent queries x 32 prompt tokens + 1 decode token over the config-2 pool at 10 / 30 /
+    50 / 100 % of the groups per query: query prefill, one decode step, and both per unit of retrieval ratio."""
+    from paper_2503_08640_amd import synth
+    p = pc.pool
+    hq, hkv, d = pc.n_q_heads, pc.n_kv_heads, pc.head_dim
+
+    def dev(x):
+        return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+
+    rows = []
+    for ratio in synth.RETRIEVAL_RATIOS:
+        qc = synth.config4_query(pc, ratio)
+        qs, ks, vs = dev(qc.q), dev(qc.k), dev(qc.v)
+        oq = torch.empty_like(qs)
+        shp = qc.k_cache.shape
+        kc = dev(qc.k_cache.reshape(-1, shp[2], shp[3])).view(shp)
+        vc = dev(qc.v_cache.reshape(-1, shp[2], shp[3])).view(shp)
+        dq = dev(qc.dec_q.reshape(-1, hq, d)).view(qc.dec_q.shape)
+        od = torch.empty_like(dq[0])
+        lens = np.diff(qc.cu_qlens)
+        self_len = torch.from_numpy((lens + 1).astype(np.int32)).cuda()
+        lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, cu_qlens=qc.cu_qlens,
+                                  sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, n_split=0, block_m=QUERY_BLOCK_M, block_n=64)
+        ws = torch.empty(max(16, lay.workspace_bytes(hq, d)), dtype=torch.uint8, device="cuda")
+        ms = []
+        for fn, n in ((lambda: B.dbsa_query_attn(lay, qs, ks, vs, k, v, pc.scale, out=oq, workspace=ws), iters),
+                      (lambda: B.dbsa_decode_attn(lay, dq[0], kc, vc, self_len, k, v, pc.scale, out=od, workspace=ws),
+                       5 * iters)):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1) / n)
+        keys = selected_keys(p, qc)
+        flops = 4.0 * d * hq * float((lens * keys).sum() + (lens * (lens + 1) // 2).sum())
+        rows.append({"retrieval_ratio": ratio, "groups_per_query": int(qc.sel_ptr[1]),
+                     "query_prefill_ms": ms[0], "query_prefill_useful_tflops": flops / ms[0] / 1e9,
+                     "decode_step_ms": ms[1],
+                     "decode_per_query_gbs": float((keys + lens + 1).sum()) * hkv * d * 2 * 2 / ms[1] / 1e6,
+                     "query_stage_ms": ms[0] + ms[1], "query_stage_ms_per_ratio": (ms[0] + ms[1]) / ratio})
+        lay.destroy()
+    return {"workload": "config 4: 128 queries x (32 prompt tokens + 1 decode token) over the config-2 pool, "
+                        "independent random selections", "rows": rows}
+
+
 def repositioned_stage(torch, B, pc, qc, k, v, qs, ks, vs, oq, dq, kc, vc, self_len, od, plain_query_ms,
                        plain_decode_ms, iters: int = 20):
     """Query prefill and one decode step of config 3 through the *_rope entry points (timing only:
@@ -357,6 +408,7 @@ def main() -> int:
             "unique_gb_per_step": (union_keys * hkv * d * 2 * 1 + float((lens + 1).sum()) * hkv * d * 2 * 2) / 1e9,
         }
         del k8, v8
+        out["config4_sweep"] = config4_sweep(torch, B, pc, k, v)
         # the pool structure the paper itself runs (Sec. 3: blocks of 50 demonstrations, first block = sink,
         # two preceding blocks visible, 30 % of the blocks per query)
         pp = synth.paper_setting_pool()
