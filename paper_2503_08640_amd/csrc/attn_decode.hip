@@ -844,16 +844,20 @@ __global__ __launch_bounds__(64, 2) void decode_group_kv8_kernel(AttnParams p) {
 }
 
 // Merge the partial states of one (query, head): slots [slot_ptr[u], slot_ptr[u+1]).
-// Thread d owns output channel d.  The per-slot maxima and sums are read with one slot per
-// thread (not one after the other by everyone), the weights 2^(m_s - m*) go through LDS, and
-// the weighted sum of the accumulators runs with independent loads in flight.
-__global__ __launch_bounds__(kD) void decode_group_merge_kernel(AttnParams p) {
-  constexpr int kRow = kD + kPartialPad, kCap = 256;
+// 2 x 128 threads: thread (part, d) owns output channel d for the slots of its parity.  The
+// per-slot maxima and sums are read with one slot per thread (not one after the other by
+// everyone), the weights 2^(m_s - m*) go through LDS, and the weighted sum of the accumulators
+// runs with eight independent loads in flight per thread; the two parities meet in LDS.
+constexpr int kMergeThreads = 2 * kD;
+__global__ __launch_bounds__(kMergeThreads) void decode_group_merge_kernel(AttnParams p) {
+  constexpr int kRow = kD + kPartialPad, kCap = 256, kWaves = kMergeThreads / 64;
   __shared__ float w_sh[kCap];
-  __shared__ float red[2][kD / 64];
-  const int u = blockIdx.x / p.n_q_heads, head = blockIdx.x % p.n_q_heads, d = threadIdx.x;
+  __shared__ float red[2][kWaves];
+  __shared__ float acc_sh[kD];
+  const int u = blockIdx.x / p.n_q_heads, head = blockIdx.x % p.n_q_heads;
+  const int t = threadIdx.x, d = t % kD, part = t / kD;
   const int s0 = static_cast<int>(p.gm_slot_ptr[u]), s1 = static_cast<int>(p.gm_slot_ptr[u + 1]);
-  const float* part = p.partial + static_cast<int64_t>(head) * kRow;
+  const float* partial = p.partial + static_cast<int64_t>(head) * kRow;
   const int64_t slot_stride = static_cast<int64_t>(p.n_q_heads) * kRow;
 
   auto block_reduce = [&](float x, bool is_max, int which) {
@@ -861,42 +865,46 @@ __global__ __launch_bounds__(kD) void decode_group_merge_kernel(AttnParams p) {
       const float y = __shfl_xor(x, o, 64);
       x = is_max ? fmaxf(x, y) : x + y;
     }
-    if (d % 64 == 0) red[which][d / 64] = x;
+    if (t % 64 == 0) red[which][t / 64] = x;
     __syncthreads();
     float r = red[which][0];
-    for (int w = 1; w < kD / 64; ++w) r = is_max ? fmaxf(r, red[which][w]) : r + red[which][w];
+    for (int w = 1; w < kWaves; ++w) r = is_max ? fmaxf(r, red[which][w]) : r + red[which][w];
     return r;
   };
 
   float m = -1.0e30f;
-  for (int s = s0 + d; s < s1; s += kD) m = fmaxf(m, part[s * slot_stride + kD]);
+  for (int s = s0 + t; s < s1; s += kMergeThreads) m = fmaxf(m, partial[s * slot_stride + kD]);
   const float m_star = block_reduce(m, true, 0);
 
   float l = 0.f, acc = 0.f;
   for (int base = s0; base < s1; base += kCap) {
     const int n = min(kCap, s1 - base);
     __syncthreads();  // previous round's weights are consumed
-    for (int i = d; i < n; i += kD) {
-      const float w = __builtin_amdgcn_exp2f(part[(base + i) * slot_stride + kD] - m_star);
+    for (int i = t; i < n; i += kMergeThreads) {
+      const float w = __builtin_amdgcn_exp2f(partial[(base + i) * slot_stride + kD] - m_star);
       w_sh[i] = w;
-      l = fmaf(part[(base + i) * slot_stride + kD + 1], w, l);
+      l = fmaf(partial[(base + i) * slot_stride + kD + 1], w, l);
     }
     __syncthreads();
-    const float* col = part + static_cast<int64_t>(base) * slot_stride + d;
-    int i = 0;
-    for (; i + 8 <= n; i += 8) {
+    const float* col = partial + static_cast<int64_t>(base) * slot_stride + d;
+    int i = part;
+    for (; i + 14 < n; i += 16) {
       float v[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) v[j] = col[(i + j) * slot_stride];
+      for (int j = 0; j < 8; ++j) v[j] = col[(i + 2 * j) * slot_stride];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) acc = fmaf(v[j], w_sh[i + j], acc);
+      for (int j = 0; j < 8; ++j) acc = fmaf(v[j], w_sh[i + 2 * j], acc);
     }
-    for (; i < n; ++i) acc = fmaf(col[i * slot_stride], w_sh[i], acc);
+    for (; i < n; i += 2) acc = fmaf(col[i * slot_stride], w_sh[i], acc);
   }
   const float l_star = block_reduce(l, false, 1);
-  __bf16* o = static_cast<__bf16*>(const_cast<void*>(p.o.ptr));
-  o[static_cast<int64_t>(u) * p.o.stride_tok + static_cast<int64_t>(head) * p.o.stride_head + d] =
-      static_cast<__bf16>(acc / l_star);
+  if (part == 1) acc_sh[d] = acc;
+  __syncthreads();
+  if (part == 0) {
+    __bf16* o = static_cast<__bf16*>(const_cast<void*>(p.o.ptr));
+    o[static_cast<int64_t>(u) * p.o.stride_tok + static_cast<int64_t>(head) * p.o.stride_head + d] =
+        static_cast<__bf16>((acc + acc_sh[d]) / l_star);
+  }
 }
 
 }  // namespace
@@ -941,7 +949,7 @@ hipError_t launch_decode_group_kv8(const AttnParams& p_in, hipStream_t stream) {
     decode_group_kernel<false><<<decode_grid(p), dim3(64), kLdsBytes, stream>>>(p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  decode_group_merge_kernel<<<dim3(p.n_queries * p.n_q_heads), dim3(kD), 0, stream>>>(p);
+  decode_group_merge_kernel<<<dim3(p.n_queries * p.n_q_heads), dim3(kMergeThreads), 0, stream>>>(p);
   return hipGetLastError();
 }
 
@@ -997,6 +1005,6 @@ hipError_t launch_decode_group(const AttnParams& p_in, hipStream_t stream) {
     e = hipGetLastError();
   }
   if (e != hipSuccess) return e;
-  decode_group_merge_kernel<<<dim3(p.n_queries * p.n_q_heads), dim3(kD), 0, stream>>>(p);
+  decode_group_merge_kernel<<<dim3(p.n_queries * p.n_q_heads), dim3(kMergeThreads), 0, stream>>>(p);
   return hipGetLastError();
 }
