@@ -670,14 +670,15 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
       // every KV run is walked once for all the queries that selected it
       // Items that serve several batches of 32 / r queries: the batches of one item run as waves
       // of ONE workgroup that share its tiles in LDS, once a key is walked often enough for that
-      // to outweigh the barrier per half tile (measured: 2 waves from ~2 walks per key on, 4 from 2.5).
+      // to outweigh the barrier per half tile (measured over 16-256 queries at 10-100 % retrieval: 2
+      // waves pay from ~1.5 walks per key on, 4 from ~2.3).
       p.decode_waves = 1;
       {
         int k = 0;
         while ((32 >> k) > 32 / r) ++k;
         const float walks = L->gm_walks_per_key[k];
-        if (r % 4 == 0 && walks >= 2.5f) p.decode_waves = 4;
-        else if (r % 2 == 0 && walks >= 1.9f) p.decode_waves = 2;
+        if (r % 4 == 0 && walks >= 2.3f) p.decode_waves = 4;
+        else if (r % 2 == 0 && walks >= 1.5f) p.decode_waves = 2;
       }
       fill_decode_rows(p, L, r / p.decode_waves);
       e = launch_decode_group(p, s);
