@@ -200,40 +200,43 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
     k_lane_off[j] = static_cast<unsigned>(row_in * kp_stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u;
     v_lane_off[j] = static_cast<unsigned>(row_in * vp_stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u;
   }
-  // load block j (0 .. kBlocksPerWave-1) of this wave's share of a K / V tile
-  auto issue_k_block = [&](const TileRef& t, int stage, int j) DBSA_INLINE {
+  // this wave's share (kBlocksPerWave 1-KiB blocks) of a K / V tile.  ONE branch per tile picks
+  // the full-pool-tile path, whose per-lane offsets are precomputed: decided per block, the
+  // branches and their scalar bookkeeping cost more issue time than the loads themselves.
+  auto issue_k = [&](const TileRef& t, int stage) DBSA_INLINE {
     const uint64_t base = (t.self ? kself : kpool) + static_cast<uint64_t>(static_cast<unsigned>(t.start)) *
                                                          static_cast<unsigned>(2 * (t.self ? ks_stride : kp_stride));
-    const unsigned dst = lds0 + stage * kTileBytes + (wave * kBlocksPerWave + j) * 1024;
+    const unsigned dst = lds0 + stage * kTileBytes + wave * kBlocksPerWave * 1024;
     if (__builtin_expect(!t.self && t.len == kBN, 1)) {
-      dma16(base, k_lane_off[j], dst);
+#pragma unroll
+      for (int j = 0; j < kBlocksPerWave; ++j) dma16(base, k_lane_off[j], dst + j * 1024);
     } else {
       const int stride = t.self ? ks_stride : kp_stride;
-      const int row_in = 4 * (wave * kBlocksPerWave + j) + lane / 16;
-      const int row = min(row_in, t.len - 1);  // rows past the tail repeat the last key
-      dma16(base, static_cast<unsigned>(row * stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u, dst);
-    }
-  };
-  auto issue_v_block = [&](const TileRef& t, int stage, int j) DBSA_INLINE {
-    const uint64_t base = (t.self ? vself : vpool) + static_cast<uint64_t>(static_cast<unsigned>(t.start)) *
-                                                         static_cast<unsigned>(2 * (t.self ? vs_stride : vp_stride));
-    const unsigned dst = lds0 + (KS + stage) * kTileBytes + (wave * kBlocksPerWave + j) * 1024;
-    if (__builtin_expect(!t.self && t.len == kBN, 1)) {
-      dma16(base, v_lane_off[j], dst);
-    } else {
-      const int stride = t.self ? vs_stride : vp_stride;
-      const int row_in = 4 * (wave * kBlocksPerWave + j) + lane / 16;
-      const int row = min(row_in, t.len - 1);
-      dma16(base, static_cast<unsigned>(row * stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u, dst);
-    }
-  };
-  auto issue_k = [&](const TileRef& t, int stage) DBSA_INLINE {
 #pragma unroll
-    for (int j = 0; j < kBlocksPerWave; ++j) issue_k_block(t, stage, j);
+      for (int j = 0; j < kBlocksPerWave; ++j) {
+        const int row_in = 4 * (wave * kBlocksPerWave + j) + lane / 16;
+        const int row = min(row_in, t.len - 1);  // rows past the tail repeat the last key
+        dma16(base, static_cast<unsigned>(row * stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u, dst + j * 1024);
+      }
+    }
   };
   auto issue_v = [&](const TileRef& t, int stage) DBSA_INLINE {
+    const uint64_t base = (t.self ? vself : vpool) + static_cast<uint64_t>(static_cast<unsigned>(t.start)) *
+                                                         static_cast<unsigned>(2 * (t.self ? vs_stride : vp_stride));
+    const unsigned dst = lds0 + (KS + stage) * kTileBytes + wave * kBlocksPerWave * 1024;
+    if (__builtin_expect(!t.self && t.len == kBN, 1)) {
 #pragma unroll
-    for (int j = 0; j < kBlocksPerWave; ++j) issue_v_block(t, stage, j);
+      for (int j = 0; j < kBlocksPerWave; ++j) dma16(base, v_lane_off[j], dst + j * 1024);
+    } else {
+      const int stride = t.self ? vs_stride : vp_stride;
+#pragma unroll
+      for (int j = 0; j < kBlocksPerWave; ++j) {
+        const int row_in = 4 * (wave * kBlocksPerWave + j) + lane / 16;
+        const int row = min(row_in, t.len - 1);
+        dma16(base, static_cast<unsigned>(row * stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u,
+              dst + j * 1024);
+      }
+    }
   };
 
   // ---- per-lane LDS read addresses (absolute LDS byte addresses, stage included) ----
@@ -414,7 +417,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
     __syncthreads();
 
     // rare: some row's maximum outgrew the lagging running maximum
-    if (__builtin_amdgcn_ballot_w64(mx_cur > kRescaleSlack) != 0) {
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx_cur > kRescaleSlack) != 0, 0)) {
       const float delta = fmaxf(mx_cur, 0.f);
       const float alpha = __builtin_amdgcn_exp2f(-delta);
       m_run += delta;
@@ -438,7 +441,18 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
     }
     const bool has_next = it + 1 < n_tiles;
     const TileRef nxt = refs[0];
-    int in_w0 = 0, in_w1 = 0;  // list entry it+3+SL (zero past the end), needed by the next step's K load
+    // List entry it+3+SL (zero past the end), needed by the next step's K load.  Requested FIRST:
+    // a scalar load shares its counter with the LDS fragment reads and returns out of order with
+    // them, so while it is in flight every fragment wait drains the whole queue; behind the
+    // load instructions of this step it has returned before the first such wait.
+    int in_w0 = 0, in_w1 = 0;
+    if (it + 3 + SL < n_tiles) {
+      in_w0 = ent[2 * (it + 3 + SL)];
+      in_w1 = ent[2 * (it + 3 + SL) + 1];
+    }
+    if constexpr (ROPE) {
+      if (it + 2 < n_tiles) nxt_shift = lshift[it + 2];
+    }
     bf16x2 pk[2][8];
     float p0 = 0.f, p1 = 0.f;  // exponentials of one matrix step, packed during the next
 
@@ -458,13 +472,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
         // load sits behind a branch on the list length, and each branch splits the straight-line code.)
         if (it + 2 + SL < n_tiles) issue_k(refs[1 + SL], k_wr);
         if (it + SL < n_tiles) issue_v(refs[SL - 1], v_wr);
-        if (it + 3 + SL < n_tiles) {
-          in_w0 = ent[2 * (it + 3 + SL)];
-          in_w1 = ent[2 * (it + 3 + SL) + 1];
-        }
-        if constexpr (ROPE) {
-          if (it + 2 < n_tiles) nxt_shift = lshift[it + 2];
-        }
       }
       if constexpr (t > 0) {
         constexpr int u = t - 1;
@@ -480,7 +487,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
     });
     pk[1][7] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);
     l_run += p0 + p1;
-    if (has_next && (nxt.causal || nxt.len < kBN)) apply_mask(s_nxt, nxt);
+    if (__builtin_expect(has_next && (nxt.causal || nxt.len < kBN), 0)) apply_mask(s_nxt, nxt);
     {
       // every K fragment of tile it+1 has been requested: the K addresses move on to the stage of K(it+2)
       const int k_next = (k_rd + 1 == KS) ? 0 : k_rd + 1;
