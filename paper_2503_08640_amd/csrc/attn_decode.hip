@@ -537,6 +537,7 @@ __global__ __launch_bounds__(64 * W) void decode_group_shared_kernel(AttnParams 
     if (hh + 1 < n_half) wait_vmcnt<2 * kPerWave>();
     else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");  // no LDS read of this pair may move above the barrier
     // every wave is past pair hh-1: its slot takes pair hh+2
     if (hh + 2 < n_half) issue_pair(hh + 2);
     if (!active) continue;
