@@ -300,3 +300,58 @@ def test_attention_calls_reject_what_the_kernels_do_not_implement():
         B.dbsa_decode_attn(layq, to_dev(qc.dec_q[0]), kc, kc, torch.tensor([9, 9], dtype=torch.int32, device="cuda"),
                            kp, vp, pc.scale, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
     assert ei.value.code == B.DBSA_ERR_WORKSPACE
+
+
+# ---------------------------------------------------------------------------
+# rows whose maximum keeps growing: the lazy-rescale path of every kernel
+# ---------------------------------------------------------------------------
+def _ramp_keys(k_bits, seg_bounds, direction, top, rng):
+    """Keys = ramp(position inside its segment) * direction + small noise: with queries along
+    `direction` the scores of a segment rise from 0 to about scale * |q| * `top`, i.e. by
+    far more than the kernels' rescale slack (8 in log2 units) from one 64-key tile to the next."""
+    n, hkv, d = k_bits.shape
+    ramp = np.zeros(n, dtype=np.float32)
+    for a, b in seg_bounds:
+        if b > a:
+            ramp[a:b] = np.arange(b - a, dtype=np.float32) / max(1, b - a - 1)
+    k = ramp[:, None, None] * top * direction[None, None, :] + 0.3 * rng.standard_normal((n, hkv, d)).astype(np.float32)
+    return synth.f32_to_bf16_bits(k)
+
+
+@pytest.mark.parametrize("hq,hkv,block_m", [(8, 2, 32), (4, 4, 128), (8, 1, 64)])
+def test_growing_row_maxima_take_the_rescale_path(hq, hkv, block_m):
+    rng = np.random.default_rng(77)
+    pc = small_pool_case("ramp", 2090 + hq, hq=hq, hkv=hkv, pool_tokens=3000, groups=3, lens=(32, 128))
+    p = pc.pool
+    d = pc.head_dim
+    u = rng.standard_normal(d).astype(np.float32)
+    u /= np.linalg.norm(u)
+    c = 32.0                                            # |q . u|
+    top = 200.0 / (pc.scale * c)                        # scores reach ~200
+    gb = p.group_token_bounds()
+    segs = [(0, p.sink_len)] + [(int(gb[g]), int(gb[g + 1])) for g in range(p.n_groups)]
+    pc.k = _ramp_keys(pc.k, segs, u, top, rng)
+    pc.q = synth.f32_to_bf16_bits(c * u[None, None, :] + rng.standard_normal(pc.q.shape).astype(np.float32))
+    # the inputs do what they are meant to: along the keys of a group the tile maxima of a row rise by
+    # more than the slack of 8 (log2 units) at nearly every 64-key tile
+    row = int(gb[1]) - 1
+    s_row = (synth.as_f64(pc.k)[int(gb[0]):row + 1, 0] @ synth.as_f64(pc.q)[row, 0]) * pc.scale * np.log2(np.e)
+    tile_max = np.array([s_row[t:t + 64].max() for t in range(0, len(s_row), 64)])
+    assert (np.diff(tile_max) > 8.0).mean() > 0.8 and len(tile_max) >= 8
+    _, o, _ = run_preencode(pc, block_m)
+    assert_close(to_f64(o), oracle_preencode(pc), f"ramped pre-encode bm={block_m}")
+
+    n_q = 36 if hq // hkv >= 4 else 5                   # many queries per group: the shared-tile decode kernels too
+    qc = synth.make_query_case("rampq", 2091, pc, n_queries=n_q, q_len=40, n_select=2, n_decode=2)
+    lens = np.diff(qc.cu_qlens)
+    qc.k = _ramp_keys(qc.k, [(int(qc.cu_qlens[i]), int(qc.cu_qlens[i + 1])) for i in range(n_q)], u, top, rng)
+    qc.q = synth.f32_to_bf16_bits(c * u[None, None, :] + rng.standard_normal(qc.q.shape).astype(np.float32))
+    qc.dec_q = synth.f32_to_bf16_bits(c * u[None, None, None, :] + rng.standard_normal(qc.dec_q.shape).astype(np.float32))
+    t_max = qc.k_cache.shape[1]
+    cache = _ramp_keys(qc.k_cache.reshape(n_q * t_max, hkv, d), [(i * t_max, i * t_max + int(lens[i]) + 2) for i in range(n_q)],
+                       u, top, rng)
+    qc.k_cache = cache.reshape(qc.k_cache.shape)
+    lay, kp, vp = _query_setup(pc, qc, block_m if block_m <= 64 else 64, 0)
+    oq = B.dbsa_query_attn(lay, to_dev(qc.q), to_dev(qc.k), to_dev(qc.v), kp, vp, pc.scale)
+    assert_close(to_f64(oq), _oracle_query(pc, qc), f"ramped query prefill Hq={hq} Hkv={hkv}")
+    _run_decode_steps(pc, qc, lay, kp, vp, range(2), f"ramped Hq={hq} Hkv={hkv}")   # one step per walk direction
