@@ -8,15 +8,18 @@
  * [0, S), then the demonstrations; groups are runs of whole demonstrations.
  *
  * All tensors are token-major [tokens, heads, D] with the D elements of one
- * (token, head) contiguous; strides are given in ELEMENTS.  Q/K/V are post-RoPE:
- * the library never applies positions, so the K handed to the query stage may be
- * a re-positioned copy (Sec. 2.2) of the K used at pre-encoding.
+ * (token, head) contiguous; strides are given in ELEMENTS.  For dbsa_preencode_attn,
+ * dbsa_query_attn, dbsa_decode_attn and dbsa_decode_attn_kv8 Q/K/V are post-RoPE:
+ * these calls never apply positions, so the K handed to the query stage may be a
+ * re-positioned copy (Sec. 2.2) of the K used at pre-encoding.  The *_rope calls
+ * apply the new in-order position ids of Sec. 2.2 themselves (see there).
  *
  * Every function returns DBSA_OK (0) or a negative error code; nothing throws
  * across the boundary.  Functions are thread-safe on distinct layouts.  The
  * attention entry points only enqueue work on the caller's stream and never
- * synchronise it.  The caller owns every tensor and the workspace; the library
- * owns only dbsa_layout objects (build / destroy).
+ * synchronise it; neither do dbsa_layout_build and dbsa_layout_destroy.  The
+ * caller owns every tensor and the workspace; the library owns only dbsa_layout
+ * objects (build / destroy) and the device blocks their lists live in.
  */
 #ifndef DBSA_H_
 #define DBSA_H_
