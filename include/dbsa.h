@@ -299,6 +299,8 @@ int dbsa_query_attn(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_tensor k
  * of them than the last-level cache holds, and what the previous step read last is still there.
  * The two directions differ by fp32 summation order only.  Calls on one layout from several
  * threads are safe; they merely share that alternation.
+ * The call only launches kernels (no allocation, no memset, no host wait), so it may be
+ * recorded into a HIP graph by stream capture; the direction is fixed at capture time.
  */
 int dbsa_decode_attn(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
                      const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool, dbsa_tensor v_pool,

@@ -114,3 +114,26 @@ def test_repositioned_decode_over_an_fp8_pool(hq, hkv):
                                           self_len, k_unrot, vq, p.sink_len, p.demo_offsets, p.group_demo_offsets,
                                           qc.sel_ptr, qc.sel_idx, f, pc.scale)
         assert_close(to_f64(od), ref, f"Hq={hq} Hkv={hkv} re-positioned fp8-pool decode step {s}")
+
+
+def test_fp8_decode_takes_the_rescale_path_when_row_maxima_keep_growing():
+    """Keys ramped along a fixed direction inside every segment and queries along that direction:
+    the scores of a run rise by more than the kernel's rescale slack from one half tile to the
+    next (forward walk; the backward walk of the other step starts at the maximum)."""
+    rng = np.random.default_rng(78)
+    pc = synth.make_pool_case("kv8ramp", 6030, dtype="bf16", n_q_heads=8, n_kv_heads=2, head_dim=128, sink_len=64,
+                              pool_tokens=3000, demo_len_range=(32, 128), n_groups=3)
+    p = pc.pool
+    u = rng.standard_normal(128).astype(np.float32)
+    u /= np.linalg.norm(u)
+    c = 32.0
+    top = 200.0 / (pc.scale * c)
+    gb = p.group_token_bounds()
+    ramp = np.zeros(p.n_tokens, dtype=np.float32)
+    for a, b in [(0, p.sink_len)] + [(int(gb[g]), int(gb[g + 1])) for g in range(p.n_groups)]:
+        ramp[a:b] = np.arange(b - a, dtype=np.float32) / max(1, b - a - 1)
+    k = ramp[:, None, None] * top * u[None, None, :] + 0.3 * rng.standard_normal(pc.k.shape).astype(np.float32)
+    pc.k = synth.f32_to_bf16_bits(k)
+    qc = synth.make_query_case("kv8rampq", 6031, pc, n_queries=12, q_len=20, n_select=2, n_decode=2)
+    qc.dec_q = synth.f32_to_bf16_bits(c * u[None, None, None, :] + rng.standard_normal(qc.dec_q.shape).astype(np.float32))
+    _decode_case(pc, qc, range(2), what="ramped keys")

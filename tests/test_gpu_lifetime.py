@@ -91,3 +91,39 @@ def test_a_call_on_another_stream_sees_the_uploaded_lists():
         side.synchronize()
         assert torch.equal(got, want)
     torch.cuda.synchronize()
+
+
+def test_decode_steps_replayed_from_a_hip_graph_match_the_eager_steps():
+    """Two decode steps (one per walk direction) captured into a HIP graph: the calls launch
+    kernels only (no allocation, no memset, workspace from the caller), so replays, with eager
+    work and synchronisations in between, must reproduce the eager results bit for bit."""
+    pc, qa, _ = _case()
+    k, v = to_dev(pc.k), to_dev(pc.v)
+    lens = np.diff(qa.cu_qlens)
+    shp = qa.k_cache.shape
+    kc = to_dev(qa.k_cache.reshape(-1, shp[2], shp[3])).view(shp)
+    vc = to_dev(qa.v_cache.reshape(-1, shp[2], shp[3])).view(shp)
+    dq = to_dev(qa.dec_q[0])
+    sl = torch.from_numpy((lens + 1).astype(np.int32)).cuda()
+    lay = _build(pc, qa)
+    ws = torch.empty(lay.workspace_bytes(pc.n_q_heads, pc.head_dim), dtype=torch.uint8, device="cuda")
+    out = [torch.empty_like(dq), torch.empty_like(dq)]
+    # eager: the first decode call on a fresh layout walks backwards, the second forwards
+    for o in out:
+        B.dbsa_decode_attn(lay, dq, kc, vc, sl, k, v, pc.scale, out=o, workspace=ws)
+    torch.cuda.synchronize()
+    want = [o.clone() for o in out]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for o in out:
+            B.dbsa_decode_attn(lay, dq, kc, vc, sl, k, v, pc.scale, out=o, workspace=ws)
+    for rep in range(4):
+        for o in out:
+            o.fill_(float("nan"))
+        ws.random_(0, 255)                              # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i in range(2):
+            assert torch.equal(out[i], want[i]), f"replay {rep}, step {i}"
+    lay.destroy()
