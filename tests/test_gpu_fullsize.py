@@ -138,6 +138,15 @@ def test_config4_sweep_full_size(cfg2, ratio):
     _query_fullsize(cfg2, qc, 32, oracle_queries=queries, decode_steps=(0,), what=f"cfg4 ratio {ratio}")
 
 
+def test_many_concurrent_queries_over_the_config2_pool(cfg2):
+    """640 queries of 8 tokens, 50 % of the groups each: four times config 4's concurrency (every
+    group serves ~320 queries = 10 items per run, 64-bit slot and reference offsets, ~90 partial
+    states per query); sampled queries against the oracle."""
+    qc = synth.make_query_case("many", 1020, cfg2, n_queries=640, q_len=8, n_select=11, n_decode=1)
+    queries = (0, 77, 319, 320, 501, 639)
+    _query_fullsize(cfg2, qc, 32, oracle_queries=queries, decode_steps=(0,), what="640 queries")
+
+
 def test_config4_full_retrieval_equals_dense_causal(cfg2):
     """At 100 % retrieval the query rows are rows of dense causal attention over
     [pool ; query] (cached many-shot ICL over the whole pool, Sec. 3 Baselines); checked
