@@ -220,7 +220,8 @@ int dbsa_layout_export_order(const dbsa_layout* layout, const int32_t** order, i
  * has passed the point of this call (one event per such stream is recorded here, so those
  * streams must still exist and must not be under graph capture); only then does a later
  * dbsa_layout_build reuse the block.  If an event cannot be recorded the call falls back to
- * hipDeviceSynchronize. */
+ * hipDeviceSynchronize.  A HIP graph that recorded calls on the layout refers to its device lists:
+ * it must not be replayed after this call. */
 void dbsa_layout_destroy(dbsa_layout* layout);
 
 /*
