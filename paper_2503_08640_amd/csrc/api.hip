@@ -261,6 +261,16 @@ void fill_decode_rows(AttnParams& p, const dbsa_layout* L, int r) {
   p.gm_pool_rows = L->gm_pool_rows[k];
 }
 
+// waves per decode workgroup for r query heads per KV head (32 % r == 0), see decode_common
+int pick_decode_waves(const dbsa_layout* L, int r) {
+  int k = 0;
+  while ((32 >> k) > 32 / r) ++k;
+  const float walks = L->gm_walks_per_key[k];
+  if (r % 4 == 0 && walks >= 2.3f) return 4;
+  if (r % 2 == 0 && walks >= 1.5f) return 2;
+  return 1;
+}
+
 void fill_lists(AttnParams& p, const dbsa_layout* L) {
   p.qtile_tab = L->dev.qtile_tab;
   p.list_ptr = L->dev.list_ptr;
@@ -547,7 +557,8 @@ int decode_kv8_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_se
   p.rope_n_pos = rope_n_pos;
   p.partial = static_cast<float*>(workspace);
   p.decode_reverse = L->last_walk_reversed.fetch_xor(1) ^ 1;
-  fill_decode_rows(p, L, r);
+  p.decode_waves = pick_decode_waves(L, r);
+  fill_decode_rows(p, L, r / p.decode_waves);
   if (order_behind_upload(L, static_cast<hipStream_t>(stream)) != hipSuccess) return DBSA_ERR_HIP;
   return launch_decode_group_kv8(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;
 }
@@ -672,14 +683,7 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
       // of ONE workgroup that share its tiles in LDS, once a key is walked often enough for that
       // to outweigh the barrier per half tile (measured over 16-256 queries at 10-100 % retrieval: 2
       // waves pay from ~1.5 walks per key on, 4 from ~2.3).
-      p.decode_waves = 1;
-      {
-        int k = 0;
-        while ((32 >> k) > 32 / r) ++k;
-        const float walks = L->gm_walks_per_key[k];
-        if (r % 4 == 0 && walks >= 2.3f) p.decode_waves = 4;
-        else if (r % 2 == 0 && walks >= 1.5f) p.decode_waves = 2;
-      }
+      p.decode_waves = pick_decode_waves(L, r);
       fill_decode_rows(p, L, r / p.decode_waves);
       e = launch_decode_group(p, s);
     } else {

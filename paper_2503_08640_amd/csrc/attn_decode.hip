@@ -382,6 +382,66 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   }
 }
 
+// One half tile (32 keys, bf16, swizzled as the loads of decode_group_kernel leave it) against
+// the 32 columns of a wave: scores, lazy-rescaled online softmax, product with the values.
+// ks / vs: the K and V half tiles in LDS; len: valid keys; k_base / v_base: this lane's fragment
+// offsets; the running state (o, m_run, l_run) is updated in place.
+__device__ inline void half_tile_attend(const lds_byte* ks, const lds_byte* vs, int len, int k_base, int v_base, int half,
+                                        const bf16x8 (&qf)[kD / 16], floatx16 (&o)[kD / 32], float& m_run,
+                                        float& l_run) {
+  floatx16 s, s2;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s[i] = 0.f, s2[i] = 0.f;
+#pragma unroll
+  for (int c = 0; c < kD / 16; c += 2) {
+    const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * c)));
+    const bf16x8 a2 = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * (c + 1))));
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[c], s, 0, 0, 0);
+    s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, qf[c + 1], s2, 0, 0, 0);
+  }
+  s += s2;
+  if (len < kHalf) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int key_local = 8 * (i / 4) + 4 * half + (i % 4);
+      s[i] = key_local < len ? s[i] : -INFINITY;
+    }
+  }
+  float mx = s[0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+  mx = half_swap_max(mx);
+  if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int ob = 0; ob < kD / 32; ++ob) o[ob] *= alpha;
+  }
+  union {
+    bf16x8 v[2];
+    bf16x2 p2[8];
+  } pf;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float p0 = __builtin_amdgcn_exp2f(s[2 * i] - m_run);
+    const float p1 = __builtin_amdgcn_exp2f(s[2 * i + 1] - m_run);
+    pf.p2[i] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);
+    l_run += p0 + p1;
+  }
+#pragma unroll
+  for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+    for (int ob = 0; ob < kD / 32; ++ob) {
+      const lds_byte* vp = vs + (v_base ^ (64 * ob)) + 16 * ch * kRowBytes;
+      const bf16x4 lo = lds_read_tr(vp);
+      const bf16x4 hi = lds_read_tr(vp + 8 * kRowBytes);
+      const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf.v[ch], o[ob], 0, 0, 0);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // The same walk for layouts whose items serve MORE queries than one wave has columns (many
 // concurrent queries, high retrieval ratios): the W waves of a workgroup take W consecutive query
@@ -546,58 +606,7 @@ __global__ __launch_bounds__(64 * W) void decode_group_shared_kernel(AttnParams 
     const lds_byte* ks = lds + (hh % kPairs) * kPairBytes;
     const lds_byte* vs = ks + kHalfBytes;
 
-    floatx16 s, s2;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) s[i] = 0.f, s2[i] = 0.f;
-#pragma unroll
-    for (int c = 0; c < kD / 16; c += 2) {
-      const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * c)));
-      const bf16x8 a2 =
-          *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * (c + 1))));
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[c], s, 0, 0, 0);
-      s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, qf[c + 1], s2, 0, 0, 0);
-    }
-    s += s2;
-    if (len < kHalf) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key_local = 8 * (i / 4) + 4 * half + (i % 4);
-        s[i] = key_local < len ? s[i] : -INFINITY;
-      }
-    }
-    float mx = s[0];
-#pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
-    mx = half_swap_max(mx);
-    if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int ob = 0; ob < kD / 32; ++ob) o[ob] *= alpha;
-    }
-    union {
-      bf16x8 v[2];
-      bf16x2 p2[8];
-    } pf;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float p0 = __builtin_amdgcn_exp2f(s[2 * i] - m_run);
-      const float p1 = __builtin_amdgcn_exp2f(s[2 * i + 1] - m_run);
-      pf.p2[i] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);
-      l_run += p0 + p1;
-    }
-#pragma unroll
-    for (int ch = 0; ch < 2; ++ch)
-#pragma unroll
-      for (int ob = 0; ob < kD / 32; ++ob) {
-        const lds_byte* vp = vs + (v_base ^ (64 * ob)) + 16 * ch * kRowBytes;
-        const bf16x4 lo = lds_read_tr(vp);
-        const bf16x4 hi = lds_read_tr(vp + 8 * kRowBytes);
-        const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf.v[ch], o[ob], 0, 0, 0);
-      }
+    half_tile_attend(ks, vs, len, k_base, v_base, half, qf, o, m_run, l_run);
   }
 
   // ---- partial state of every valid column ----
@@ -844,6 +853,164 @@ __global__ __launch_bounds__(64, 2) void decode_group_kv8_kernel(AttnParams p) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// fp8 pool, many queries per item: the W waves of a workgroup take W query batches of one item
+// (as in decode_group_shared_kernel) and share not only the staged bytes but their WIDENING: a
+// half tile's 4 KiB of K bytes and 4 KiB of V bytes arrive in a ring of three staging pairs; each
+// wave widens the rows it fetched itself (1/W of the pair: 32 bytes -> 32 bf16 per lane) into ONE
+// bf16 working pair laid out exactly as the bf16 kernels' tiles, and all waves run the bf16
+// arithmetic on that pair.  Two barriers per half tile: before the widening (every wave is done
+// with the working pair of the half tile before) and after it (the working pair is complete).
+constexpr int kStagePair8 = 2 * kSlot8;                               // 8 KiB of bytes per (K, V) half tile
+constexpr int kLdsShared8 = kPairs * kStagePair8 + kPairBytes;        // 24 KiB staging + 16 KiB working pair
+
+template <int W, bool ROPE>
+__global__ __launch_bounds__(64 * W) void decode_group_kv8_shared_kernel(AttnParams p) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  lds_byte* lds = (lds_byte*)smem;
+  lds_byte* work_k = lds + kPairs * kStagePair8;
+  lds_byte* work_v = work_k + kHalfBytes;
+  static_assert(kLoads8 % W == 0, "waves share the load instructions evenly");
+  constexpr int kPerWave = kLoads8 / W;  // load instructions per wave per K or V half tile (8 rows each)
+  const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) / 64);
+  const int lane = threadIdx.x % 64, l32 = lane % 32, half = lane / 32;
+  const int r = p.n_q_heads / p.n_kv_heads;
+  const int qpw = 32 / r;
+  // same id mapping as decode_group_shared_kernel; this launch covers the rows of pool items only
+  const int in_block = blockIdx.x % 8;
+  const int row_id = (blockIdx.x / 8) % p.launch_rows, hk = (blockIdx.x / 8) / p.launch_rows;
+  typedef const __attribute__((address_space(4))) int32_t* const_words;
+  const int row = ((const_words)(reinterpret_cast<uintptr_t>(p.gm_rows)))[p.row_offset + row_id];
+  const int wg_batch = row & 0xFF;
+  const int item = 8 * (row >> 8) + in_block;
+  if (item >= p.n_gm_items) return;
+  const const_words runs = (const_words)(reinterpret_cast<uintptr_t>(p.gm_item_run));
+  const int first_key = runs[4 * item + 0], n_keys = runs[4 * item + 1], n_q = runs[4 * item + 2];
+  const int n_half = (n_keys + kHalf - 1) / kHalf;
+  const int n_pass = (n_q + qpw - 1) / qpw;
+  if (wg_batch * W >= n_pass) return;  // (the same for all waves: the workgroup leaves as one)
+  const int pass = wg_batch * W + wave;
+  const bool active = pass < n_pass;
+
+  const unsigned char* kbase = static_cast<const unsigned char*>(p.k_pool.ptr) + hk * p.k_pool.stride_head;
+  const unsigned char* vbase = static_cast<const unsigned char*>(p.v_pool.ptr) + hk * p.v_pool.stride_head;
+  const int k_stride = static_cast<int>(p.k_pool.stride_tok), v_stride = static_cast<int>(p.v_pool.stride_tok);
+  auto half_ref = [&](int hh, int& start, int& len) {
+    const int pos = p.decode_reverse ? n_half - 1 - hh : hh;
+    start = first_key + pos * kHalf;
+    len = min(kHalf, n_keys - pos * kHalf);
+  };
+  // load instruction j of a staged operand fills rows 8j .. 8j+7 (128-byte rows; lane -> row
+  // 8j + lane/8, 16 bytes lane%8; rows past the tail repeat the last key); wave w issues the
+  // instructions j = w + W*i and later widens exactly those rows
+  auto issue_pair = [&](int hh) {
+    int start, len;
+    half_ref(hh, start, len);
+    lds_byte* k_stage = lds + (hh % kPairs) * kStagePair8;
+    lds_byte* v_stage = k_stage + kSlot8;
+    const unsigned char* kb = kbase + static_cast<int64_t>(start) * k_stride;
+    const unsigned char* vb = vbase + static_cast<int64_t>(start) * v_stride;
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+      const int j = wave + W * i;
+      const int row_k = min(8 * j + lane / 8, len - 1);
+      dma16(kb, static_cast<unsigned>(row_k * k_stride + (lane % 8) * 16), k_stage + j * 1024);
+    }
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+      const int j = wave + W * i;
+      const int row_v = min(8 * j + lane / 8, len - 1);
+      dma16(vb, static_cast<unsigned>(row_v * v_stride + (lane % 8) * 16), v_stage + j * 1024);
+    }
+  };
+  // this wave's rows of staged pair hh -> bf16 working pair: lane -> row 8j + lane/8, channels
+  // 16*(lane%8) .. +15 = the 16-byte slots 2*(lane%8) and 2*(lane%8)+1 of the 256-byte bf16 row,
+  // K slots swizzled by row % 16, V slots by 4*(row % 4) (the bf16 kernels' layouts)
+  auto widen_pair = [&](int hh) {
+    const lds_byte* k_stage = lds + (hh % kPairs) * kStagePair8;
+    const lds_byte* v_stage = k_stage + kSlot8;
+    typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+    typedef const __attribute__((address_space(3))) uintx4* bytes_ptr;
+    typedef __attribute__((address_space(3))) bf16x8* tile_ptr;
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+      const int j = wave + W * i;
+      const int row = 8 * j + lane / 8, s0 = 2 * (lane % 8);
+      const uintx4 kx = *(bytes_ptr)(k_stage + j * 1024 + lane * 16);
+      const uintx4 vx = *(bytes_ptr)(v_stage + j * 1024 + lane * 16);
+      *(tile_ptr)(work_k + row * kRowBytes + ((s0 ^ (row % 16)) * 16)) = widen8(kx[0], kx[1]);
+      *(tile_ptr)(work_k + row * kRowBytes + (((s0 + 1) ^ (row % 16)) * 16)) = widen8(kx[2], kx[3]);
+      *(tile_ptr)(work_v + row * kRowBytes + ((s0 ^ (4 * (row % 4))) * 16)) = widen8(vx[0], vx[1]);
+      *(tile_ptr)(work_v + row * kRowBytes + (((s0 + 1) ^ (4 * (row % 4))) * 16)) = widen8(vx[2], vx[3]);
+    }
+  };
+
+  const int k_base = l32 * kRowBytes + ((half ^ (l32 % 16)) * 16);
+  const int v_base = (4 * half + (lane % 16) / 4) * kRowBytes +
+                     (((2 * (l32 / 16) + (lane % 4) / 2) ^ (4 * ((lane % 16) / 4))) * 16) + (lane % 2) * 8;
+
+  // ---- this lane's column ----
+  const int q_local = pass * qpw + l32 / r;  // < 32 also for a wave without a batch
+  const bool col_valid = active && q_local < n_q;
+  typedef int intx4 __attribute__((ext_vector_type(4)));
+  const intx4 ref = *reinterpret_cast<const intx4*>(p.gm_ref_pad + (static_cast<int64_t>(item) * 32 + q_local) * 4);
+  const int u = ref[0], slot = ref[1];
+  const int head = hk * r + l32 % r;
+  const float* rot = nullptr;
+  if (ROPE) {
+    const int rot_id = min(max(ref[2] + p.self_len[u] - 1, 0), p.rope_n_pos - 1);
+    rot = p.rope_table + static_cast<int64_t>(rot_id) * kD + 16 * half;
+    asm volatile("" : "+v"(rot));
+  }
+  const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
+                     static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
+  asm volatile("" : "+v"(qp));
+  issue_pair(0);
+  if (1 < n_half) issue_pair(1);
+  const float c2 = p.scale_log2e * p.k_scale8[hk];
+  const float v_scale = p.v_scale8[hk];
+  bf16x8 qf[kD / 16];
+  load_query_fragments<ROPE>(qp, rot, c2, qf);
+  floatx16 o[kD / 32];
+#pragma unroll
+  for (int ob = 0; ob < kD / 32; ++ob)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[ob][i] = 0.f;
+  float m_run = -1.0e30f, l_run = 0.f;
+
+  for (int hh = 0; hh < n_half; ++hh) {
+    // this wave's bytes of pair hh have landed once only its part of pair hh+1 is outstanding
+    if (hh + 1 < n_half) wait_vmcnt<2 * kPerWave>();
+    else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();  // every wave is done with the working pair of half tile hh-1 ...
+    asm volatile("" ::: "memory");
+    // ... and widened its rows of staged pair hh-1 before that: the slot takes pair hh+2
+    if (hh + 2 < n_half) issue_pair(hh + 2);
+    widen_pair(hh);
+    __syncthreads();  // the working pair is complete (LDS writes of all waves visible)
+    if (!active) continue;
+    int start, len;
+    half_ref(hh, start, len);
+    half_tile_attend(work_k, work_v, len, k_base, v_base, half, qf, o, m_run, l_run);
+  }
+
+  const float l_tot = half_swap_sum(l_run);
+  if (col_valid) {
+    float* part = p.partial + (static_cast<int64_t>(slot) * p.n_q_heads + head) * (kD + kPartialPad);
+#pragma unroll
+    for (int ob = 0; ob < kD / 32; ++ob)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<floatx4*>(part + 32 * ob + 8 * g + 4 * half) =
+            floatx4{o[ob][4 * g] * v_scale, o[ob][4 * g + 1] * v_scale, o[ob][4 * g + 2] * v_scale,
+                    o[ob][4 * g + 3] * v_scale};
+    if (half == 0) {
+      part[kD] = m_run;
+      part[kD + 1] = l_tot;
+    }
+  }
+}
+
 // Merge the partial states of one (query, head): slots [slot_ptr[u], slot_ptr[u+1]).
 // 2 x 128 threads: thread (part, d) owns output channel d for the slots of its parity.  The
 // per-slot maxima and sums are read with one slot per thread (not one after the other by
@@ -915,6 +1082,28 @@ namespace {
 dim3 decode_grid(const AttnParams& p) { return dim3(static_cast<unsigned>(p.n_kv_heads) * p.launch_rows * 8); }
 }  // namespace
 
+namespace {
+template <int W>
+hipError_t launch_shared8(const AttnParams& p, hipStream_t stream) {
+  static std::atomic<bool> attr_set{false};  // setting it twice from two threads is harmless
+  if (!attr_set) {
+    for (const void* f : {reinterpret_cast<const void*>(decode_group_kv8_shared_kernel<W, false>),
+                          reinterpret_cast<const void*>(decode_group_kv8_shared_kernel<W, true>)}) {
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsShared8);
+      if (e != hipSuccess) return e;
+    }
+    attr_set = true;
+  }
+  const dim3 grid = decode_grid(p), block(64 * W);
+  if (p.rope_table)
+    decode_group_kv8_shared_kernel<W, true><<<grid, block, kLdsShared8, stream>>>(p);
+  else
+    decode_group_kv8_shared_kernel<W, false><<<grid, block, kLdsShared8, stream>>>(p);
+  return hipGetLastError();
+}
+}  // namespace
+
+// p.decode_waves as for launch_decode_group (pool rows; the self rows below are single batches)
 hipError_t launch_decode_group_kv8(const AttnParams& p_in, hipStream_t stream) {
   static std::atomic<bool> attr_set{false};  // setting it twice from two threads is harmless
   if (!attr_set) {
@@ -934,11 +1123,18 @@ hipError_t launch_decode_group_kv8(const AttnParams& p_in, hipStream_t stream) {
   if (p.n_gm_items > 0) {
     p.row_offset = 0;
     p.launch_rows = p.gm_pool_rows;
-    if (p.rope_table)
-      decode_group_kv8_kernel<true><<<decode_grid(p), dim3(64), kLds8, stream>>>(p);
-    else
-      decode_group_kv8_kernel<false><<<decode_grid(p), dim3(64), kLds8, stream>>>(p);
-    hipError_t e = hipGetLastError();
+    hipError_t e;
+    if (p.decode_waves == 4)
+      e = launch_shared8<4>(p, stream);
+    else if (p.decode_waves == 2)
+      e = launch_shared8<2>(p, stream);
+    else {
+      if (p.rope_table)
+        decode_group_kv8_kernel<true><<<decode_grid(p), dim3(64), kLds8, stream>>>(p);
+      else
+        decode_group_kv8_kernel<false><<<decode_grid(p), dim3(64), kLds8, stream>>>(p);
+      e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
   }
   // every query's own (bf16) cache: the self items of the ordinary kernel

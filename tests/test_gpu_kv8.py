@@ -137,3 +137,11 @@ def test_fp8_decode_takes_the_rescale_path_when_row_maxima_keep_growing():
     qc = synth.make_query_case("kv8rampq", 6031, pc, n_queries=12, q_len=20, n_select=2, n_decode=2)
     qc.dec_q = synth.f32_to_bf16_bits(c * u[None, None, None, :] + rng.standard_normal(qc.dec_q.shape).astype(np.float32))
     _decode_case(pc, qc, range(2), what="ramped keys")
+
+
+def test_decode_over_an_fp8_pool_config4_full_size():
+    """128 concurrent queries at 30 %: a group serves ~40 of them, so the step runs the kernel whose
+    four waves share (and share the widening of) an item's half tiles."""
+    pc = synth.config2_pool()
+    qc = synth.config4_query(pc, 0.30)
+    _decode_case(pc, qc, (0,), queries=(0, 31, 64, 127), what="cfg4 30 %")
