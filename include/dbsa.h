@@ -309,6 +309,26 @@ int dbsa_decode_attn(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_tensor 
                      float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * dbsa_decode_attn for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, arithmetic and results as dbsa_decode_attn, but the partial softmax states go
+ * to a fixed buffer of DBSA_STATIC_SCRATCH_BYTES that is part of the library image (one copy
+ * per GPU the library runs on, held until the process ends).  The call allocates nothing on
+ * the device and frees nothing.
+ * Limit: the step's partial states -- (head_dim + 4) floats per query head and slot, slots =
+ * max(B * n_split, slot_ptr[B]) -- must fit the buffer, else DBSA_ERR_WORKSPACE and nothing
+ * is launched (config 3 needs about 14 MiB).  Nothing in the buffer has to start at zero: every
+ * slot a step reads was written by the same step.  All calls on one GPU share the buffer, so
+ * two calls of this entry point that overlap on one GPU (different streams, or replays of
+ * graphs that recorded it) race; calls on one stream are ordered and safe.
+ */
+#define DBSA_STATIC_SCRATCH_BYTES (32u << 20)
+int dbsa_decode_attn_static(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_tensor k_selfcache,
+                            dbsa_tensor v_selfcache, const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool,
+                            dbsa_tensor v_pool, dbsa_tensor o, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads,
+                            int32_t head_dim, float softmax_scale, void* stream);
+
+/*
  * ---- query stage with re-positioning (Sec. 2.2) --------------------------------------------
  * The paper caches the pool's keys before the rotary transformation and, per test query,
  * re-applies it to the concatenated selected caches with new in-order position ids.  Here the

@@ -38,8 +38,9 @@ EXPORTED_SYMBOLS = (
     "dbsa_strerror", "dbsa_layout_build", "dbsa_layout_build_append", "dbsa_layout_export", "dbsa_layout_export_decode",
     "dbsa_layout_export_decode_groups", "dbsa_layout_export_order", "dbsa_layout_export_positions", "dbsa_layout_destroy", "dbsa_workspace_bytes", "dbsa_preencode_attn",
     "dbsa_query_attn", "dbsa_decode_attn", "dbsa_rope_table", "dbsa_rope_apply", "dbsa_query_attn_rope",
-    "dbsa_decode_attn_rope", "dbsa_decode_attn_kv8", "dbsa_decode_attn_kv8_rope",
+    "dbsa_decode_attn_rope", "dbsa_decode_attn_kv8", "dbsa_decode_attn_kv8_rope", "dbsa_decode_attn_static",
 )
+DBSA_STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class DbsaError(RuntimeError):
@@ -125,6 +126,9 @@ def lib() -> C.CDLL:
     L.dbsa_decode_attn.restype = C.c_int
     L.dbsa_decode_attn.argtypes = [C.c_void_p, Tensor, Tensor, Tensor, C.c_void_p, C.c_int64, Tensor, Tensor,
                                    Tensor] + tail
+    L.dbsa_decode_attn_static.restype = C.c_int
+    L.dbsa_decode_attn_static.argtypes = [C.c_void_p, Tensor, Tensor, Tensor, C.c_void_p, C.c_int64, Tensor, Tensor,
+                                          Tensor, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_void_p]
     L.dbsa_decode_attn_kv8_rope.restype = C.c_int
     L.dbsa_decode_attn_kv8_rope.argtypes = [C.c_void_p, Tensor, Tensor, Tensor, C.c_void_p, C.c_int64, Tensor, Tensor,
                                             C.c_void_p, C.c_void_p, Tensor, C.c_void_p, C.c_int32, C.c_int32,
@@ -346,6 +350,20 @@ def dbsa_decode_attn(layout: Layout, q_step, k_cache, v_cache, self_len, k_pool,
                                 C.c_void_p(_stream()))
     _check(rc, "dbsa_decode_attn")
     return o
+
+
+def dbsa_decode_attn_static(layout: Layout, q_step, k_cache, v_cache, self_len, k_pool, v_pool, scale: float, out):
+    """dbsa_decode_attn with the partial states in the library's fixed buffer: no workspace argument,
+    and ``out`` is required so that nothing is allocated on the way."""
+    assert k_cache.dim() == 4 and k_cache.stride(3) == 1 and v_cache.stride() == k_cache.stride()
+    kc = Tensor(k_cache.data_ptr(), k_cache.stride(1), k_cache.stride(2))
+    vc = Tensor(v_cache.data_ptr(), v_cache.stride(1), v_cache.stride(2))
+    rc = lib().dbsa_decode_attn_static(layout.handle, _tensor(q_step), kc, vc, C.c_void_p(self_len.data_ptr()),
+                                       k_cache.stride(0), _tensor(k_pool), _tensor(v_pool), _tensor(out),
+                                       _dtype_code(q_step), q_step.shape[1], k_pool.shape[1], q_step.shape[2],
+                                       float(scale), C.c_void_p(_stream()))
+    _check(rc, "dbsa_decode_attn_static")
+    return out
 
 
 # ---------------------------------------------------------------------------

@@ -13,7 +13,35 @@
 #include "kernels.hpp"
 #include "layout.hpp"
 
+// Partial-state buffer of dbsa_decode_attn_static: one copy per GPU, held until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress; the device address it yields
+// (one per device) is what kernels and copies receive.
+constexpr size_t kStaticScratchBytes = DBSA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up once per device.
+hipError_t static_scratch(void** out) {
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return e;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
 
 // Device blocks (with a pinned staging twin) are recycled between layouts: allocation
 // calls, not the copied bytes, dominate the cost of a layout build.  Nothing here waits for
@@ -247,6 +275,13 @@ constexpr int64_t kWorkgroupSlots = 512;
 constexpr int64_t kMaxQuerySplit = 4;
 constexpr int64_t kMinRun = 16;
 
+// bytes of partial states one decode step writes: the larger of its two schedules
+size_t decode_workspace_need(const dbsa_layout* L, int32_t n_q_heads, int32_t head_dim) {
+  const size_t slots = std::max<size_t>(static_cast<size_t>(L->n_queries) * L->n_split,
+                                        L->gm_slot_ptr.empty() ? 0 : static_cast<size_t>(L->gm_slot_ptr.back()));
+  return slots * n_q_heads * (head_dim + kPartialPad) * sizeof(float);
+}
+
 bool mfma_tile_sizes_ok(const dbsa_layout* L) {
   const int bm = L->block_m;
   return L->block_n == 64 && (bm == 32 || bm == 64 || bm == 128 || bm == 256);
@@ -360,7 +395,7 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
                   const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool, dbsa_tensor v_pool,
                   dbsa_tensor o, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                   float softmax_scale, void* workspace, size_t workspace_bytes, void* stream,
-                  const float* rope_table, int32_t rope_n_pos);
+                  const float* rope_table, int32_t rope_n_pos, size_t need_bytes = 0);
 
 }  // namespace
 
@@ -513,6 +548,21 @@ int dbsa_decode_attn(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_sel
                        n_q_heads, n_kv_heads, head_dim, softmax_scale, workspace, workspace_bytes, stream, nullptr, 0);
 }
 
+int dbsa_decode_attn_static(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache,
+                            dbsa_tensor v_selfcache, const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool,
+                            dbsa_tensor v_pool, dbsa_tensor o, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads,
+                            int32_t head_dim, float softmax_scale, void* stream) {
+  if (!L || !L->query_stage || n_q_heads <= 0 || head_dim <= 0) return DBSA_ERR_INVALID_ARG;
+  // the partial states of this step must fit the fixed buffer
+  const size_t need = decode_workspace_need(L, n_q_heads, head_dim);
+  if (need > kStaticScratchBytes) return DBSA_ERR_WORKSPACE;
+  void* ptr = nullptr;
+  if (static_scratch(&ptr) != hipSuccess) return DBSA_ERR_HIP;
+  return decode_common(L, q_step, k_selfcache, v_selfcache, self_len, stride_query, k_pool, v_pool, o, dtype,
+                       n_q_heads, n_kv_heads, head_dim, softmax_scale, ptr, kStaticScratchBytes, stream, nullptr, 0,
+                       std::max<size_t>(need, 1));
+}
+
 namespace {
 int decode_kv8_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfcache, dbsa_tensor v_selfcache,
                       const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool8, dbsa_tensor v_pool8,
@@ -636,7 +686,7 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
                   const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool, dbsa_tensor v_pool,
                   dbsa_tensor o, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                   float softmax_scale, void* workspace, size_t workspace_bytes, void* stream,
-                  const float* rope_table, int32_t rope_n_pos) {
+                  const float* rope_table, int32_t rope_n_pos, size_t need_bytes) {
   if (!L || !L->on_device || !L->query_stage || !self_len) return DBSA_ERR_INVALID_ARG;
   if (int rc = check_shapes(dtype, n_q_heads, n_kv_heads, head_dim, softmax_scale)) return rc;
   if (!tensor_ok(q_step, dtype) || !tensor_ok(k_selfcache, dtype) || !tensor_ok(v_selfcache, dtype) ||
@@ -670,7 +720,8 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
   if (e != hipSuccess) return DBSA_ERR_HIP;
   if (dtype == DBSA_BF16) {
     if (L->block_n != 64 || n_q_heads / n_kv_heads > 32) return DBSA_ERR_UNSUPPORTED;
-    const size_t need = dbsa_workspace_bytes(L, n_q_heads, head_dim);
+    // need_bytes: what the caller has checked the step to write (the fixed-buffer entry point)
+    const size_t need = need_bytes ? need_bytes : dbsa_workspace_bytes(L, n_q_heads, head_dim);
     if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
       return DBSA_ERR_WORKSPACE;
     p.partial = static_cast<float*>(workspace);
