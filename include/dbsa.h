@@ -215,6 +215,20 @@ int dbsa_layout_export_decode_groups(const dbsa_layout* layout, const int64_t** 
  * of an owner first. */
 int dbsa_layout_export_order(const dbsa_layout* layout, const int32_t** order, int64_t* n_order);
 
+/*
+ * Schedule of a persistent prefill-shaped launch (plumbing of the launches, not an operation of
+ * the paper): large launches run as many workgroups as the chip holds, n_classes of them per
+ * block of query heads, and worker c walks the Q tiles records[4 * class_ptr[c]] ..
+ * records[4 * class_ptr[c+1]) one after the other, four int32 each: (q_start, q_len, first list
+ * entry, list entries).  Every Q tile appears exactly once.  Tiles are dealt in launch order in
+ * rounds of n_classes, the longest list of a round to the worker with the least work so far (work
+ * of a tile = its list entries + 3).  A layout keeps ONE schedule, fixed by the first call that
+ * needs one (this call or an attention call): INVALID_ARG for another n_classes later, for
+ * n_classes outside [1, 512] or a NULL layout.  The arrays belong to the layout.
+ */
+int dbsa_layout_export_schedule(const dbsa_layout* layout, int32_t n_classes, const int32_t** class_ptr,
+                                const int32_t** records);
+
 /* NULL is allowed.  Does not wait for the device: it may be called right after the last launch
  * that uses the layout.  The device lists stay intact until every stream the layout was used on
  * has passed the point of this call (one event per such stream is recorded here, so those

@@ -39,6 +39,7 @@ EXPORTED_SYMBOLS = (
     "dbsa_layout_export_decode_groups", "dbsa_layout_export_order", "dbsa_layout_export_positions", "dbsa_layout_destroy", "dbsa_workspace_bytes", "dbsa_preencode_attn",
     "dbsa_query_attn", "dbsa_decode_attn", "dbsa_rope_table", "dbsa_rope_apply", "dbsa_query_attn_rope",
     "dbsa_decode_attn_rope", "dbsa_decode_attn_kv8", "dbsa_decode_attn_kv8_rope", "dbsa_decode_attn_static",
+    "dbsa_layout_export_schedule",
 )
 DBSA_STATIC_SCRATCH_BYTES = 32 << 20
 
@@ -99,6 +100,9 @@ def lib() -> C.CDLL:
     L.dbsa_layout_export_positions.argtypes = [C.c_void_p] + [C.POINTER(C.POINTER(C.c_int32))] * 3
     L.dbsa_layout_export_order.restype = C.c_int
     L.dbsa_layout_export_order.argtypes = [C.c_void_p, C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int64)]
+    L.dbsa_layout_export_schedule.restype = C.c_int
+    L.dbsa_layout_export_schedule.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.POINTER(C.c_int32)),
+                                              C.POINTER(C.POINTER(C.c_int32))]
     L.dbsa_layout_destroy.restype = None
     L.dbsa_layout_destroy.argtypes = [C.c_void_p]
     L.dbsa_workspace_bytes.restype = C.c_size_t
@@ -231,6 +235,16 @@ class Layout:
         def arr(p, n):
             return np.ctypeslib.as_array(p, shape=(n,)).copy() if n else np.zeros(0, np.int32)
         return arr(ls, n_ent), arr(qs, nr.value), arr(cl, n_queries)
+
+    def export_schedule(self, n_classes: int):
+        """-> (class_ptr [n_classes+1], records [n_qtiles, 4]) int32 copies."""
+        cp, rc = C.POINTER(C.c_int32)(), C.POINTER(C.c_int32)()
+        _check(lib().dbsa_layout_export_schedule(self.handle, int(n_classes), C.byref(cp), C.byref(rc)),
+               "dbsa_layout_export_schedule")
+        ptr = np.ctypeslib.as_array(cp, shape=(n_classes + 1,)).copy()
+        n = int(ptr[-1])
+        rec = np.ctypeslib.as_array(rc, shape=(n, 4)).copy() if n else np.zeros((0, 4), np.int32)
+        return ptr, rec
 
     def workspace_bytes(self, n_q_heads: int, head_dim: int) -> int:
         return int(lib().dbsa_workspace_bytes(self.handle, n_q_heads, head_dim))

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libdbsa.so")
-SOURCES = ["layout.cpp", "api.hip", "attn_prefill.hip", "attn_decode.hip", "attn_mfma.hip", "attn_plain.hip", "rope.hip"]
+SOURCES = ["layout.cpp", "api.hip", "attn_prefill.hip", "attn_prefill64.hip", "attn_decode.hip", "attn_mfma.hip", "attn_plain.hip", "rope.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

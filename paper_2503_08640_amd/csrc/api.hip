@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -126,11 +127,13 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
                b_dec = L->dec_ent.size() * sizeof(int32_t), b_spl = L->split_ptr.size() * sizeof(int64_t),
                b_gsp = L->gm_slot_ptr.size() * sizeof(int64_t),
                b_lsh = L->list_shift.size() * sizeof(int32_t), b_gir = L->gm_item_run.size() * sizeof(int32_t),
-               b_grp = L->gm_ref_pad.size() * sizeof(int32_t), b_grw = L->gm_rows.size() * sizeof(int32_t);
+               b_grp = L->gm_ref_pad.size() * sizeof(int32_t), b_grw = L->gm_rows.size() * sizeof(int32_t),
+               b_srec = L->qtile_tab.size() * sizeof(int32_t), b_sptr = (kMaxSchedClasses + 1) * sizeof(int32_t);
   const size_t o_tab = 0, o_ptr = o_tab + pad(b_tab), o_ent = o_ptr + pad(b_ptr), o_ord = o_ent + pad(b_ent),
                o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), o_gsp = o_spl + pad(b_spl),
                o_lsh = o_gsp + pad(b_gsp), o_gir = o_lsh + pad(b_lsh), o_grp = o_gir + pad(b_gir),
-               o_grw = o_grp + pad(b_grp), total = o_grw + pad(b_grw) + 256;
+               o_grw = o_grp + pad(b_grp), o_srec = o_grw + pad(b_grw), o_sptr = o_srec + pad(b_srec),
+               lists_end = o_srec, total = o_sptr + pad(b_sptr) + 256;
   ListBlock blk{};
   hipError_t e = acquire_block(total, &blk);
   if (e != hipSuccess) return e;
@@ -154,7 +157,8 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   hipEvent_t uploaded = nullptr;
   e = hipEventCreateWithFlags(&uploaded, hipEventDisableTiming);
   if (e == hipSuccess) {
-    e = hipMemcpyAsync(blk.dev, blk.pinned, total, hipMemcpyHostToDevice, stream);
+    // (the room behind lists_end is filled by the first call that uses a schedule)
+    e = hipMemcpyAsync(blk.dev, blk.pinned, lists_end, hipMemcpyHostToDevice, stream);
     if (e == hipSuccess) e = hipEventRecord(uploaded, stream);
     if (e != hipSuccess) {
       (void)hipStreamSynchronize(stream);  // the copy may have been queued: the block must not be reused under it
@@ -183,6 +187,8 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   L->dev.gm_item_run = reinterpret_cast<int32_t*>(b + o_gir);
   L->dev.gm_ref_pad = reinterpret_cast<int32_t*>(b + o_grp);
   L->dev.gm_rows = reinterpret_cast<int32_t*>(b + o_grw);
+  L->dev.sched_rec = reinterpret_cast<int32_t*>(b + o_srec);
+  L->dev.sched_ptr = reinterpret_cast<int32_t*>(b + o_sptr);
   return hipSuccess;
 }
 
@@ -220,6 +226,7 @@ void free_device_lists(dbsa_layout* L) {
       blk.busy.clear();
     }
     if (d.uploaded) (void)hipEventDestroy(static_cast<hipEvent_t>(d.uploaded));
+    if (d.sched_uploaded) (void)hipEventDestroy(static_cast<hipEvent_t>(d.sched_uploaded));
     release_block(blk);
     if (current != d.device) (void)hipSetDevice(current);
   }
@@ -238,6 +245,64 @@ hipError_t order_behind_upload(const dbsa_layout* L, hipStream_t stream) {
   }
   L->used_streams.push_back(s);
   return hipSuccess;
+}
+
+// compute units of the current device (what a persistent launch and the decode chunking are sized for)
+int device_compute_units() {
+  static std::mutex m;
+  static int cus[kMaxDevices] = {};
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return 256;
+  std::lock_guard<std::mutex> lock(m);
+  if (!cus[device]) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n <= 0) n = 256;
+    cus[device] = n;
+  }
+  return cus[device];
+}
+
+// The layout's schedule for a persistent launch with n_classes workers per head block, on the
+// device and ordered before `stream`'s next work.  A layout keeps ONE schedule: false if it
+// already holds one for another number of workers, or if the schedule would have to be copied
+// while the stream is being captured into a graph (the caller then launches one workgroup per tile).
+bool ensure_schedule(const dbsa_layout* L, int32_t n_classes, hipStream_t stream) {
+  if (n_classes < 1 || n_classes > kMaxSchedClasses || !L->dev.sched_rec) return false;
+  std::lock_guard<std::mutex> lock(L->sched_mutex);
+  if (L->sched_classes != 0 && L->sched_classes != n_classes) return false;
+  if (!L->sched_on_device) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
+      (void)hipGetLastError();
+      return false;
+    }
+    if (L->sched_classes == 0) {
+      dbsa_balance_schedule(L, n_classes, &L->sched_ptr, &L->sched_rec);
+      L->sched_classes = n_classes;
+    }
+    // through the pinned twin of the device block, at the same offsets
+    unsigned char* dev = static_cast<unsigned char*>(L->dev.base);
+    unsigned char* pin = static_cast<unsigned char*>(L->dev.staging);
+    const size_t o_rec = reinterpret_cast<unsigned char*>(L->dev.sched_rec) - dev;
+    const size_t o_ptr = reinterpret_cast<unsigned char*>(L->dev.sched_ptr) - dev;
+    const size_t b_ptr = L->sched_ptr.size() * sizeof(int32_t);
+    std::memcpy(pin + o_rec, L->sched_rec.data(), L->sched_rec.size() * sizeof(int32_t));
+    std::memcpy(pin + o_ptr, L->sched_ptr.data(), b_ptr);
+    hipEvent_t done = nullptr;
+    if (hipEventCreateWithFlags(&done, hipEventDisableTiming) != hipSuccess) return false;
+    if (hipMemcpyAsync(dev + o_rec, pin + o_rec, o_ptr + b_ptr - o_rec, hipMemcpyHostToDevice, stream) != hipSuccess ||
+        hipEventRecord(done, stream) != hipSuccess) {
+      (void)hipStreamSynchronize(stream);
+      (void)hipEventDestroy(done);
+      return false;
+    }
+    L->dev.sched_uploaded = done;
+    L->dev.sched_stream = stream;
+    L->sched_on_device = true;
+  } else if (stream != L->dev.sched_stream) {
+    if (hipStreamWaitEvent(stream, static_cast<hipEvent_t>(L->dev.sched_uploaded), 0) != hipSuccess) return false;
+  }
+  return true;
 }
 
 bool tensor_ok(const dbsa_tensor& t, int dtype) {
@@ -381,6 +446,23 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
         p.partial = static_cast<float*>(workspace);
       }
     }
+    // Launches with several Q tiles per workgroup place run persistently: as many workgroups as the
+    // chip holds (one of four waves or two of two per compute unit), each walking a balanced share
+    // of the Q tiles of its head block.
+    const int row_blocks = p.heads_per_block * (L->block_m / 32);
+    static const bool no_persist = getenv("DBSA_NO_PERSIST") != nullptr;  // (development switch)
+    if (!no_persist && d == 128 && max_stride < (int64_t{1} << 24) && !rope_table && p.q_split == 1 &&
+        (row_blocks == 4 || row_blocks == 8)) {
+      const int64_t head_blocks = hq / p.heads_per_block;
+      const int64_t places = static_cast<int64_t>(device_compute_units()) * (row_blocks == 8 ? 1 : 2);
+      const int64_t classes = places / head_blocks;
+      if (classes >= 1 && L->n_qtiles() >= 2 * classes && ensure_schedule(L, static_cast<int32_t>(classes), static_cast<hipStream_t>(stream))) {
+        p.sched_rec = L->dev.sched_rec;
+        p.sched_ptr = L->dev.sched_ptr;
+        p.sched_classes = static_cast<int32_t>(classes);
+        p.n_head_blocks = static_cast<int32_t>(head_blocks);
+      }
+    }
     e = (d == 128 && max_stride < (int64_t{1} << 24))
             ? launch_prefill_pipelined(p, static_cast<hipStream_t>(stream))
             : launch_prefill_mfma(p, d, static_cast<hipStream_t>(stream));
@@ -506,6 +588,24 @@ int dbsa_layout_export_order(const dbsa_layout* L, const int32_t** order, int64_
   if (!L) return DBSA_ERR_INVALID_ARG;
   if (order) *order = L->order.data();
   if (n_order) *n_order = static_cast<int64_t>(L->order.size());
+  return DBSA_OK;
+}
+
+int dbsa_layout_export_schedule(const dbsa_layout* L, int32_t n_classes, const int32_t** class_ptr,
+                                const int32_t** records) {
+  if (!L || n_classes < 1 || n_classes > kMaxSchedClasses) return DBSA_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(L->sched_mutex);
+  if (L->sched_classes != 0 && L->sched_classes != n_classes) return DBSA_ERR_INVALID_ARG;
+  if (L->sched_classes == 0) {
+    try {
+      dbsa_balance_schedule(L, n_classes, &L->sched_ptr, &L->sched_rec);
+    } catch (...) {
+      return DBSA_ERR_INVALID_ARG;
+    }
+    L->sched_classes = n_classes;
+  }
+  if (class_ptr) *class_ptr = L->sched_ptr.data();
+  if (records) *records = L->sched_rec.data();
   return DBSA_OK;
 }
 

@@ -33,6 +33,7 @@
 //     row of the wave outgrows it, which is rare once a few tiles have been seen.
 #include <atomic>
 #include <cstdint>
+#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -644,6 +645,17 @@ hipError_t launch_stage(const AttnParams& p, hipStream_t stream) {
 hipError_t launch_prefill_pipelined(const AttnParams& p, hipStream_t stream) {
   if (p.n_qtiles == 0) return hipSuccess;
   const int row_blocks = p.heads_per_block * (p.block_m / 32);
+  // with a persistent schedule: the kernel with 64 rows per wave, one wave per SIMD
+  static const bool force64 = getenv("DBSA_PREFILL64") != nullptr;  // (development switch: that kernel without a schedule)
+  if ((p.sched_rec || force64) && !p.rope_table && (row_blocks == 4 || row_blocks == 8)) {
+    hipError_t e = launch_prefill64(p, stream);
+    const int n_split = p.q_split > 1 ? p.q_split : 1;
+    if (e != hipSuccess || n_split == 1) return e;
+    const int64_t pairs = static_cast<int64_t>(p.n_rows) * p.n_q_heads;
+    prefill_merge_kernel<<<dim3(static_cast<unsigned>((pairs + kMergePairs - 1) / kMergePairs)), dim3(32 * kMergePairs), 0,
+                           stream>>>(p, p.n_rows, n_split);
+    return hipGetLastError();
+  }
   switch (row_blocks) {
     case 1: return launch_stage<1, 1>(p, stream);
     case 2: return launch_stage<2, 1>(p, stream);

@@ -56,6 +56,12 @@ struct AttnParams {
   // shapes
   int32_t n_q_heads, n_kv_heads, block_m, block_n;
   int32_t heads_per_block;    // query heads handled by one workgroup (divides Hq/Hkv)
+  // persistent prefill-shaped launch (null: one workgroup per Q tile): workgroup w serves head block
+  // w % n_head_blocks and records sched_ptr[c] .. sched_ptr[c+1]-1, c = w / n_head_blocks, of
+  // sched_rec = [n_qtiles][4] (q_start, q_len, first list entry, entries)
+  const int32_t* sched_rec;
+  const int32_t* sched_ptr;
+  int32_t sched_classes, n_head_blocks;
   int32_t query_stage;        // prefill-shaped calls: 1 = query prefill (lists may name self tiles), 0 = pre-encode
   // re-positioning (null table: inputs carry their final positions already)
   const float* rope_table;    // [rope_n_pos][D/2][2] fp32 (cos, sin) of id * inv_freq
@@ -72,6 +78,9 @@ struct AttnParams {
 hipError_t launch_prefill_mfma(const AttnParams& p, int head_dim, hipStream_t stream);
 // software-pipelined variant for head_dim 128 (attn_prefill.hip)
 hipError_t launch_prefill_pipelined(const AttnParams& p, hipStream_t stream);
+// the same mathematics with 64 query rows per wave, one wave per SIMD (attn_prefill64.hip); kernel
+// only: launch_prefill_pipelined runs the merge pass of a split launch
+hipError_t launch_prefill64(const AttnParams& p, hipStream_t stream);
 // group-major split-KV decode + merge for head_dim 128 (attn_decode.hip)
 hipError_t launch_decode_group(const AttnParams& p, hipStream_t stream);
 // the same with pool K/V stored as fp8 (e4m3) bytes and per-KV-head scales

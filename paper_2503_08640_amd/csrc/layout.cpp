@@ -359,3 +359,37 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
   });
   return DBSA_OK;
 }
+
+void dbsa_balance_schedule(const dbsa_layout* L, int32_t n_classes, std::vector<int32_t>* class_ptr,
+                           std::vector<int32_t>* rec) {
+  constexpr int64_t kTileCost = 3;  // what a Q tile costs beyond its list, in list entries
+  const int64_t nt = L->n_qtiles();
+  std::vector<int64_t> load(static_cast<size_t>(n_classes), 0);
+  std::vector<std::vector<int32_t>> tiles_of(static_cast<size_t>(n_classes));
+  std::vector<int32_t> round, by_load(static_cast<size_t>(n_classes));
+  auto entries = [&](int32_t t) { return L->list_ptr[t + 1] - L->list_ptr[t]; };
+  for (int64_t a = 0; a < nt; a += n_classes) {
+    const int64_t b = std::min<int64_t>(nt, a + n_classes);
+    round.assign(L->order.begin() + a, L->order.begin() + b);
+    std::stable_sort(round.begin(), round.end(), [&](int32_t x, int32_t y) { return entries(x) > entries(y); });
+    std::iota(by_load.begin(), by_load.end(), 0);
+    std::stable_sort(by_load.begin(), by_load.end(), [&](int32_t x, int32_t y) { return load[x] < load[y]; });
+    for (size_t i = 0; i < round.size(); ++i) {
+      const int32_t c = by_load[i];
+      tiles_of[c].push_back(round[i]);
+      load[c] += entries(round[i]) + kTileCost;
+    }
+  }
+  class_ptr->assign(static_cast<size_t>(n_classes) + 1, 0);
+  rec->clear();
+  rec->reserve(static_cast<size_t>(nt) * 4);
+  for (int32_t c = 0; c < n_classes; ++c) {
+    for (int32_t t : tiles_of[c]) {
+      rec->push_back(L->qtile_tab[4 * t + 0]);
+      rec->push_back(L->qtile_tab[4 * t + 1]);
+      rec->push_back(static_cast<int32_t>(L->list_ptr[t]));
+      rec->push_back(static_cast<int32_t>(entries(t)));
+    }
+    (*class_ptr)[c + 1] = static_cast<int32_t>(rec->size() / 4);
+  }
+}

@@ -25,6 +25,12 @@ struct dbsa_device_lists {
   int32_t* gm_item_run = nullptr; // [n_items][4]
   int32_t* gm_ref_pad = nullptr;  // [n_items][32][4]
   int32_t* gm_rows = nullptr;
+  // room for ONE persistent-launch schedule (dbsa_layout::sched), filled by the first prefill-shaped
+  // call that uses one
+  int32_t* sched_rec = nullptr;   // [n_qtiles][4]
+  int32_t* sched_ptr = nullptr;   // [kMaxSchedClasses + 1]
+  void* sched_uploaded = nullptr; // event recorded behind the schedule's copy
+  void* sched_stream = nullptr;   // stream of that copy
   // ordering of the asynchronous upload against the calls that read the lists (HIP handles kept
   // as plain pointers so that host-only code can include this header)
   void* upload_stream = nullptr;  // stream the lists were copied on
@@ -79,7 +85,16 @@ struct dbsa_layout {
   int64_t shortest_list = 0;        // fewest entries any Q tile lists
   int64_t max_rotation_id = -1;     // largest id a prefill row looks up: max(list_shift[e] + rows of the tile) - 1
 
-  dbsa_device_lists dev;
+  // Schedule of a persistent prefill-shaped launch for n_classes workers (dbsa_balance_schedule),
+  // computed by the first call that needs one and kept: class c walks records
+  // sched_ptr[c] .. sched_ptr[c+1]-1 of sched_rec, four words each (q_start, q_len, first list
+  // entry, entries).  0 classes: none yet.
+  mutable std::mutex sched_mutex;
+  mutable int32_t sched_classes = 0;
+  mutable std::vector<int32_t> sched_ptr, sched_rec;
+  mutable bool sched_on_device = false;
+
+  mutable dbsa_device_lists dev;
   // direction of the last walk over the pool's keys by an attention call on this layout (the
   // decode call alternates it); not part of the lists, hence mutable
   mutable std::atomic<int> last_walk_reversed{0};
@@ -91,6 +106,16 @@ struct dbsa_layout {
   int64_t n_qtiles() const { return static_cast<int64_t>(qtile_tab.size() / 4); }
   int64_t n_ent() const { return static_cast<int64_t>(list_ent.size() / 2); }
 };
+
+constexpr int32_t kMaxSchedClasses = 512;
+
+// Deals the Q tiles of a layout to n_classes workers for a launch in which every worker walks its
+// tiles one after the other: tiles are taken in launch order (owner-major, so that at any time all
+// workers read the K/V of the same owner) in rounds of n_classes, and within a round the longest
+// list goes to the worker with the least work so far.  Work of a tile = its list entries + a fixed
+// cost per tile.  Pure host integer work.
+void dbsa_balance_schedule(const dbsa_layout* L, int32_t n_classes, std::vector<int32_t>* class_ptr,
+                           std::vector<int32_t>* rec);
 
 // Pure host integer work; returns a DBSA_* code and fills `L` on success.
 // first_group < 0: every segment; >= 0 (pre-encode only): Q tiles of groups first_group.. alone
