@@ -229,6 +229,13 @@ int dbsa_layout_export_order(const dbsa_layout* layout, const int32_t** order, i
 int dbsa_layout_export_schedule(const dbsa_layout* layout, int32_t n_classes, const int32_t** class_ptr,
                                 const int32_t** records);
 
+/*
+ * Device blocks (each with a pinned host twin) that hold the lists of destroyed layouts and wait
+ * to be reused by a later dbsa_layout_build (plumbing).  At most 16 are kept: idle blocks beyond
+ * that are freed, oldest first, when a layout is destroyed or a build has to allocate.
+ */
+int32_t dbsa_pooled_list_blocks(void);
+
 /* NULL is allowed.  Does not wait for the device: it may be called right after the last launch
  * that uses the layout.  The device lists stay intact until every stream the layout was used on
  * has passed the point of this call (one event per such stream is recorded here, so those
@@ -312,8 +319,9 @@ int dbsa_query_attn(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_tensor k
  * Successive calls on one layout alternate the direction in which every run of keys is walked
  * (front to back, back to front): a step reads the same selected keys as the step before, more
  * of them than the last-level cache holds, and what the previous step read last is still there.
- * The two directions differ by fp32 summation order only.  Calls on one layout from several
- * threads are safe; they merely share that alternation.
+ * The two directions differ by fp32 summation order only.  Only a call that passes every check
+ * and is launched changes the direction: a rejected call leaves the next one as it would have
+ * been.  Calls on one layout from several threads are safe; they merely share that alternation.
  * The call only launches kernels (no allocation, no memset, no host wait), so it may be
  * recorded into a HIP graph by stream capture; the direction is fixed at capture time.
  */
@@ -363,9 +371,12 @@ int dbsa_rope_table(const double* inv_freq, int32_t head_dim, int32_t n_pos, flo
 /*
  * out[t][h] = x[t][h] rotated at id positions[t] (device int32 [n_tokens]), or at first_id + t
  * when positions is NULL: the encoding-time rotation (pool keys: ids 0 .. N-1, Sec. 2.1; a
- * query's own keys: their index inside the query).  x and out may be the same tensor.  ids are
- * clamped to [0, n_pos).  head_dim a multiple of 16 up to 128.  Errors: INVALID_ARG,
- * UNSUPPORTED, HIP.
+ * query's own keys: their index inside the query).  x and out may be the same tensor.  With
+ * positions == NULL the ids are known to the host: INVALID_ARG unless 0 <= first_id and
+ * first_id + n_tokens <= n_pos.  ids read from `positions` live on the device and are not checked:
+ * the kernel clamps each to [0, n_pos), so an id outside the table gives the rotation of the
+ * nearest table row instead of a fault; keeping them inside is the caller's duty.  head_dim a
+ * multiple of 16 up to 128.  Errors: INVALID_ARG, UNSUPPORTED, HIP.
  */
 int dbsa_rope_apply(dbsa_tensor x, dbsa_tensor out, int32_t n_tokens, int32_t n_heads, int32_t head_dim, int32_t dtype,
                     const int32_t* positions, int32_t first_id, const float* table, int32_t n_pos, void* stream);
@@ -385,9 +396,11 @@ int dbsa_query_attn_rope(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_ten
 
 /*
  * dbsa_decode_attn with re-positioning.  q_step is UN-rotated; the self caches hold keys rotated
- * at their index inside the query (the new token, index self_len[u] - 1, included).  ids beyond
- * the table are clamped, so rope_n_pos must exceed qref_shift[ref] + self_len[u] for every
- * reference (2 * pool tokens + the longest self cache always suffices).
+ * at their index inside the query (the new token, index self_len[u] - 1, included).  A row looks
+ * up id qref_shift[ref] + self_len[u] - 1.  self_len lives on the device, so the host bounds it by
+ * what a query's cache can hold, Tmax = stride_query / k_selfcache.stride_tok tokens: INVALID_ARG
+ * unless rope_n_pos > max(qref_shift) + Tmax - 1 (2 * pool tokens + Tmax always suffices).  A
+ * self_len beyond Tmax is the caller's error; the kernel clamps the id to the table.
  * bf16, head_dim 128, 32 % (n_q_heads / n_kv_heads) == 0 (else UNSUPPORTED).
  */
 int dbsa_decode_attn_rope(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_tensor k_selfcache,

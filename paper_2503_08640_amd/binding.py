@@ -38,7 +38,7 @@ EXPORTED_SYMBOLS = (
     "dbsa_strerror", "dbsa_layout_build", "dbsa_layout_build_append", "dbsa_layout_export", "dbsa_layout_export_decode",
     "dbsa_layout_export_decode_groups", "dbsa_layout_export_order", "dbsa_layout_export_positions", "dbsa_layout_destroy", "dbsa_workspace_bytes", "dbsa_preencode_attn",
     "dbsa_query_attn", "dbsa_decode_attn", "dbsa_rope_table", "dbsa_rope_apply", "dbsa_query_attn_rope",
-    "dbsa_decode_attn_rope", "dbsa_decode_attn_kv8", "dbsa_decode_attn_kv8_rope", "dbsa_decode_attn_static",
+    "dbsa_decode_attn_rope", "dbsa_decode_attn_kv8", "dbsa_decode_attn_kv8_rope", "dbsa_decode_attn_static", "dbsa_pooled_list_blocks",
     "dbsa_layout_export_schedule",
 )
 DBSA_STATIC_SCRATCH_BYTES = 32 << 20
@@ -103,6 +103,8 @@ def lib() -> C.CDLL:
     L.dbsa_layout_export_schedule.restype = C.c_int
     L.dbsa_layout_export_schedule.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.POINTER(C.c_int32)),
                                               C.POINTER(C.POINTER(C.c_int32))]
+    L.dbsa_pooled_list_blocks.restype = C.c_int32
+    L.dbsa_pooled_list_blocks.argtypes = []
     L.dbsa_layout_destroy.restype = None
     L.dbsa_layout_destroy.argtypes = [C.c_void_p]
     L.dbsa_workspace_bytes.restype = C.c_size_t

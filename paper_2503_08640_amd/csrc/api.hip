@@ -59,7 +59,8 @@ struct ListBlock {
 };
 std::mutex g_pool_mutex;
 std::vector<ListBlock> g_pool_blocks;
-// blocks kept per process before a build waits for the oldest busy one instead of allocating
+// blocks kept per process: at the cap a build waits for the oldest busy block that fits instead of
+// allocating, and idle blocks beyond it are freed, oldest first
 constexpr size_t kMaxPoolBlocks = 16;
 
 bool block_idle(ListBlock& blk) {
@@ -71,6 +72,20 @@ bool block_idle(ListBlock& blk) {
   for (hipEvent_t ev : blk.busy) (void)hipEventDestroy(ev);
   blk.busy.clear();
   return true;
+}
+
+// Frees idle blocks, oldest first, until at most `keep` are pooled (g_pool_mutex held).  Blocks
+// still read by running work stay; they go at a later call.
+void trim_pool_locked(size_t keep) {
+  for (size_t i = 0; i < g_pool_blocks.size() && g_pool_blocks.size() > keep;) {
+    if (!block_idle(g_pool_blocks[i])) {
+      ++i;
+      continue;
+    }
+    (void)hipFree(g_pool_blocks[i].dev);
+    (void)hipHostFree(g_pool_blocks[i].pinned);
+    g_pool_blocks.erase(g_pool_blocks.begin() + static_cast<std::ptrdiff_t>(i));
+  }
 }
 
 hipError_t acquire_block(size_t bytes, ListBlock* out) {
@@ -101,6 +116,8 @@ hipError_t acquire_block(size_t bytes, ListBlock* out) {
       take(fits);
       return hipSuccess;
     }
+    // no pooled block is large enough: make room for the new one among those that are too small
+    if (g_pool_blocks.size() >= kMaxPoolBlocks) trim_pool_locked(kMaxPoolBlocks - 1);
   }
   ListBlock blk{nullptr, nullptr, (bytes + bytes / 2 + 65535) / 65536 * 65536, device, {}};
   e = hipMalloc(&blk.dev, blk.capacity);
@@ -117,6 +134,7 @@ hipError_t acquire_block(size_t bytes, ListBlock* out) {
 void release_block(const ListBlock& blk) {
   std::lock_guard<std::mutex> lock(g_pool_mutex);
   g_pool_blocks.push_back(blk);
+  trim_pool_locked(kMaxPoolBlocks);
 }
 
 // Copy every list into ONE device block with a single asynchronous copy from pinned memory.
@@ -334,11 +352,16 @@ int pick_heads_per_block(int r, int block_m) {
   return best;
 }
 
-// split query prefill: workgroups the chip holds at two per compute unit, most runs per list,
-// fewest tiles per run
-constexpr int64_t kWorkgroupSlots = 512;
+// split query prefill: most runs per list, fewest tiles per run
 constexpr int64_t kMaxQuerySplit = 4;
 constexpr int64_t kMinRun = 16;
+// The kernel that re-positions (attn_prefill.hip) starts a row's running maximum from the first
+// tile of its run, so that tile must hold a key the row sees.  Only the tiles on a Q tile's own
+// diagonal hide keys from some of its rows, they are the last block_m / 64 entries of a list and
+// every row sees the first of them: a run of more entries than that never starts behind it.
+static_assert(kMinRun > 256 / 64, "a run of a split list must reach back beyond the diagonal tiles of a Q tile");
+// workgroups the device the layout was built for holds at two per compute unit
+int64_t workgroup_slots(const dbsa_layout* L) { return 2 * static_cast<int64_t>(L->compute_units); }
 
 // bytes of partial states one decode step writes: the larger of its two schedules
 size_t decode_workspace_need(const dbsa_layout* L, int32_t n_q_heads, int32_t head_dim) {
@@ -350,6 +373,23 @@ size_t decode_workspace_need(const dbsa_layout* L, int32_t n_q_heads, int32_t he
 bool mfma_tile_sizes_ok(const dbsa_layout* L) {
   const int bm = L->block_m;
   return L->block_n == 64 && (bm == 32 || bm == 64 || bm == 128 || bm == 256);
+}
+
+// Every step reads the same selected keys, more of them than the last-level cache holds, so a
+// step that walks them in the order of the step before finds none of them cached.  Successive
+// decode calls on one layout therefore alternate the direction in which each run of keys is
+// walked (the query prefill walks forward): what the previous call read last is read first.
+// Called once a call has passed every check, so that a rejected call leaves the order of
+// summation of the next one as it was.
+int32_t next_walk_direction(const dbsa_layout* L) { return L->last_walk_reversed.fetch_xor(1) ^ 1; }
+
+// A re-positioning decode row of query u looks up id shift + self_len[u] - 1.  self_len lives on
+// the device; what the host knows is that a query's cache holds at most stride_query / stride_tok
+// tokens before it would run into the next query's, so the table must cover the largest shift of
+// the layout plus that many positions.
+bool decode_ids_in_table(const dbsa_layout* L, int64_t stride_query, int64_t stride_tok, int32_t rope_n_pos) {
+  const int64_t t_max = std::max<int64_t>(1, stride_query / std::max<int64_t>(stride_tok, 1));
+  return L->max_decode_shift + t_max - 1 < rope_n_pos;
 }
 
 // launch rows of the group-major decode for r query heads per KV head (32 % r == 0)
@@ -436,7 +476,7 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
     if (want_query_stage && d == 128 && workspace && reinterpret_cast<uintptr_t>(workspace) % 16 == 0) {
       const int64_t wgs = L->n_qtiles() * (hq / p.heads_per_block);
       // eight-wave workgroups (112 KiB of LDS) sit alone on a compute unit, smaller ones in pairs
-      const int64_t slots = p.heads_per_block * (L->block_m / 32) == 8 ? kWorkgroupSlots / 2 : kWorkgroupSlots;
+      const int64_t slots = workgroup_slots(L) / (p.heads_per_block * (L->block_m / 32) == 8 ? 2 : 1);
       int64_t split = wgs > 0 ? std::min<int64_t>(kMaxQuerySplit, (slots + wgs - 1) / wgs) : 1;
       split = std::min(split, L->shortest_list / kMinRun);
       const size_t need = static_cast<size_t>(L->n_query_tokens) * hq * static_cast<size_t>(std::max<int64_t>(split, 1)) *
@@ -450,11 +490,10 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
     // chip holds (one of four waves or two of two per compute unit), each walking a balanced share
     // of the Q tiles of its head block.
     const int row_blocks = p.heads_per_block * (L->block_m / 32);
-    static const bool no_persist = getenv("DBSA_NO_PERSIST") != nullptr;  // (development switch)
-    if (!no_persist && d == 128 && max_stride < (int64_t{1} << 24) && !rope_table && p.q_split == 1 &&
+    if (d == 128 && max_stride < (int64_t{1} << 24) && !rope_table && p.q_split == 1 &&
         (row_blocks == 4 || row_blocks == 8)) {
       const int64_t head_blocks = hq / p.heads_per_block;
-      const int64_t places = static_cast<int64_t>(device_compute_units()) * (row_blocks == 8 ? 1 : 2);
+      const int64_t places = static_cast<int64_t>(L->compute_units) * (row_blocks == 8 ? 1 : 2);
       const int64_t classes = places / head_blocks;
       if (classes >= 1 && L->n_qtiles() >= 2 * classes && ensure_schedule(L, static_cast<int32_t>(classes), static_cast<hipStream_t>(stream))) {
         p.sched_rec = L->dev.sched_rec;
@@ -503,6 +542,8 @@ int build_layout(const dbsa_pool_desc* pool, const dbsa_select_desc* sel, int32_
   dbsa_layout* L = new (std::nothrow) dbsa_layout();
   if (!L) return DBSA_ERR_INVALID_ARG;
   int rc = DBSA_OK;
+  // the decode chunking and the split / persistent prefill launches are sized for the current device
+  if (!(flags & DBSA_LAYOUT_HOST_ONLY)) L->compute_units = device_compute_units();
   try {
     rc = dbsa_build_host_lists(pool, sel, first_group, block_m, block_n, L);
   } catch (...) {
@@ -609,6 +650,11 @@ int dbsa_layout_export_schedule(const dbsa_layout* L, int32_t n_classes, const i
   return DBSA_OK;
 }
 
+int32_t dbsa_pooled_list_blocks(void) {
+  std::lock_guard<std::mutex> lock(g_pool_mutex);
+  return static_cast<int32_t>(g_pool_blocks.size());
+}
+
 void dbsa_layout_destroy(dbsa_layout* L) {
   if (!L) return;
   if (L->on_device) free_device_lists(L);
@@ -621,7 +667,7 @@ size_t dbsa_workspace_bytes(const dbsa_layout* L, int32_t n_q_heads, int32_t hea
                                   L->gm_slot_ptr.empty() ? 0 : static_cast<size_t>(L->gm_slot_ptr.back()));
   // a split query prefill keeps up to kMaxQuerySplit partial states per row; it is only used when
   // the launch has fewer workgroups than the chip holds, which bounds the number of Q tiles
-  if (L->n_qtiles() < kWorkgroupSlots) slots = std::max<size_t>(slots, static_cast<size_t>(L->n_query_tokens) * kMaxQuerySplit);
+  if (L->n_qtiles() < workgroup_slots(L)) slots = std::max<size_t>(slots, static_cast<size_t>(L->n_query_tokens) * kMaxQuerySplit);
   return slots * n_q_heads * (head_dim + kPartialPad) * sizeof(float);
 }
 
@@ -687,6 +733,7 @@ int decode_kv8_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_se
   const size_t need = dbsa_workspace_bytes(L, n_q_heads, head_dim);
   if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
     return DBSA_ERR_WORKSPACE;
+  if (rope_table && !decode_ids_in_table(L, stride_query, k_selfcache.stride_tok, rope_n_pos)) return DBSA_ERR_INVALID_ARG;
   AttnParams p{};
   fill_lists(p, L);
   p.q = view(q_step);
@@ -706,10 +753,10 @@ int decode_kv8_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_se
   p.rope_table = rope_table;
   p.rope_n_pos = rope_n_pos;
   p.partial = static_cast<float*>(workspace);
-  p.decode_reverse = L->last_walk_reversed.fetch_xor(1) ^ 1;
   p.decode_waves = pick_decode_waves(L, r);
   fill_decode_rows(p, L, r / p.decode_waves);
   if (order_behind_upload(L, static_cast<hipStream_t>(stream)) != hipSuccess) return DBSA_ERR_HIP;
+  p.decode_reverse = next_walk_direction(L);  // nothing rejects the call from here on
   return launch_decode_group_kv8(p, static_cast<hipStream_t>(stream)) == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;
 }
 }  // namespace
@@ -751,6 +798,8 @@ int dbsa_rope_apply(dbsa_tensor x, dbsa_tensor out, int32_t n_tokens, int32_t n_
   if (!x.ptr || !out.ptr || !table || n_tokens < 0 || n_heads < 1 || n_pos < 1 || x.stride_tok <= 0 ||
       x.stride_head <= 0 || out.stride_tok <= 0 || out.stride_head <= 0)
     return DBSA_ERR_INVALID_ARG;
+  // ids the host can see must lie inside the table (ids read from `positions` are clamped by the kernel)
+  if (!positions && (first_id < 0 || static_cast<int64_t>(first_id) + n_tokens > n_pos)) return DBSA_ERR_INVALID_ARG;
   return launch_rope_apply(view(x), view(out), n_tokens, n_heads, head_dim, dtype == DBSA_BF16, positions, first_id,
                            table, n_pos, static_cast<hipStream_t>(stream)) == hipSuccess
              ? DBSA_OK
@@ -810,25 +859,29 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
   p.scale_log2e = softmax_scale * 1.4426950408889634f;
   p.rope_table = rope_table;
   p.rope_n_pos = rope_n_pos;
-  // Every step reads the same selected keys, more of them than the last-level cache holds, so a
-  // step that walks them in the order of the step before finds none of them cached.  Successive
-  // calls on one layout therefore alternate the direction in which each run of keys is walked
-  // (the query prefill walks forward): what the previous call read last is read first.
-  p.decode_reverse = L->last_walk_reversed.fetch_xor(1) ^ 1;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = order_behind_upload(L, s);
-  if (e != hipSuccess) return DBSA_ERR_HIP;
+  // every reason to reject the call comes first
+  const int r = n_q_heads / n_kv_heads;
+  const int64_t max_stride = std::max(std::max(p.k_pool.stride_tok, p.v_pool.stride_tok),
+                                      std::max(p.k_self.stride_tok, p.v_self.stride_tok));
+  const bool group_major = dtype == DBSA_BF16 && head_dim == 128 && 32 % r == 0 && max_stride < (int64_t{1} << 24);
   if (dtype == DBSA_BF16) {
-    if (L->block_n != 64 || n_q_heads / n_kv_heads > 32) return DBSA_ERR_UNSUPPORTED;
+    if (L->block_n != 64 || r > 32) return DBSA_ERR_UNSUPPORTED;
     // need_bytes: what the caller has checked the step to write (the fixed-buffer entry point)
     const size_t need = need_bytes ? need_bytes : dbsa_workspace_bytes(L, n_q_heads, head_dim);
     if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16 != 0)
       return DBSA_ERR_WORKSPACE;
     p.partial = static_cast<float*>(workspace);
-    const int r = n_q_heads / n_kv_heads;
-    const int64_t max_stride = std::max(std::max(p.k_pool.stride_tok, p.v_pool.stride_tok),
-                                        std::max(p.k_self.stride_tok, p.v_self.stride_tok));
-    if (head_dim == 128 && 32 % r == 0 && max_stride < (int64_t{1} << 24)) {
+  }
+  if (rope_table) {
+    if (!group_major) return DBSA_ERR_UNSUPPORTED;  // only the group-major kernel re-positions
+    if (!decode_ids_in_table(L, stride_query, k_selfcache.stride_tok, rope_n_pos)) return DBSA_ERR_INVALID_ARG;
+  }
+  hipError_t e = order_behind_upload(L, s);
+  if (e != hipSuccess) return DBSA_ERR_HIP;
+  p.decode_reverse = next_walk_direction(L);
+  if (dtype == DBSA_BF16) {
+    if (group_major) {
       // every KV run is walked once for all the queries that selected it
       // Items that serve several batches of 32 / r queries: the batches of one item run as waves
       // of ONE workgroup that share its tiles in LDS, once a key is walked often enough for that
@@ -838,12 +891,10 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
       fill_decode_rows(p, L, r / p.decode_waves);
       e = launch_decode_group(p, s);
     } else {
-      if (rope_table) return DBSA_ERR_UNSUPPORTED;  // only the group-major kernel re-positions
       e = launch_decode_mfma(p, head_dim, s);
       if (e == hipSuccess) e = launch_decode_merge(p, head_dim, /*out_bf16=*/true, s);
     }
   } else {
-    if (rope_table) return DBSA_ERR_UNSUPPORTED;
     e = launch_decode_plain(p, head_dim, /*bf16_storage=*/false, s);
   }
   return e == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;

@@ -645,9 +645,9 @@ hipError_t launch_stage(const AttnParams& p, hipStream_t stream) {
 hipError_t launch_prefill_pipelined(const AttnParams& p, hipStream_t stream) {
   if (p.n_qtiles == 0) return hipSuccess;
   const int row_blocks = p.heads_per_block * (p.block_m / 32);
-  // with a persistent schedule: the kernel with 64 rows per wave, one wave per SIMD
-  static const bool force64 = getenv("DBSA_PREFILL64") != nullptr;  // (development switch: that kernel without a schedule)
-  if ((p.sched_rec || force64) && !p.rope_table && (row_blocks == 4 || row_blocks == 8)) {
+  // four or eight row blocks, inputs at their final positions: the kernel with 64 rows per wave, one
+  // wave per SIMD (persistent if the call carries a schedule, else one workgroup per Q tile and run)
+  if (!p.rope_table && (row_blocks == 4 || row_blocks == 8)) {
     hipError_t e = launch_prefill64(p, stream);
     const int n_split = p.q_split > 1 ? p.q_split : 1;
     if (e != hipSuccess || n_split == 1) return e;

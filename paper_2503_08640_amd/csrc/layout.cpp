@@ -236,8 +236,12 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
       max_tiles = std::max(max_tiles, t);
       tile_batches += t * ((static_cast<int64_t>(users[s].size()) + kItemQueries - 1) / kItemQueries);
     }
+    // single-wave workgroups the chip holds per KV head of an 8-KV-head model (six per compute
+    // unit), three quarters of them for pool runs: the rest is for the queries' own caches and for
+    // items that take a second batch of queries
+    const int64_t run_slots = std::max<int64_t>(1, static_cast<int64_t>(L->compute_units) * 6 / 8 * 3 / 4);
     int64_t chunk = sel->n_split > 0 ? (max_tiles + sel->n_split - 1) / sel->n_split
-                                     : std::min<int64_t>(32, (tile_batches + 143) / 144);
+                                     : std::min<int64_t>(32, (tile_batches + run_slots - 1) / run_slots);
     chunk = std::max<int64_t>(1, chunk);
     L->gm_chunk_tiles = static_cast<int32_t>(chunk);
     // displacement of segment s for user u, as in list_shift but without a tile offset
@@ -290,6 +294,7 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
   }
 
   for (size_t i = 3; i < L->gm_items.size(); i += 4) L->gm_max_queries = std::max(L->gm_max_queries, L->gm_items[i]);
+  for (const int32_t shift : L->gm_qshift) L->max_decode_shift = std::max<int64_t>(L->max_decode_shift, shift);
   {
     const size_t n_items = L->gm_items.size() / 4;
     L->gm_item_run.resize(n_items * 4);

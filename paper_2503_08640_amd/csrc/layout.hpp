@@ -84,6 +84,10 @@ struct dbsa_layout {
   int32_t gm_max_queries = 1;       // most queries any schedule item serves
   int64_t shortest_list = 0;        // fewest entries any Q tile lists
   int64_t max_rotation_id = -1;     // largest id a prefill row looks up: max(list_shift[e] + rows of the tile) - 1
+  int64_t max_decode_shift = 0;     // largest gm_qshift: a decode row of self_len n looks up id shift + n - 1
+  // compute units of the device the launches are sized for (set before the host lists are built;
+  // 256 when the layout is built without a device)
+  int32_t compute_units = 256;
 
   // Schedule of a persistent prefill-shaped launch for n_classes workers (dbsa_balance_schedule),
   // computed by the first call that needs one and kept: class c walks records

@@ -169,39 +169,3 @@ def test_appending_groups_reproduces_the_full_encoding(w):
     B.dbsa_preencode_attn(app, q, k, v, pc.scale, out=o)
     assert torch.equal(o.view(torch.int16), o_full.view(torch.int16))
     assert_close(to_f64(o[first_new:]), _oracle(pc, np.arange(first_new, p.n_tokens)), f"appended groups, w={w}")
-
-
-def test_append_cost_does_not_grow_with_the_pool():
-    """Encoding one added block costs the same whether the pool holds 12 or 47 blocks (Sec. 1),
-    while re-encoding the whole pool grows with it."""
-    pc = synth.paper_setting_pool()
-    p = pc.pool
-    q, k, v = to_dev(pc.q), to_dev(pc.k), to_dev(pc.v)
-    o = torch.empty_like(q)
-
-    def timed(lay, q_, k_, v_, o_):
-        for _ in range(2):
-            B.dbsa_preencode_attn(lay, q_, k_, v_, pc.scale, out=o_)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(5):
-            B.dbsa_preencode_attn(lay, q_, k_, v_, pc.scale, out=o_)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / 5
-
-    t_app, t_full = [], []
-    for n_groups in (12, 24, 47):
-        do = p.demo_offsets[: p.group_demo_offsets[n_groups] + 1]
-        gdo = p.group_demo_offsets[: n_groups + 1]
-        n = int(do[-1])
-        app = B.dbsa_layout_build_append(p.sink_len, do, gdo, 2, n_groups - 1, block_m=32, block_n=64)
-        full = B.dbsa_layout_build(p.sink_len, do, gdo, 2, block_m=32, block_n=64)
-        t_app.append(timed(app, q[:n], k[:n], v[:n], o[:n]))
-        t_full.append(timed(full, q[:n], k[:n], v[:n], o[:n]))
-    print(f"[append] ms to add one block to 11/23/46 blocks: {np.round(t_app, 3).tolist()}; "
-          f"full re-encode: {np.round(t_full, 3).tolist()}", flush=True)
-    assert max(t_app) <= 1.5 * min(t_app)
-    assert t_full[2] >= 2.5 * t_full[0]
-    assert max(t_app) <= 0.2 * t_full[2]
-

@@ -105,6 +105,18 @@ def test_repositioned_decode_with_many_queries_per_group(hq, hkv):
     _repositioned_case(pc, qc, 32, 10000.0, decode_steps=range(2), what=f"many queries Hq={hq} Hkv={hkv}")
 
 
+@pytest.mark.parametrize("hq,hkv,block_m,q_len", [(4, 4, 128, [1500, 1283]), (4, 2, 256, [1700, 1201]), (2, 2, 256, [1999])])
+def test_repositioned_split_prefill_with_large_q_tiles(hq, hkv, block_m, q_len):
+    """Few long queries under Q tiles of 128 / 256 rows: the lists are cut into runs (the workspace is given),
+    and the last block_m / 64 entries of every list hide keys from the Q tile's upper rows.  No run may start
+    among them behind the first: the kernel takes a row's first maximum from the first tile of its run."""
+    pc = synth.make_pool_case("ropebig", 4030 + block_m + hq, dtype="bf16", n_q_heads=hq, n_kv_heads=hkv, head_dim=128,
+                              sink_len=70, pool_tokens=6000, demo_len_range=(64, 300), n_groups=3)
+    sels = [[2, 0, 1], [1]][:len(q_len)]
+    qc = synth.make_query_case("ropebigq", 4031, pc, n_queries=len(q_len), q_len=q_len, selections=sels)
+    _repositioned_case(pc, qc, block_m, 500000.0, what=f"split, bm={block_m} T={q_len}")
+
+
 def test_repositioned_stage_matches_the_position_free_stage_when_ids_do_not_move():
     """All groups in pool order: new ids = encoding ids, so the re-positioned calls must agree
     with the position-free calls on explicitly rotated inputs (same kernels, other code path)."""

@@ -1,0 +1,107 @@
+"""Wall-clock checks, kept apart from the parity suite: a noisy box can fail these without saying
+anything about correctness.  Times are medians over single launches bracketed by device events.
+
+Query stage against the retrieval ratio (Sec. 1: cost proportional to the retrieved share; Sec. 4:
+latency): the cost of a call is modelled as t = alpha + beta * keys, keys = the mean number of pool
+keys one query attends.  alpha is what does not shrink with the selection: launch and merge passes,
+the queries' own tokens, a pipeline fill per Q tile, and - for the decode step, which fetches a group
+once for ALL the queries that selected it - the bytes of the union of the selections, which at 128
+queries is nearly the whole pool at every ratio.  The checks are on the fit (linear, increasing) and
+on the proportional part (t - alpha); alpha itself is bounded as a share of the full-cache time so
+that a growing fixed cost is noticed.
+
+Appending a block (Sec. 1: demonstrations are added without re-encoding the pool)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_08640_amd import binding as B
+from paper_2503_08640_amd import synth
+from gpu_util import to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def median_ms(fn, launches=30, warmup=3):
+    for _ in range(warmup):
+        fn()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return float(np.median([a.elapsed_time(b) for a, b in ev]))
+
+
+def linear_fit(keys, t):
+    beta, alpha = np.polyfit(keys, t, 1)
+    r2 = 1 - ((t - (alpha + beta * keys)) ** 2).sum() / ((t - t.mean()) ** 2).sum()
+    return float(alpha), float(beta), float(r2)
+
+
+# share of the full-cache (100 % retrieval) time that the fixed part alpha may take
+ALPHA_SHARE = {"prefill": 0.08, "decode": 0.30}
+
+
+def test_query_stage_time_is_affine_in_the_retrieved_keys():
+    cfg2 = synth.config2_pool()
+    p = cfg2.pool
+    kp, vp = to_dev(cfg2.k), to_dev(cfg2.v)
+    lens = np.diff(p.group_token_bounds())
+    keys, t_pre, t_dec = [], [], []
+    for ratio in synth.RETRIEVAL_RATIOS:
+        qc = synth.config4_query(cfg2, ratio)
+        lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, cu_qlens=qc.cu_qlens,
+                                  sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, n_split=0, block_m=32, block_n=64)
+        qs, ks, vs = to_dev(qc.q), to_dev(qc.k), to_dev(qc.v)
+        out = torch.empty_like(qs)
+        ws = torch.empty(max(16, lay.workspace_bytes(cfg2.n_q_heads, cfg2.head_dim)), dtype=torch.uint8, device="cuda")
+        t_pre.append(median_ms(lambda: B.dbsa_query_attn(lay, qs, ks, vs, kp, vp, cfg2.scale, out=out, workspace=ws)))
+        shp = qc.k_cache.shape
+        kc = to_dev(qc.k_cache.reshape(-1, shp[2], shp[3])).view(shp)
+        vc = to_dev(qc.v_cache.reshape(-1, shp[2], shp[3])).view(shp)
+        self_len = torch.from_numpy((np.diff(qc.cu_qlens) + 1).astype(np.int32)).cuda()
+        dq = to_dev(qc.dec_q[0])
+        od = torch.empty_like(dq)
+        t_dec.append(median_ms(lambda: B.dbsa_decode_attn(lay, dq, kc, vc, self_len, kp, vp, cfg2.scale, out=od, workspace=ws)))
+        keys.append(p.sink_len + np.mean([lens[qc.sel_idx[qc.sel_ptr[u]:qc.sel_ptr[u + 1]]].sum()
+                                          for u in range(qc.n_queries)]))
+    keys = np.array(keys)
+    for what, t in (("prefill", np.array(t_pre)), ("decode", np.array(t_dec))):
+        alpha, beta, r2 = linear_fit(keys, t)
+        prop = (t[0] - alpha) / (t[-1] - alpha)
+        print(f"[scaling] {what}: ms at 10/30/50/100 % = {np.round(t, 4).tolist()}  alpha={alpha:.4f} ms "
+              f"beta={beta * 1e3:.4f} us/key R^2={r2:.5f}  t10/t100={t[0] / t[-1]:.4f} keys10/keys100={keys[0] / keys[-1]:.4f} "
+              f"(t10-alpha)/(t100-alpha)={prop:.4f}", flush=True)
+        assert r2 >= 0.99, what
+        assert np.all(np.diff(t) > 0) and beta > 0, what
+        assert abs(prop / (keys[0] / keys[-1]) - 1.0) <= 0.25, what
+        assert alpha <= ALPHA_SHARE[what] * t[-1], what
+    # Sec. 1: more than 2x over attending the full cache at 30 % retrieval, prefill and decode together
+    stage = np.array(t_pre) + np.array(t_dec)
+    print(f"[scaling] stage: t30/t100 = {stage[1] / stage[-1]:.4f}", flush=True)
+    assert stage[-1] / stage[1] >= 2.0
+
+
+def test_append_cost_does_not_grow_with_the_pool():
+    """Encoding one added block costs the same whether the pool holds 12 or 47 blocks (Sec. 1),
+    while re-encoding the whole pool grows with it."""
+    pc = synth.paper_setting_pool()
+    p = pc.pool
+    q, k, v = to_dev(pc.q), to_dev(pc.k), to_dev(pc.v)
+    o = torch.empty_like(q)
+    t_app, t_full = [], []
+    for n_groups in (12, 24, 47):
+        do = p.demo_offsets[: p.group_demo_offsets[n_groups] + 1]
+        gdo = p.group_demo_offsets[: n_groups + 1]
+        n = int(do[-1])
+        app = B.dbsa_layout_build_append(p.sink_len, do, gdo, 2, n_groups - 1, block_m=32, block_n=64)
+        full = B.dbsa_layout_build(p.sink_len, do, gdo, 2, block_m=32, block_n=64)
+        t_app.append(median_ms(lambda: B.dbsa_preencode_attn(app, q[:n], k[:n], v[:n], pc.scale, out=o[:n]), 10))
+        t_full.append(median_ms(lambda: B.dbsa_preencode_attn(full, q[:n], k[:n], v[:n], pc.scale, out=o[:n]), 10))
+    print(f"[append] ms to add one block to 11/23/46 blocks: {np.round(t_app, 3).tolist()}; "
+          f"full re-encode: {np.round(t_full, 3).tolist()}", flush=True)
+    assert max(t_app) <= 1.5 * min(t_app)
+    assert t_full[2] >= 2.5 * t_full[0]
+    assert max(t_app) <= 0.2 * t_full[2]

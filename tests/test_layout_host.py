@@ -381,3 +381,76 @@ def test_rotary_calls_reject_bad_arguments_before_touching_the_device():
     assert L.dbsa_decode_attn_rope(lay.handle, t, t, t, C.c_void_p(16), 1024, t, t, t, None, 0, *tail) == \
         B.DBSA_ERR_INVALID_ARG
 
+
+
+def test_rotation_ids_known_to_the_host_must_lie_inside_the_table():
+    """With positions == NULL the ids are first_id .. first_id + n_tokens - 1: checked before any launch."""
+    import ctypes as C
+    L = B.lib()
+    t = B.Tensor(16, 256, 128)
+    tab = C.c_void_p(16)
+    assert L.dbsa_rope_apply(t, t, 4, 2, 128, B.DBSA_BF16, None, 5, tab, 8, None) == B.DBSA_ERR_INVALID_ARG    # ids 5..8, table of 8
+    assert L.dbsa_rope_apply(t, t, 4, 2, 128, B.DBSA_BF16, None, -1, tab, 8, None) == B.DBSA_ERR_INVALID_ARG
+    assert L.dbsa_rope_apply(t, t, 2 ** 31 - 1, 2, 128, B.DBSA_BF16, None, 2 ** 31 - 1, tab, 8, None) == \
+        B.DBSA_ERR_INVALID_ARG                                                                               # no 32-bit wrap
+
+
+def test_default_decode_chunk_follows_the_compute_unit_count():
+    """A layout built without a device is sized for 256 compute units: runs of pool tiles are cut so that
+    about 144 single-wave workgroups per KV head (six per compute unit over eight KV heads, three
+    quarters of them for pool runs) cover the step, and never longer than 32 tiles."""
+    pc = synth.make_pool_case("chunkpool", 11, dtype="bf16", n_q_heads=2, n_kv_heads=1, head_dim=16, sink_len=64,
+                              pool_tokens=60000, demo_len_range=(200, 600), n_groups=6).pool
+    run_slots = 256 * 6 // 8 * 3 // 4
+    assert run_slots == 144
+    seen = set()
+    for nq in (1, 8, 40, 100, 200):
+        cu = np.arange(nq + 1, dtype=np.int32)
+        sel_ptr = (np.arange(nq + 1) * pc.n_groups).astype(np.int32)
+        sel_idx = np.tile(np.arange(pc.n_groups, dtype=np.int32), nq)
+        lay = B.dbsa_layout_build(pc.sink_len, pc.demo_offsets, pc.group_demo_offsets, cu_qlens=cu, sel_ptr=sel_ptr,
+                                  sel_idx=sel_idx, n_split=0, block_m=64, block_n=64, host_only=True)
+        got = lay.export_decode_groups(pc.n_groups, nq)
+        tiles = np.diff(got["seg_ptr"])
+        batches = int(tiles.sum()) * ((nq + 31) // 32)       # every segment serves all nq queries
+        want = max(1, min(32, -(-batches // run_slots)))
+        assert got["chunk_tiles"] == want, (nq, got["chunk_tiles"], want)
+        seen.add(want)
+        # no run is longer than the chunk, and a segment's runs differ by at most one tile
+        assert got["items"][:, 1].max() <= want
+    assert len(seen) >= 3 and 32 in seen
+
+
+@pytest.mark.parametrize("n_classes", [1, 7, 64, 512])
+def test_persistent_schedule_deals_every_tile_once_and_balances(n_classes):
+    """Records repeat the layout's own tables; every Q tile is served by exactly one worker; no worker
+    carries more than the mean load plus one round's spread."""
+    pc = synth.make_pool_case("schedpool", 5, dtype="bf16", n_q_heads=2, n_kv_heads=1, head_dim=16, sink_len=100,
+                              pool_tokens=40000, demo_len_range=(100, 900), n_groups=9).pool
+    lay = B.dbsa_layout_build(pc.sink_len, pc.demo_offsets, pc.group_demo_offsets, block_m=64, block_n=64,
+                              host_only=True)
+    tab, ptr, _ = lay.export()
+    cptr, rec = lay.export_schedule(n_classes)
+    n = tab.shape[0]
+    assert cptr[0] == 0 and cptr[-1] == n and np.all(np.diff(cptr) >= 0)
+    entries = np.diff(ptr)
+    by_key = {(int(tab[t, 0]), int(tab[t, 1])): t for t in range(n)}
+    assert len(by_key) == n
+    served = np.zeros(n, np.int32)
+    load = np.zeros(n_classes)
+    for c in range(n_classes):
+        for q_start, q_len, first, count in rec[cptr[c]:cptr[c + 1]]:
+            t = by_key[(int(q_start), int(q_len))]
+            served[t] += 1
+            assert first == ptr[t] and count == entries[t]
+            load[c] += count + 3
+    assert np.all(served == 1)
+    # greedy dealing: the heaviest worker is at most one tile's cost above the lightest ... within
+    # a round; over the launch the spread stays below the cost of the largest tile
+    assert load.max() - load.min() <= entries.max() + 3
+    # a layout keeps one schedule
+    import ctypes as C
+    assert B.lib().dbsa_layout_export_schedule(lay.handle, n_classes + 1, None, None) == B.DBSA_ERR_INVALID_ARG
+    assert B.lib().dbsa_layout_export_schedule(lay.handle, n_classes, None, None) == B.DBSA_OK
+    assert B.lib().dbsa_layout_export_schedule(lay.handle, 0, None, None) == B.DBSA_ERR_INVALID_ARG
+    assert B.lib().dbsa_layout_export_schedule(None, 4, None, None) == B.DBSA_ERR_INVALID_ARG
