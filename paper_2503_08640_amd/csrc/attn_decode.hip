@@ -21,16 +21,11 @@
 #include <cstdint>
 
 #include "kernels.hpp"
+#include "mfma_common.hpp"
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-typedef short shortx4 __attribute__((ext_vector_type(4)));
+using namespace dbsa_mfma;
 
 constexpr int kD = 128;
 constexpr int kHalf = 32;                      // keys per half tile
@@ -41,88 +36,189 @@ constexpr int kLdsBytes = kSlots * kHalfBytes;  // 24 KiB per wave: six waves pe
 constexpr int kLoadsPerGroup = kHalfBytes / 1024;  // LDS-DMA instructions per K or V half tile
 constexpr float kRescaleSlack = 8.f;
 
-typedef __attribute__((address_space(3))) unsigned char lds_byte;
+// What one workgroup of the group-major step walks: a run of consecutive pool keys for up to 32
+// queries, or one query's own cache.
+struct DecodeItem {
+  int hk;         // KV head
+  int batch;      // query batch of the launch row
+  int item;       // pool items first, then one self item per query
+  bool self_item;
+  int n_q, first_key, n_keys, self_u;
+};
 
-__device__ inline bf16x4 lds_read_tr(const lds_byte* p) {
-  typedef __attribute__((address_space(3))) shortx4* tr_ptr;
-  const shortx4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(p));
-  return __builtin_bit_cast(bf16x4, t);
-}
-__device__ inline float half_swap_max(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ inline float half_swap_sum(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-// 16 bytes per lane from global memory straight into LDS (lane l lands at dst + 16*l),
-// asynchronous: completion is awaited with an explicit vmcnt wait.
-__device__ inline void dma16(const void* gbase_in, unsigned byte_off, lds_byte* dst) {
-  const uint64_t g = reinterpret_cast<uint64_t>(gbase_in);
-  // (readfirstlane returns a signed int: widen through unsigned, or the low word would be sign-extended)
-  const unsigned g_hi = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(g >> 32)));
-  const unsigned g_lo = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(g & 0xFFFFFFFFu)));
-  const void* gbase = reinterpret_cast<const void*>((static_cast<uint64_t>(g_hi) << 32) | static_cast<uint64_t>(g_lo));
-  const unsigned m0v = static_cast<unsigned>(
-      __builtin_amdgcn_readfirstlane(static_cast<int>(reinterpret_cast<uintptr_t>(dst) & 0xFFFFFFFFu)));
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(m0v), "v"(byte_off), "s"(gbase)
-               : "memory");
-}
-
-// Wait until at most N vector-memory operations of this wave are outstanding.  The memory
-// clobber keeps the LDS reads of the awaited stage below the wait.
-template <int N>
-__device__ inline void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
-// The 8 B-operand fragments of one score column: the query row (qp points at this lane's first
-// channel, 8 * half), pre-multiplied by scale * log2 e.  ROPE: the row is stored un-rotated and is
-// rotated here with the table row `rot` (16 floats = cos, sin of 8 channel pairs per (chunk, half)).
-template <bool ROPE>
-__device__ inline void load_query_fragments(const __bf16* qp, const float* rot, float c2, bf16x8 (&qf)[kD / 16]) {
-  if (ROPE) {
-    // channel d < 64 of chunk c pairs with channel d + 64 of chunk c + 4, both held by this lane
-#pragma unroll
-    for (int c = 0; c < kD / 32; ++c) {
-      const bf16x8 lo = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
-      const bf16x8 hi = *reinterpret_cast<const bf16x8*>(qp + 16 * (c + kD / 32));
-      floatx4 cs[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) cs[j] = *reinterpret_cast<const floatx4*>(rot + 32 * c + 4 * j);
-      union {
-        bf16x8 v;
-        bf16x2 p2[4];
-      } a, b;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float x0 = static_cast<float>(lo[2 * e]), y0 = static_cast<float>(hi[2 * e]);
-        const float x1 = static_cast<float>(lo[2 * e + 1]), y1 = static_cast<float>(hi[2 * e + 1]);
-        const float c0 = cs[e][0] * c2, s0 = cs[e][1] * c2, c1 = cs[e][2] * c2, s1 = cs[e][3] * c2;
-        a.p2[e] = __builtin_convertvector(floatx2{x0 * c0 - y0 * s0, x1 * c1 - y1 * s1}, bf16x2);
-        b.p2[e] = __builtin_convertvector(floatx2{y0 * c0 + x0 * s0, y1 * c1 + x1 * s1}, bf16x2);
-      }
-      qf[c] = a.v;
-      qf[c + kD / 32] = b.v;
-    }
+// Workgroup id -> (KV head, launch row, item in the row's block of 8), the item fastest.  A row
+// is (block, query batch); the rows of one block follow each other, so the workgroups that walk
+// one item's keys for different query batches have ids 8 apart: they start together AND on the
+// same XCD (ids are dealt to the 8 XCDs in turn), and all but the first find the keys in that
+// XCD's L2.  Rows exist only for batches some item of the block has.  False: the id names no item.
+// Everything the first loads need (the run, the query references) is one load away from the item
+// index: all workgroups of a step start together, and every further dependent load at their start
+// is a microsecond or two in which no tile data moves.  (The schedule lists are read-only while a
+// kernel runs: scalar loads through the constant path.)
+__device__ DBSA_INLINE bool locate_decode_item(const AttnParams& p, DecodeItem& it) {
+  const int in_block = blockIdx.x % 8;
+  const int row_id = (blockIdx.x / 8) % p.launch_rows;
+  it.hk = (blockIdx.x / 8) / p.launch_rows;
+  const int row = ((const_words)(reinterpret_cast<uintptr_t>(p.gm_rows)))[p.row_offset + row_id];
+  it.batch = row & 0xFF;
+  const int block = row >> 8;
+  it.self_item = block >= p.n_pool_blocks;
+  it.item = it.self_item ? p.n_gm_items + 8 * (block - p.n_pool_blocks) + in_block : 8 * block + in_block;
+  if (it.item >= (it.self_item ? p.n_gm_items + p.n_queries : p.n_gm_items)) return false;
+  const const_words runs = (const_words)(reinterpret_cast<uintptr_t>(p.gm_item_run));
+  it.n_q = 1, it.first_key = 0, it.n_keys = 0, it.self_u = 0;
+  if (!it.self_item) {
+    it.first_key = runs[4 * it.item + 0];
+    it.n_keys = runs[4 * it.item + 1];
+    it.n_q = runs[4 * it.item + 2];
   } else {
+    it.self_u = it.item - p.n_gm_items;
+    it.n_keys = __builtin_amdgcn_readfirstlane(p.self_len[it.self_u]);
+  }
+  return true;
+}
+
+// A lane's score column: lanes l and l + 32 share column l % 32 = (query l32 / r of the wave's
+// batch, head l32 % r of the KV head).
+struct DecodeColumn {
+  int slot, head;
+  bool valid;        // the batch has a query for this column (the others compute on a repeated reference)
+  const __bf16* qp;  // the query row, at this lane's first channel
+  const float* rot;  // ROPE: table row of the column, 16 floats (cos, sin of 8 channel pairs) per (chunk c < 4, half)
+};
+
+// pass: the wave's query batch (of 32 / r queries) inside the item; active: the wave has a batch.
+// ROPE: the row is rotated at the id that stands for the new in-order position of the item's keys
+// (Sec. 2.2): shift of the reference + the query's own length - 1.
+// (The addresses are formed here, before the tile loads go out: they wait for the query reference
+// just loaded, and that wait must not include the tile loads.)
+template <bool ROPE>
+__device__ DBSA_INLINE DecodeColumn decode_column(const AttnParams& p, const DecodeItem& it, int pass, bool active, int r,
+                                                  int l32, int half) {
+  DecodeColumn c;
+  const int q_local = pass * (32 / r) + l32 / r;  // index into the item's query list (< 32 also without a batch)
+  c.valid = active && q_local < it.n_q;
+  int u = it.self_u, rot_id = 0;
+  if (it.self_item) {
+    c.slot = static_cast<int>(p.gm_slot_ptr[it.self_u + 1]) - 1;
+  } else {
+    // (query, slot, shift, 0); references past the item's last one repeat it
+    typedef int intx4 __attribute__((ext_vector_type(4)));
+    const intx4 ref = *reinterpret_cast<const intx4*>(p.gm_ref_pad + (static_cast<int64_t>(it.item) * 32 + q_local) * 4);
+    u = ref[0];
+    c.slot = ref[1];
+    if (ROPE) rot_id = ref[2];
+  }
+  c.head = it.hk * r + l32 % r;
+  c.rot = nullptr;
+  if (ROPE) {
+    rot_id = min(max(rot_id + p.self_len[u] - 1, 0), p.rope_n_pos - 1);
+    c.rot = p.rope_table + static_cast<int64_t>(rot_id) * kD + 16 * half;
+    asm volatile("" : "+v"(c.rot));
+  }
+  c.qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
+         static_cast<int64_t>(c.head) * p.q.stride_head + 8 * half;
+  asm volatile("" : "+v"(c.qp));
+  return c;
+}
+
+// The pieces of one half tile (32 keys) against the 32 columns of a wave.  The kernels differ in
+// where K and V come from and in what they issue between the pieces; the arithmetic is shared.
+union ProbFrag {
+  bf16x8 v[2];
+  bf16x2 p2[8];
+};
+
+// scores of a bf16 K half tile in LDS (swizzled as the loads of decode_group_kernel leave it):
+// two accumulator chains of four MFMAs instead of one of eight, half the latency
+__device__ DBSA_INLINE floatx16 half_tile_scores(const lds_byte* ks, int k_base, const bf16x8 (&qf)[kD / 16]) {
+  floatx16 s, s2;
 #pragma unroll
-    for (int c = 0; c < kD / 16; ++c) {
-      const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
-      union {
-        bf16x8 v;
-        bf16x2 p2[4];
-      } sc;
+  for (int i = 0; i < 16; ++i) s[i] = 0.f, s2[i] = 0.f;
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        sc.p2[e] = __builtin_convertvector(
-            floatx2{static_cast<float>(raw[2 * e]) * c2, static_cast<float>(raw[2 * e + 1]) * c2}, bf16x2);
-      qf[c] = sc.v;
+  for (int c = 0; c < kD / 16; c += 2) {
+    const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * c)));
+    const bf16x8 a2 = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * (c + 1))));
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[c], s, 0, 0, 0);
+    s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, qf[c + 1], s2, 0, 0, 0);
+  }
+  s += s2;
+  return s;
+}
+
+// masks the keys past `len`, moves the lazily rescaled running state (o, m_run, l_run) and leaves
+// the probabilities as the B operand of the second product
+__device__ DBSA_INLINE void half_tile_softmax(floatx16& s, int len, int half, floatx16 (&o)[kD / 32], float& m_run,
+                                              float& l_run, ProbFrag& pf) {
+  if (len < kHalf) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int key_local = 8 * (i / 4) + 4 * half + (i % 4);
+      s[i] = key_local < len ? s[i] : -INFINITY;
     }
+  }
+  float mx = s[0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+  mx = half_swap_max(mx);
+  if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int ob = 0; ob < kD / 32; ++ob) o[ob] *= alpha;
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float p0 = __builtin_amdgcn_exp2f(s[2 * i] - m_run);
+    const float p1 = __builtin_amdgcn_exp2f(s[2 * i + 1] - m_run);
+    pf.p2[i] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);
+    l_run += p0 + p1;
+  }
+}
+
+// o += V^T P^T for a bf16 V half tile in LDS (transposed fragments through the LDS transpose read)
+__device__ DBSA_INLINE void half_tile_weigh(const lds_byte* vs, int v_base, const ProbFrag& pf, floatx16 (&o)[kD / 32]) {
+#pragma unroll
+  for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+    for (int ob = 0; ob < kD / 32; ++ob) {
+      const lds_byte* vp = vs + (v_base ^ (64 * ob)) + 16 * ch * kRowBytes;
+      const bf16x4 lo = lds_read_tr(vp);
+      const bf16x4 hi = lds_read_tr(vp + 8 * kRowBytes);
+      const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf.v[ch], o[ob], 0, 0, 0);
+    }
+}
+
+// One whole half tile: ks / vs are the K and V half tiles in LDS, len the valid keys, k_base /
+// v_base this lane's fragment offsets; the running state is updated in place.
+__device__ DBSA_INLINE void half_tile_attend(const lds_byte* ks, const lds_byte* vs, int len, int k_base, int v_base, int half,
+                                             const bf16x8 (&qf)[kD / 16], floatx16 (&o)[kD / 32], float& m_run,
+                                             float& l_run) {
+  floatx16 s = half_tile_scores(ks, k_base, qf);
+  ProbFrag pf;
+  half_tile_softmax(s, len, half, o, m_run, l_run, pf);
+  half_tile_weigh(vs, v_base, pf, o);
+}
+
+// The partial softmax state of a valid column: accumulators (times out_scale), running maximum, row sum.
+__device__ DBSA_INLINE void store_partial_state(const AttnParams& p, const DecodeColumn& c, int half, const floatx16 (&o)[kD / 32],
+                                                float m_run, float l_run, float out_scale) {
+  const float l_tot = half_swap_sum(l_run);
+  if (!c.valid) return;
+  float* part = p.partial + (static_cast<int64_t>(c.slot) * p.n_q_heads + c.head) * (kD + kPartialPad);
+#pragma unroll
+  for (int ob = 0; ob < kD / 32; ++ob)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      *reinterpret_cast<floatx4*>(part + 32 * ob + 8 * g + 4 * half) =
+          floatx4{o[ob][4 * g] * out_scale, o[ob][4 * g + 1] * out_scale, o[ob][4 * g + 2] * out_scale,
+                  o[ob][4 * g + 3] * out_scale};
+  if (half == 0) {
+    part[kD] = m_run;
+    part[kD + 1] = l_tot;
   }
 }
 
@@ -135,37 +231,13 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   const int lane = threadIdx.x, l32 = lane % 32, half = lane / 32;
   const int r = p.n_q_heads / p.n_kv_heads;
   const int qpw = 32 / r;  // queries per wave
-  // Workgroup id -> (KV head, launch row, item in the row's block of 8), the item fastest.  A row
-  // is (block, query batch); the rows of one block follow each other, so the workgroups that walk
-  // one item's keys for different query batches have ids 8 apart: they start together AND on the
-  // same XCD (ids are dealt to the 8 XCDs in turn), and all but the first find the keys in that
-  // XCD's L2.  Rows exist only for batches some item of the block has.
-  const int in_block = blockIdx.x % 8;
-  const int row_id = (blockIdx.x / 8) % p.launch_rows, hk = (blockIdx.x / 8) / p.launch_rows;
-  typedef const __attribute__((address_space(4))) int32_t* const_words;
-  const int row = ((const_words)(reinterpret_cast<uintptr_t>(p.gm_rows)))[p.row_offset + row_id];
-  const int pass = row & 0xFF, block = row >> 8;
-
   // ---- the item: a run of pool tiles for several queries, or one query's own cache ----
-  const bool self_item = block >= p.n_pool_blocks;
-  const int item = self_item ? p.n_gm_items + 8 * (block - p.n_pool_blocks) + in_block : 8 * block + in_block;
-  if (item >= (self_item ? p.n_gm_items + p.n_queries : p.n_gm_items)) return;
-  // (the schedule lists are read-only while a kernel runs: scalar loads through the constant path)
-  const const_words runs = (const_words)(reinterpret_cast<uintptr_t>(p.gm_item_run));
-  // the run is a stretch of consecutive key rows: first_key .. first_key + n_keys.  Everything
-  // the first loads need (the run, the query references) is one load away from the item index:
-  // all workgroups of a step start together, and every further dependent load at their start is
-  // a microsecond or two in which no tile data moves.
-  int n_q = 1, n_half = 0, first_key = 0, n_keys = 0, self_u = 0;
-  if (!self_item) {
-    first_key = runs[4 * item + 0];
-    n_keys = runs[4 * item + 1];
-    n_q = runs[4 * item + 2];
-  } else {
-    self_u = item - p.n_gm_items;
-    n_keys = __builtin_amdgcn_readfirstlane(p.self_len[self_u]);
-  }
-  n_half = (n_keys + kHalf - 1) / kHalf;
+  DecodeItem it;
+  if (!locate_decode_item(p, it)) return;
+  const int hk = it.hk, pass = it.batch, n_q = it.n_q, first_key = it.first_key, n_keys = it.n_keys, self_u = it.self_u;
+  const bool self_item = it.self_item;
+  // the run is a stretch of consecutive key rows: first_key .. first_key + n_keys
+  const int n_half = (n_keys + kHalf - 1) / kHalf;
   const __bf16* kbase = self_item ? static_cast<const __bf16*>(p.k_self.ptr) + self_u * p.stride_query +
                                         hk * p.k_self.stride_head
                                   : static_cast<const __bf16*>(p.k_pool.ptr) + hk * p.k_pool.stride_head;
@@ -252,32 +324,7 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
   if (pass >= n_pass) return;
   {
     // ---- this lane's column: query and head ----
-    const int q_local = pass * qpw + l32 / r;  // index into the item's query list (< 32)
-    const bool col_valid = q_local < n_q;
-    int u = self_u, slot, rot_id = 0;
-    if (self_item) {
-      slot = static_cast<int>(p.gm_slot_ptr[self_u + 1]) - 1;
-    } else {
-      // (query, slot, shift, 0); references past the item's last one repeat it
-      typedef int intx4 __attribute__((ext_vector_type(4)));
-      const intx4 ref = *reinterpret_cast<const intx4*>(p.gm_ref_pad + (static_cast<int64_t>(item) * 32 + q_local) * 4);
-      u = ref[0];
-      slot = ref[1];
-      if (ROPE) rot_id = ref[2];
-    }
-    const int head = hk * r + l32 % r;
-    // table row of this column: 16 floats (cos, sin of 8 channel pairs) per (chunk c < 4, half)
-    const float* rot = nullptr;
-    if (ROPE) {
-      rot_id = min(max(rot_id + p.self_len[u] - 1, 0), p.rope_n_pos - 1);
-      rot = p.rope_table + static_cast<int64_t>(rot_id) * kD + 16 * half;
-      asm volatile("" : "+v"(rot));
-    }
-    // (the row address is formed here, before the tile loads go out: it waits for the query
-    // reference just loaded, and that wait must not include the tile loads)
-    const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
-                       static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
-    asm volatile("" : "+v"(qp));
+    const DecodeColumn col = decode_column<ROPE>(p, it, pass, true, r, l32, half);
 
     // ---- wave-private ring of three 8-KiB slots: load groups go out in the order K(0) V(0) K(1)
     // V(1) K(2) ..., group g into slot g % 3, and group g+3 as soon as the product that reads group
@@ -287,7 +334,7 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
     issue_v(0);
     if (1 < n_half) issue_k(1);
     bf16x8 qf[kD / 16];
-    load_query_fragments<ROPE>(qp, rot, c2, qf);
+    load_query_fragments<ROPE>(col.qp, col.rot, c2, qf);
     floatx16 o[kD / 32];
 #pragma unroll
     for (int ob = 0; ob < kD / 32; ++ob)
@@ -303,143 +350,20 @@ __global__ __launch_bounds__(64, 2) void decode_group_kernel(AttnParams p) {
       const lds_byte* ks = lds + ((2 * hh) % kSlots) * kHalfBytes;
       const lds_byte* vs = lds + ((2 * hh + 1) % kSlots) * kHalfBytes;
 
-      // two accumulator chains of four MFMAs instead of one of eight: half the latency
-      floatx16 s, s2;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[i] = 0.f, s2[i] = 0.f;
-#pragma unroll
-      for (int c = 0; c < kD / 16; c += 2) {
-        const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * c)));
-        const bf16x8 a2 =
-            *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * (c + 1))));
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[c], s, 0, 0, 0);
-        s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, qf[c + 1], s2, 0, 0, 0);
-      }
-      s += s2;
+      floatx16 s = half_tile_scores(ks, k_base, qf);
       // the K slot is free (its LDS reads were consumed by the MFMAs above): it takes the group
       // three places on, V(hh+1)
       if (hh + 1 < n_half) issue_v(hh + 1);
-      if (len < kHalf) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key_local = 8 * (i / 4) + 4 * half + (i % 4);
-          s[i] = key_local < len ? s[i] : -INFINITY;
-        }
-      }
-      float mx = s[0];
-#pragma unroll
-      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
-      mx = half_swap_max(mx);
-      if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        l_run *= alpha;
-#pragma unroll
-        for (int ob = 0; ob < kD / 32; ++ob) o[ob] *= alpha;
-      }
-      union {
-        bf16x8 v[2];
-        bf16x2 p2[8];
-      } pf;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float p0 = __builtin_amdgcn_exp2f(s[2 * i] - m_run);
-        const float p1 = __builtin_amdgcn_exp2f(s[2 * i + 1] - m_run);
-        pf.p2[i] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);
-        l_run += p0 + p1;
-      }
+      ProbFrag pf;
+      half_tile_softmax(s, len, half, o, m_run, l_run, pf);
       // V(hh) has landed once only K(hh+1) and V(hh+1) are outstanding
       wait_groups(hh + 1 < n_half ? 2 : 0);
-#pragma unroll
-      for (int ch = 0; ch < 2; ++ch)
-#pragma unroll
-        for (int ob = 0; ob < kD / 32; ++ob) {
-          const lds_byte* vp = vs + (v_base ^ (64 * ob)) + 16 * ch * kRowBytes;
-          const bf16x4 lo = lds_read_tr(vp);
-          const bf16x4 hi = lds_read_tr(vp + 8 * kRowBytes);
-          const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf.v[ch], o[ob], 0, 0, 0);
-        }
+      half_tile_weigh(vs, v_base, pf, o);
       if (hh + 2 < n_half) issue_k(hh + 2);  // into the slot V(hh) just left
     }
 
-    // ---- partial state of every valid column ----
-    const float l_tot = half_swap_sum(l_run);
-    if (col_valid) {
-      float* part = p.partial + (static_cast<int64_t>(slot) * p.n_q_heads + head) * (kD + kPartialPad);
-#pragma unroll
-      for (int ob = 0; ob < kD / 32; ++ob)
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-          *reinterpret_cast<floatx4*>(part + 32 * ob + 8 * g + 4 * half) =
-              floatx4{o[ob][4 * g], o[ob][4 * g + 1], o[ob][4 * g + 2], o[ob][4 * g + 3]};
-      if (half == 0) {
-        part[kD] = m_run;
-        part[kD + 1] = l_tot;
-      }
-    }
+    store_partial_state(p, col, half, o, m_run, l_run, 1.f);
   }
-}
-
-// One half tile (32 keys, bf16, swizzled as the loads of decode_group_kernel leave it) against
-// the 32 columns of a wave: scores, lazy-rescaled online softmax, product with the values.
-// ks / vs: the K and V half tiles in LDS; len: valid keys; k_base / v_base: this lane's fragment
-// offsets; the running state (o, m_run, l_run) is updated in place.
-__device__ inline void half_tile_attend(const lds_byte* ks, const lds_byte* vs, int len, int k_base, int v_base, int half,
-                                        const bf16x8 (&qf)[kD / 16], floatx16 (&o)[kD / 32], float& m_run,
-                                        float& l_run) {
-  floatx16 s, s2;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) s[i] = 0.f, s2[i] = 0.f;
-#pragma unroll
-  for (int c = 0; c < kD / 16; c += 2) {
-    const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * c)));
-    const bf16x8 a2 = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(ks + (k_base ^ (32 * (c + 1))));
-    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[c], s, 0, 0, 0);
-    s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, qf[c + 1], s2, 0, 0, 0);
-  }
-  s += s2;
-  if (len < kHalf) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int key_local = 8 * (i / 4) + 4 * half + (i % 4);
-      s[i] = key_local < len ? s[i] : -INFINITY;
-    }
-  }
-  float mx = s[0];
-#pragma unroll
-  for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
-  mx = half_swap_max(mx);
-  if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    l_run *= alpha;
-#pragma unroll
-    for (int ob = 0; ob < kD / 32; ++ob) o[ob] *= alpha;
-  }
-  union {
-    bf16x8 v[2];
-    bf16x2 p2[8];
-  } pf;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const float p0 = __builtin_amdgcn_exp2f(s[2 * i] - m_run);
-    const float p1 = __builtin_amdgcn_exp2f(s[2 * i + 1] - m_run);
-    pf.p2[i] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);
-    l_run += p0 + p1;
-  }
-#pragma unroll
-  for (int ch = 0; ch < 2; ++ch)
-#pragma unroll
-    for (int ob = 0; ob < kD / 32; ++ob) {
-      const lds_byte* vp = vs + (v_base ^ (64 * ob)) + 16 * ch * kRowBytes;
-      const bf16x4 lo = lds_read_tr(vp);
-      const bf16x4 hi = lds_read_tr(vp + 8 * kRowBytes);
-      const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf.v[ch], o[ob], 0, 0, 0);
-    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -464,26 +388,11 @@ __global__ __launch_bounds__(64 * W) void decode_group_shared_kernel(AttnParams 
   const int lane = threadIdx.x % 64, l32 = lane % 32, half = lane / 32;
   const int r = p.n_q_heads / p.n_kv_heads;
   const int qpw = 32 / r;  // queries per wave
-  // workgroup id -> (KV head, launch row, item of the row's block of 8) as in decode_group_kernel;
   // a row's batch counts batches of W * qpw queries here
-  const int in_block = blockIdx.x % 8;
-  const int row_id = (blockIdx.x / 8) % p.launch_rows, hk = (blockIdx.x / 8) / p.launch_rows;
-  typedef const __attribute__((address_space(4))) int32_t* const_words;
-  const int row = ((const_words)(reinterpret_cast<uintptr_t>(p.gm_rows)))[p.row_offset + row_id];
-  const int wg_batch = row & 0xFF, block = row >> 8;
-  const bool self_item = block >= p.n_pool_blocks;
-  const int item = self_item ? p.n_gm_items + 8 * (block - p.n_pool_blocks) + in_block : 8 * block + in_block;
-  if (item >= (self_item ? p.n_gm_items + p.n_queries : p.n_gm_items)) return;
-  const const_words runs = (const_words)(reinterpret_cast<uintptr_t>(p.gm_item_run));
-  int n_q = 1, first_key = 0, n_keys = 0, self_u = 0;
-  if (!self_item) {
-    first_key = runs[4 * item + 0];
-    n_keys = runs[4 * item + 1];
-    n_q = runs[4 * item + 2];
-  } else {
-    self_u = item - p.n_gm_items;
-    n_keys = __builtin_amdgcn_readfirstlane(p.self_len[self_u]);
-  }
+  DecodeItem it;
+  if (!locate_decode_item(p, it)) return;
+  const int hk = it.hk, wg_batch = it.batch, n_q = it.n_q, first_key = it.first_key, n_keys = it.n_keys, self_u = it.self_u;
+  const bool self_item = it.self_item;
   const int n_half = (n_keys + kHalf - 1) / kHalf;
   const int n_pass = (n_q + qpw - 1) / qpw;
   // (everything up to here is the same for all waves: the workgroup leaves as one)
@@ -558,33 +467,12 @@ __global__ __launch_bounds__(64 * W) void decode_group_shared_kernel(AttnParams 
   const float c2 = p.scale_log2e;
 
   // ---- this lane's column: query and head ----
-  const int q_local = pass * qpw + l32 / r;  // index into the item's query list (< 32 also without a batch)
-  const bool col_valid = active && q_local < n_q;
-  int u = self_u, slot, rot_id = 0;
-  if (self_item) {
-    slot = static_cast<int>(p.gm_slot_ptr[self_u + 1]) - 1;
-  } else {
-    typedef int intx4 __attribute__((ext_vector_type(4)));
-    const intx4 ref = *reinterpret_cast<const intx4*>(p.gm_ref_pad + (static_cast<int64_t>(item) * 32 + q_local) * 4);
-    u = ref[0];
-    slot = ref[1];
-    if (ROPE) rot_id = ref[2];
-  }
-  const int head = hk * r + l32 % r;
-  const float* rot = nullptr;
-  if (ROPE) {
-    rot_id = min(max(rot_id + p.self_len[u] - 1, 0), p.rope_n_pos - 1);
-    rot = p.rope_table + static_cast<int64_t>(rot_id) * kD + 16 * half;
-    asm volatile("" : "+v"(rot));
-  }
-  const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
-                     static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
-  asm volatile("" : "+v"(qp));
+  const DecodeColumn col = decode_column<ROPE>(p, it, pass, active, r, l32, half);
 
   issue_pair(0);
   if (1 < n_half) issue_pair(1);
   bf16x8 qf[kD / 16];
-  load_query_fragments<ROPE>(qp, rot, c2, qf);
+  load_query_fragments<ROPE>(col.qp, col.rot, c2, qf);
   floatx16 o[kD / 32];
 #pragma unroll
   for (int ob = 0; ob < kD / 32; ++ob)
@@ -609,21 +497,7 @@ __global__ __launch_bounds__(64 * W) void decode_group_shared_kernel(AttnParams 
     half_tile_attend(ks, vs, len, k_base, v_base, half, qf, o, m_run, l_run);
   }
 
-  // ---- partial state of every valid column ----
-  const float l_tot = half_swap_sum(l_run);
-  if (col_valid) {
-    float* part = p.partial + (static_cast<int64_t>(slot) * p.n_q_heads + head) * (kD + kPartialPad);
-#pragma unroll
-    for (int ob = 0; ob < kD / 32; ++ob)
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-        *reinterpret_cast<floatx4*>(part + 32 * ob + 8 * g + 4 * half) =
-            floatx4{o[ob][4 * g], o[ob][4 * g + 1], o[ob][4 * g + 2], o[ob][4 * g + 3]};
-    if (half == 0) {
-      part[kD] = m_run;
-      part[kD + 1] = l_tot;
-    }
-  }
+  store_partial_state(p, col, half, o, m_run, l_run, 1.f);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -659,16 +533,10 @@ __global__ __launch_bounds__(64, 2) void decode_group_kv8_kernel(AttnParams p) {
   const int lane = threadIdx.x, l32 = lane % 32, half = lane / 32;
   const int r = p.n_q_heads / p.n_kv_heads;
   const int qpw = 32 / r;
-  // same id mapping as decode_group_kernel; this launch covers the rows of pool items only
-  const int in_block = blockIdx.x % 8;
-  const int row_id = (blockIdx.x / 8) % p.launch_rows, hk = (blockIdx.x / 8) / p.launch_rows;
-  typedef const __attribute__((address_space(4))) int32_t* const_words;
-  const int row = ((const_words)(reinterpret_cast<uintptr_t>(p.gm_rows)))[p.row_offset + row_id];
-  const int pass = row & 0xFF;
-  const int item = 8 * (row >> 8) + in_block;
-  if (item >= p.n_gm_items) return;
-  const const_words runs = (const_words)(reinterpret_cast<uintptr_t>(p.gm_item_run));
-  const int first_key = runs[4 * item + 0], n_keys = runs[4 * item + 1], n_q = runs[4 * item + 2];
+  // this launch covers the rows of pool items only
+  DecodeItem it;
+  if (!locate_decode_item(p, it) || it.self_item) return;
+  const int hk = it.hk, pass = it.batch, n_q = it.n_q, first_key = it.first_key, n_keys = it.n_keys;
   const int n_half = (n_keys + kHalf - 1) / kHalf;
   if (pass >= (n_q + qpw - 1) / qpw) return;
 
@@ -719,22 +587,8 @@ __global__ __launch_bounds__(64, 2) void decode_group_kv8_kernel(AttnParams p) {
   const int v_base = (4 * half + (lane % 16) / 4) * kRowBytes +
                      (((2 * (l32 / 16) + (lane % 4) / 2) ^ (4 * ((lane % 16) / 4))) * 16) + (lane % 2) * 8;
 
-  // ---- this lane's column ----
-  const int q_local = pass * qpw + l32 / r;
-  const bool col_valid = q_local < n_q;
-  typedef int intx4 __attribute__((ext_vector_type(4)));
-  const intx4 ref = *reinterpret_cast<const intx4*>(p.gm_ref_pad + (static_cast<int64_t>(item) * 32 + q_local) * 4);
-  const int u = ref[0], slot = ref[1];
-  const int head = hk * r + l32 % r;
-  const float* rot = nullptr;
-  if (ROPE) {  // as in decode_group_kernel: the stored keys keep their encoding-time rotation
-    const int rot_id = min(max(ref[2] + p.self_len[u] - 1, 0), p.rope_n_pos - 1);
-    rot = p.rope_table + static_cast<int64_t>(rot_id) * kD + 16 * half;
-    asm volatile("" : "+v"(rot));
-  }
-  const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
-                     static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
-  asm volatile("" : "+v"(qp));
+  // ---- this lane's column (ROPE as in decode_group_kernel: the stored keys keep their encoding-time rotation) ----
+  const DecodeColumn col = decode_column<ROPE>(p, it, pass, true, r, l32, half);
   issue_k(0);
   issue_v(0);
   if (1 < n_half) {
@@ -744,7 +598,7 @@ __global__ __launch_bounds__(64, 2) void decode_group_kv8_kernel(AttnParams p) {
   const float c2 = p.scale_log2e * p.k_scale8[hk];
   const float v_scale = p.v_scale8[hk];
   bf16x8 qf[kD / 16];
-  load_query_fragments<ROPE>(qp, rot, c2, qf);
+  load_query_fragments<ROPE>(col.qp, col.rot, c2, qf);
   floatx16 o[kD / 32];
 #pragma unroll
   for (int ob = 0; ob < kD / 32; ++ob)
@@ -777,36 +631,8 @@ __global__ __launch_bounds__(64, 2) void decode_group_kv8_kernel(AttnParams p) {
     // the K slot is free (its bytes are in registers): it takes the K bytes two half tiles on
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     if (hh + 2 < n_half) issue_k(hh + 2);
-    if (len < kHalf) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key_local = 8 * (i / 4) + 4 * half + (i % 4);
-        s[i] = key_local < len ? s[i] : -INFINITY;
-      }
-    }
-    float mx = s[0];
-#pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
-    mx = half_swap_max(mx);
-    if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int ob = 0; ob < kD / 32; ++ob) o[ob] *= alpha;
-    }
-    union {
-      bf16x8 v[2];
-      bf16x2 p2[8];
-    } pf;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float p0 = __builtin_amdgcn_exp2f(s[2 * i] - m_run);
-      const float p1 = __builtin_amdgcn_exp2f(s[2 * i + 1] - m_run);
-      pf.p2[i] = __builtin_convertvector(floatx2{p0, p1}, bf16x2);
-      l_run += p0 + p1;
-    }
+    ProbFrag pf;
+    half_tile_softmax(s, len, half, o, m_run, l_run, pf);
     // V(hh) has landed once only K(hh+1), V(hh+1) and K(hh+2) are outstanding
     wait_groups((more ? 2 : 0) + (hh + 2 < n_half ? 1 : 0));
     // staged V bytes -> the swizzled bf16 working tile
@@ -822,35 +648,12 @@ __global__ __launch_bounds__(64, 2) void decode_group_kv8_kernel(AttnParams p) {
     // the V slot is free: it takes the V bytes two half tiles on
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     if (hh + 2 < n_half) issue_v(hh + 2);
-#pragma unroll
-    for (int ch = 0; ch < 2; ++ch)
-#pragma unroll
-      for (int ob = 0; ob < kD / 32; ++ob) {
-        const lds_byte* vp = work_v + (v_base ^ (64 * ob)) + 16 * ch * kRowBytes;
-        const bf16x4 lo = lds_read_tr(vp);
-        const bf16x4 hi = lds_read_tr(vp + 8 * kRowBytes);
-        const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        o[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf.v[ch], o[ob], 0, 0, 0);
-      }
+    half_tile_weigh(work_v, v_base, pf, o);
     // the working tile is rewritten in the next round: its reads must have returned
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   }
 
-  const float l_tot = half_swap_sum(l_run);
-  if (col_valid) {
-    float* part = p.partial + (static_cast<int64_t>(slot) * p.n_q_heads + head) * (kD + kPartialPad);
-#pragma unroll
-    for (int ob = 0; ob < kD / 32; ++ob)
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-        *reinterpret_cast<floatx4*>(part + 32 * ob + 8 * g + 4 * half) =
-            floatx4{o[ob][4 * g] * v_scale, o[ob][4 * g + 1] * v_scale, o[ob][4 * g + 2] * v_scale,
-                    o[ob][4 * g + 3] * v_scale};
-    if (half == 0) {
-      part[kD] = m_run;
-      part[kD + 1] = l_tot;
-    }
-  }
+  store_partial_state(p, col, half, o, m_run, l_run, v_scale);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -876,16 +679,10 @@ __global__ __launch_bounds__(64 * W) void decode_group_kv8_shared_kernel(AttnPar
   const int lane = threadIdx.x % 64, l32 = lane % 32, half = lane / 32;
   const int r = p.n_q_heads / p.n_kv_heads;
   const int qpw = 32 / r;
-  // same id mapping as decode_group_shared_kernel; this launch covers the rows of pool items only
-  const int in_block = blockIdx.x % 8;
-  const int row_id = (blockIdx.x / 8) % p.launch_rows, hk = (blockIdx.x / 8) / p.launch_rows;
-  typedef const __attribute__((address_space(4))) int32_t* const_words;
-  const int row = ((const_words)(reinterpret_cast<uintptr_t>(p.gm_rows)))[p.row_offset + row_id];
-  const int wg_batch = row & 0xFF;
-  const int item = 8 * (row >> 8) + in_block;
-  if (item >= p.n_gm_items) return;
-  const const_words runs = (const_words)(reinterpret_cast<uintptr_t>(p.gm_item_run));
-  const int first_key = runs[4 * item + 0], n_keys = runs[4 * item + 1], n_q = runs[4 * item + 2];
+  // this launch covers the rows of pool items only; a row's batch counts batches of W * qpw queries
+  DecodeItem it;
+  if (!locate_decode_item(p, it) || it.self_item) return;
+  const int hk = it.hk, wg_batch = it.batch, n_q = it.n_q, first_key = it.first_key, n_keys = it.n_keys;
   const int n_half = (n_keys + kHalf - 1) / kHalf;
   const int n_pass = (n_q + qpw - 1) / qpw;
   if (wg_batch * W >= n_pass) return;  // (the same for all waves: the workgroup leaves as one)
@@ -950,27 +747,13 @@ __global__ __launch_bounds__(64 * W) void decode_group_kv8_shared_kernel(AttnPar
                      (((2 * (l32 / 16) + (lane % 4) / 2) ^ (4 * ((lane % 16) / 4))) * 16) + (lane % 2) * 8;
 
   // ---- this lane's column ----
-  const int q_local = pass * qpw + l32 / r;  // < 32 also for a wave without a batch
-  const bool col_valid = active && q_local < n_q;
-  typedef int intx4 __attribute__((ext_vector_type(4)));
-  const intx4 ref = *reinterpret_cast<const intx4*>(p.gm_ref_pad + (static_cast<int64_t>(item) * 32 + q_local) * 4);
-  const int u = ref[0], slot = ref[1];
-  const int head = hk * r + l32 % r;
-  const float* rot = nullptr;
-  if (ROPE) {
-    const int rot_id = min(max(ref[2] + p.self_len[u] - 1, 0), p.rope_n_pos - 1);
-    rot = p.rope_table + static_cast<int64_t>(rot_id) * kD + 16 * half;
-    asm volatile("" : "+v"(rot));
-  }
-  const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(u) * p.q.stride_tok +
-                     static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
-  asm volatile("" : "+v"(qp));
+  const DecodeColumn col = decode_column<ROPE>(p, it, pass, active, r, l32, half);
   issue_pair(0);
   if (1 < n_half) issue_pair(1);
   const float c2 = p.scale_log2e * p.k_scale8[hk];
   const float v_scale = p.v_scale8[hk];
   bf16x8 qf[kD / 16];
-  load_query_fragments<ROPE>(qp, rot, c2, qf);
+  load_query_fragments<ROPE>(col.qp, col.rot, c2, qf);
   floatx16 o[kD / 32];
 #pragma unroll
   for (int ob = 0; ob < kD / 32; ++ob)
@@ -994,21 +777,7 @@ __global__ __launch_bounds__(64 * W) void decode_group_kv8_shared_kernel(AttnPar
     half_tile_attend(work_k, work_v, len, k_base, v_base, half, qf, o, m_run, l_run);
   }
 
-  const float l_tot = half_swap_sum(l_run);
-  if (col_valid) {
-    float* part = p.partial + (static_cast<int64_t>(slot) * p.n_q_heads + head) * (kD + kPartialPad);
-#pragma unroll
-    for (int ob = 0; ob < kD / 32; ++ob)
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-        *reinterpret_cast<floatx4*>(part + 32 * ob + 8 * g + 4 * half) =
-            floatx4{o[ob][4 * g] * v_scale, o[ob][4 * g + 1] * v_scale, o[ob][4 * g + 2] * v_scale,
-                    o[ob][4 * g + 3] * v_scale};
-    if (half == 0) {
-      part[kD] = m_run;
-      part[kD + 1] = l_tot;
-    }
-  }
+  store_partial_state(p, col, half, o, m_run, l_run, v_scale);
 }
 
 // Merge the partial states of one (query, head): slots [slot_ptr[u], slot_ptr[u+1]).

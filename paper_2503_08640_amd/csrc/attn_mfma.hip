@@ -19,15 +19,12 @@
 // supplies the address of key k0 + i/4, channels c0 + 4*(i%4).. and receives keys
 // k0..k0+3 of channel c0 + i.
 #include "kernels.hpp"
+#include "mfma_common.hpp"
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-typedef short shortx4 __attribute__((ext_vector_type(4)));
+using namespace dbsa_mfma;
+
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBN = 64;            // keys per KV tile
@@ -50,24 +47,6 @@ __device__ inline bf16x8 pack8(const floatx16& s, int first) {
   for (int i = 0; i < 4; ++i)
     u.p[i] = __builtin_convertvector(floatx2{s[first + 2 * i], s[first + 2 * i + 1]}, bf16x2);
   return u.v;
-}
-
-// LDS transpose read of 4 keys x 16 channels per 16-lane group (see the file header).
-__device__ inline bf16x4 lds_read_tr(const __bf16* p) {
-  typedef __attribute__((address_space(3))) shortx4* lds_ptr;
-  const shortx4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
-  return __builtin_bit_cast(bf16x4, t);
-}
-
-// Exchange a value between lane l and lane l^32 (the two half-waves hold the two key
-// halves of the same row) and combine it.
-__device__ inline float half_swap_max(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ inline float half_swap_sum(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 constexpr float kRescaleSlack = 8.f;  // log2 units the running max may lag before accumulators are rescaled

@@ -38,16 +38,11 @@
 #include <utility>
 
 #include "kernels.hpp"
+#include "mfma_common.hpp"
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef short shortx4 __attribute__((ext_vector_type(4)));
+using namespace dbsa_mfma;
 
 constexpr int kD = 128;
 constexpr int kBN = 64;                       // keys per KV tile
@@ -56,69 +51,6 @@ constexpr int kTileBytes = kBN * kRowBytes;   // 16 KiB per K or V tile
 constexpr int kRing = 4;                      // operand fragments in flight per wave (divides 32)
 constexpr int kDist = kRing - 1;              // a fragment is read this many matrix instructions early
 constexpr float kRescaleSlack = 8.f;          // log2 units
-
-typedef __attribute__((address_space(3))) unsigned char lds_byte;
-typedef const __attribute__((address_space(4))) int32_t* const_words;  // read-only lists: scalar loads
-
-#define DBSA_INLINE __attribute__((always_inline))
-
-// calls f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): loops whose index must
-// stay a compile-time constant (register arrays, immediate LDS offsets)
-template <typename F, int... I>
-__device__ DBSA_INLINE void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
-  (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, typename F>
-__device__ DBSA_INLINE void static_for(F&& f) {
-  static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
-__device__ inline bf16x4 lds_read_tr(const lds_byte* p) {
-  typedef __attribute__((address_space(3))) shortx4* tr_ptr;
-  const shortx4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(p));
-  return __builtin_bit_cast(bf16x4, t);
-}
-
-// Combine a value held by lanes l and l^32 (the two half-waves hold the two key halves of
-// the same row).
-__device__ inline float half_swap_max(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ inline float half_swap_sum(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-// 16 bytes per lane from global memory straight into LDS: lane l's piece lands at
-// LDS byte address lds_addr + 16*l.  Issued through inline assembly so that the transfer
-// stays asynchronous: the kernel waits for it explicitly (vmcnt) right before the workgroup
-// barrier that publishes the stage, instead of before the next LDS read of any stage.
-// Both addresses are wave-uniform and must reach the instruction in scalar registers.  The
-// callers keep every step of their computation scalar (pool bases made uniform once with
-// uniform64, tile starts from scalar loads), so that forming them costs scalar instructions
-// only and no round trip through the vector unit.
-__device__ inline void dma16(uint64_t gbase, unsigned byte_off, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_addr), "v"(byte_off), "s"(gbase)
-               : "memory");
-}
-
-// A wave-uniform 64-bit value, in scalar registers as far as the compiler is concerned.
-// (readfirstlane returns a signed int: widen through unsigned, or the low word would be sign-extended)
-__device__ inline uint64_t uniform64(uint64_t x) {
-  const unsigned hi = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(x >> 32)));
-  const unsigned lo = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(x & 0xFFFFFFFFu)));
-  return (static_cast<uint64_t>(hi) << 32) | static_cast<uint64_t>(lo);
-}
-
-// Wait until at most N vector-memory operations of this wave are outstanding (they complete
-// in issue order).  The memory clobber keeps LDS accesses of the awaited stage below the wait.
-template <int N>
-__device__ inline void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
 
 struct TileRef {
   int start, len;
@@ -273,35 +205,13 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   const float c2 = p.scale_log2e;
   bf16x8 qf[kD / 16];
   const const_words lshift = (const_words)(reinterpret_cast<uintptr_t>(p.list_shift + (ROPE ? e0 : 0)));
-  // rebuilds qf rotated at id shift + (row inside the tile); channel d < 64 of chunk c pairs with
-  // channel d + 64 of chunk c + 4, both held by this lane
+  // rebuilds qf rotated at id shift + (row inside the tile)
   auto load_q_rotated = [&](int shift) DBSA_INLINE {
     const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(row_tok) * p.q.stride_tok +
                        static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
     const int id = min(max(shift + row_local, 0), p.rope_n_pos - 1);
     const float* rot = p.rope_table + static_cast<int64_t>(id) * kD + 16 * half;
-#pragma unroll
-    for (int c = 0; c < kD / 32; ++c) {
-      const bf16x8 lo = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
-      const bf16x8 hi = *reinterpret_cast<const bf16x8*>(qp + 16 * (c + kD / 32));
-      floatx4 cs[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) cs[j] = *reinterpret_cast<const floatx4*>(rot + 32 * c + 4 * j);
-      union {
-        bf16x8 v;
-        bf16x2 p2[4];
-      } a, b;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float x0 = static_cast<float>(lo[2 * e]), y0 = static_cast<float>(hi[2 * e]);
-        const float x1 = static_cast<float>(lo[2 * e + 1]), y1 = static_cast<float>(hi[2 * e + 1]);
-        const float c0 = cs[e][0] * c2, s0 = cs[e][1] * c2, c1 = cs[e][2] * c2, s1 = cs[e][3] * c2;
-        a.p2[e] = __builtin_convertvector(floatx2{x0 * c0 - y0 * s0, x1 * c1 - y1 * s1}, bf16x2);
-        b.p2[e] = __builtin_convertvector(floatx2{y0 * c0 + x0 * s0, y1 * c1 + x1 * s1}, bf16x2);
-      }
-      qf[c] = a.v;
-      qf[c + kD / 32] = b.v;
-    }
+    load_query_fragments<true>(qp, rot, c2, qf);
   };
   int cur_shift = 0, nxt_shift = 0;  // rotation ids of the entry whose scores are computed next / after that
   if constexpr (ROPE) {
@@ -311,19 +221,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_prefill_kernel(AttnParams p) 
   } else {
     const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(row_tok) * p.q.stride_tok +
                        static_cast<int64_t>(head) * p.q.stride_head + 8 * half;
-#pragma unroll
-    for (int c = 0; c < kD / 16; ++c) {
-      const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
-      union {
-        bf16x8 v;
-        bf16x2 p2[4];
-      } sc;
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        sc.p2[e] = __builtin_convertvector(
-            floatx2{static_cast<float>(raw[2 * e]) * c2, static_cast<float>(raw[2 * e + 1]) * c2}, bf16x2);
-      qf[c] = sc.v;
-    }
+    load_query_fragments<false>(qp, nullptr, c2, qf);
   }
 
   floatx16 o[kD / 32];
