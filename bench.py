@@ -24,9 +24,10 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# tokens per Q tile (x 4 query heads of one KV head per workgroup)
+# tokens per Q tile (x 4 query heads of one KV head per workgroup); 32-token queries (config 4) take 32-token tiles
 from paper_2503_08640_amd.binding import BENCH_BLOCK_M_PREENCODE as PRE_BLOCK_M  # noqa: E402
 from paper_2503_08640_amd.binding import BENCH_BLOCK_M_QUERY as QUERY_BLOCK_M  # noqa: E402
+from paper_2503_08640_amd.binding import BENCH_BLOCK_M_SHORT_QUERY as SHORT_QUERY_BLOCK_M  # noqa: E402
 
 
 def visible_pairs_pre(pool, prev_window: int = 0) -> int:
@@ -167,7 +168,7 @@ def config4_sweep(torch, B, pc, k, v, iters: int = 20):
         lens = np.diff(qc.cu_qlens)
         self_len = torch.from_numpy((lens + 1).astype(np.int32)).cuda()
         lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, cu_qlens=qc.cu_qlens,
-                                  sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, n_split=0, block_m=QUERY_BLOCK_M, block_n=64)
+                                  sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, n_split=0, block_m=SHORT_QUERY_BLOCK_M, block_n=64)
         ws = torch.empty(max(16, lay.workspace_bytes(hq, d)), dtype=torch.uint8, device="cuda")
         st = [stats(launch_samples(torch, fn, n)) for fn, n in
               ((lambda: B.dbsa_query_attn(lay, qs, ks, vs, k, v, pc.scale, out=oq, workspace=ws), max(iters, MIN_STAGE_LAUNCHES)),
@@ -480,8 +481,8 @@ def main() -> int:
             "launch_stats": {"preencode": stats(pre_s), "query_prefill": stats(query_s), "decode_step": stats(decode_s)},
         },
         "roofline": {
-            "kernel": "attn_prefill64_kernel<2,1,false,true> (pre-encode launch: persistent, two waves of 64 query rows "
-                      "per workgroup, two workgroups per compute unit; the <2,1,true,*> instances serve the query prefill)",
+            "kernel": "attn_prefill64_kernel<4,2,false,true> (pre-encode launch: persistent, four waves of 64 query rows "
+                      "per workgroup, one workgroup per compute unit; the <4,2,true,*> instances serve the query prefill)",
             "bound": "mfma", "achieved": pre_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": pre_tflops / PEAK_BF16_TFLOPS, "traffic": traffic.get("preencode"),
             "traffic_measured_at": traffic_at,
@@ -490,7 +491,7 @@ def main() -> int:
                             "frac_at_median": flops_pre / stats(pre_s)["median_ms"] / 1e9 / PEAK_BF16_TFLOPS},
         },
         "roofline_query_prefill": {
-            "kernel": "attn_prefill64_kernel<2,1,true,false> + prefill_merge_kernel (32 Q tiles x 8 head blocks, lists cut in two)",
+            "kernel": "attn_prefill64_kernel<4,2,true,false> + prefill_merge_kernel (16 Q tiles x 8 head blocks, lists cut in two)",
             "bound": "mfma", "achieved": flops_query / query_ms / 1e9, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": flops_query / query_ms / 1e9 / PEAK_BF16_TFLOPS, "traffic": traffic.get("query_prefill"),
             "algorithmic": {"useful_tflop_per_launch": flops_query / 1e12, "launch_ms": query_ms,

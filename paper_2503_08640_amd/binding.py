@@ -17,11 +17,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdbsa.so")
 
 # Q-tile heights the benchmark launches with for grouped-query models (4 query heads per KV head):
-# 32 tokens x 4 heads = four waves per workgroup, two workgroups per compute unit, so that one
-# workgroup's prologue and epilogue overlap the other's tile loop.  The full-size GPU tests use
+# 64 tokens x 4 heads = four waves of 64 rows per workgroup, one workgroup per compute unit: every
+# K/V tile a compute unit fetches serves 256 rows, and each wave issues a quarter of its loads
+# (measured against 32-token tiles, two workgroups of two waves per compute unit: pre-encode of
+# the 90k pool 8 % faster, prefill of 64-token queries 20 %).  Queries shorter than 64 tokens keep
+# 32-token tiles (half the rows of a 64-token tile would be padding).  The full-size GPU tests use
 # the same values.
-BENCH_BLOCK_M_PREENCODE = 32
-BENCH_BLOCK_M_QUERY = 32
+BENCH_BLOCK_M_PREENCODE = 64
+BENCH_BLOCK_M_QUERY = 64
+BENCH_BLOCK_M_SHORT_QUERY = 32
 
 DBSA_OK = 0
 DBSA_ERR_INVALID_ARG = -1
