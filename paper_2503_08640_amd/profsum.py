@@ -2,6 +2,7 @@
 profiles/hbm_traffic.json (the HBM bytes per launch that bench.py prints as `traffic`).
 
     python -m paper_2503_08640_amd.profsum stats    <..._kernel_stats.csv>
+    python -m paper_2503_08640_amd.profsum trace    <..._kernel_trace.csv> [--match SUBSTR ...]
     python -m paper_2503_08640_amd.profsum counters <..._counter_collection.csv> [--match SUBSTR ...]
     python -m paper_2503_08640_amd.profsum traffic  --fetch <csv> --write <csv> --out profiles/hbm_traffic.json
                                                     [--commit HASH]
@@ -54,6 +55,41 @@ def cmd_stats(args) -> int:
     return 0
 
 
+def clusters(durations, ratio: float = 1.5):
+    """Splits {dispatch: duration} into groups of similar duration (sorted; a new group starts where the next
+    duration is more than `ratio` times the one before): one kernel name often serves launches of several sizes."""
+    order = sorted(durations, key=durations.get)
+    groups, cur = [], []
+    for d in order:
+        if cur and durations[d] > ratio * durations[cur[-1]]:
+            groups.append(cur)
+            cur = []
+        cur.append(d)
+    if cur:
+        groups.append(cur)
+    return groups
+
+
+def cmd_trace(args) -> int:
+    dur, grid = defaultdict(dict), defaultdict(dict)
+    for r in csv.DictReader(open(args.file, newline="")):
+        k = short_name(r["Kernel_Name"], 200)
+        if args.match and not any(m in k for m in args.match):
+            continue
+        d = int(r["Dispatch_Id"])
+        dur[k][d] = float(r["End_Timestamp"]) - float(r["Start_Timestamp"])
+        grid[k][d] = (int(r["Grid_Size_X"]) // max(1, int(r["Workgroup_Size_X"])), int(r["Grid_Size_Y"]), int(r["Grid_Size_Z"]),
+                      int(r["Workgroup_Size_X"]))
+    print(f"{'kernel (launches of similar duration grouped)':<58}{'calls':>6}{'average us':>12}{'min us':>10}{'max us':>10}  workgroups x threads")
+    for k in sorted(dur, key=lambda k: -sum(dur[k].values())):
+        for g in clusters(dur[k]):
+            v = [dur[k][d] / 1e3 for d in g]
+            grids = sorted({grid[k][d] for d in g})
+            gs = ", ".join(f"{a}x{b}x{c} x {t}" if (b, c) != (1, 1) else f"{a} x {t}" for a, b, c, t in grids[:3]) + (" ..." if len(grids) > 3 else "")
+            print(f"{short_name(k, 56):<58}{len(v):>6}{sum(v) / len(v):>12.2f}{min(v):>10.2f}{max(v):>10.2f}  {gs}")
+    return 0
+
+
 def read_counters(path):
     """-> {kernel: {counter: [value per dispatch]}}, {kernel: [duration ns per dispatch]}, {kernel: grid sizes}"""
     vals = defaultdict(lambda: defaultdict(dict))
@@ -73,13 +109,14 @@ def cmd_counters(args) -> int:
     for k in sorted(vals):
         if args.match and not any(m in k for m in args.match):
             continue
-        n = len(dur[k])
-        mean_us = sum(dur[k].values()) / n / 1e3
-        print(f"{short_name(k, 100)}   dispatches {n}   mean duration under the counters {mean_us:.1f} us   "
-              f"grid {sorted(set(grid[k].values()))}")
-        for c in sorted(vals[k]):
-            v = list(vals[k][c].values())
-            print(f"    {c:<34} mean per dispatch {sum(v) / len(v):>18.1f}")
+        for g in clusters(dur[k]):
+            n = len(g)
+            mean_us = sum(dur[k][d] for d in g) / n / 1e3
+            print(f"{short_name(k, 100)}   dispatches {n}   mean duration under the counters {mean_us:.1f} us   "
+                  f"grid {sorted({grid[k][d] for d in g})}")
+            for c in sorted(vals[k]):
+                v = [vals[k][c][d] for d in g if d in vals[k][c]]
+                print(f"    {c:<34} mean per dispatch {sum(v) / max(1, len(v)):>18.1f}")
     return 0
 
 
@@ -153,6 +190,10 @@ def main() -> int:
     a.add_argument("file")
     a.add_argument("--min-percent", type=float, default=0.05)
     a.set_defaults(fn=cmd_stats)
+    a = sub.add_parser("trace")
+    a.add_argument("file")
+    a.add_argument("--match", nargs="*", default=[])
+    a.set_defaults(fn=cmd_trace)
     a = sub.add_parser("counters")
     a.add_argument("file")
     a.add_argument("--match", nargs="*", default=[])
