@@ -230,6 +230,20 @@ int dbsa_layout_export_schedule(const dbsa_layout* layout, int32_t n_classes, co
                                 const int32_t** records);
 
 /*
+ * The decode schedule's work items with up to 64 queries each (plumbing; query-stage layouts):
+ * record i = four int32 (first reference, references, first tile, tiles): the queries
+ * qrefs[first reference .. + references) of dbsa_layout_export_decode_groups, at most 64, over the
+ * tiles seg_ent[first tile .. + tiles) of one run of one segment.  Every (item, query) pair of the
+ * decode schedule appears in exactly one record, with the slot it has there.  row_fill = share of
+ * the 64 rows of a record that carry a query, weighted by tiles: a decode step with four query
+ * heads per KV head, no re-positioning and row_fill >= 0.55 runs these records as a dense
+ * contraction (64 queries per wavefront) instead of the 32-column work items; the partial states
+ * and the merge are the same.  The array belongs to the layout.  Errors: INVALID_ARG.
+ */
+int dbsa_layout_export_matrix_records(const dbsa_layout* layout, const int32_t** records, int64_t* n_records,
+                                      float* row_fill);
+
+/*
  * Device blocks (each with a pinned host twin) that hold the lists of destroyed layouts and wait
  * to be reused by a later dbsa_layout_build (plumbing).  At most 16 are kept: idle blocks beyond
  * that are freed, oldest first, when a layout is destroyed or a build has to allocate.

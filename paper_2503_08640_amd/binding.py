@@ -42,7 +42,7 @@ EXPORTED_SYMBOLS = (
     "dbsa_strerror", "dbsa_layout_build", "dbsa_layout_build_append", "dbsa_layout_export", "dbsa_layout_export_decode",
     "dbsa_layout_export_decode_groups", "dbsa_layout_export_order", "dbsa_layout_export_positions", "dbsa_layout_destroy", "dbsa_workspace_bytes", "dbsa_preencode_attn",
     "dbsa_query_attn", "dbsa_decode_attn", "dbsa_rope_table", "dbsa_rope_apply", "dbsa_query_attn_rope",
-    "dbsa_decode_attn_rope", "dbsa_decode_attn_kv8", "dbsa_decode_attn_kv8_rope", "dbsa_decode_attn_static", "dbsa_pooled_list_blocks",
+    "dbsa_decode_attn_rope", "dbsa_decode_attn_kv8", "dbsa_decode_attn_kv8_rope", "dbsa_decode_attn_static", "dbsa_pooled_list_blocks", "dbsa_layout_export_matrix_records",
     "dbsa_layout_export_schedule",
 )
 DBSA_STATIC_SCRATCH_BYTES = 32 << 20
@@ -107,6 +107,9 @@ def lib() -> C.CDLL:
     L.dbsa_layout_export_schedule.restype = C.c_int
     L.dbsa_layout_export_schedule.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.POINTER(C.c_int32)),
                                               C.POINTER(C.POINTER(C.c_int32))]
+    L.dbsa_layout_export_matrix_records.restype = C.c_int
+    L.dbsa_layout_export_matrix_records.argtypes = [C.c_void_p, C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int64),
+                                                    C.POINTER(C.c_float)]
     L.dbsa_pooled_list_blocks.restype = C.c_int32
     L.dbsa_pooled_list_blocks.argtypes = []
     L.dbsa_layout_destroy.restype = None
@@ -241,6 +244,14 @@ class Layout:
         def arr(p, n):
             return np.ctypeslib.as_array(p, shape=(n,)).copy() if n else np.zeros(0, np.int32)
         return arr(ls, n_ent), arr(qs, nr.value), arr(cl, n_queries)
+
+    def export_matrix_records(self):
+        """-> (records [n, 4] int32 copies: (first reference, references, first tile, tiles), row_fill)."""
+        rp, n, fill = C.POINTER(C.c_int32)(), C.c_int64(), C.c_float()
+        _check(lib().dbsa_layout_export_matrix_records(self.handle, C.byref(rp), C.byref(n), C.byref(fill)),
+               "dbsa_layout_export_matrix_records")
+        rec = np.ctypeslib.as_array(rp, shape=(n.value, 4)).copy() if n.value else np.zeros((0, 4), np.int32)
+        return rec, float(fill.value)
 
     def export_schedule(self, n_classes: int):
         """-> (class_ptr [n_classes+1], records [n_qtiles, 4]) int32 copies."""

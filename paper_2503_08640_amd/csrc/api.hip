@@ -146,12 +146,15 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
                b_gsp = L->gm_slot_ptr.size() * sizeof(int64_t),
                b_lsh = L->list_shift.size() * sizeof(int32_t), b_gir = L->gm_item_run.size() * sizeof(int32_t),
                b_grp = L->gm_ref_pad.size() * sizeof(int32_t), b_grw = L->gm_rows.size() * sizeof(int32_t),
-               b_srec = L->qtile_tab.size() * sizeof(int32_t), b_sptr = (kMaxSchedClasses + 1) * sizeof(int32_t);
+               b_gse = L->gm_seg_ent.size() * sizeof(int32_t), b_gqr = L->gm_qrefs.size() * sizeof(int32_t),
+               b_srec = L->qtile_tab.size() * sizeof(int32_t), b_sptr = (kMaxSchedClasses + 1) * sizeof(int32_t),
+               b_mrec = L->mx_rec.size() * sizeof(int32_t);
   const size_t o_tab = 0, o_ptr = o_tab + pad(b_tab), o_ent = o_ptr + pad(b_ptr), o_ord = o_ent + pad(b_ent),
                o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), o_gsp = o_spl + pad(b_spl),
                o_lsh = o_gsp + pad(b_gsp), o_gir = o_lsh + pad(b_lsh), o_grp = o_gir + pad(b_gir),
-               o_grw = o_grp + pad(b_grp), o_srec = o_grw + pad(b_grw), o_sptr = o_srec + pad(b_srec),
-               lists_end = o_srec, total = o_sptr + pad(b_sptr) + 256;
+               o_grw = o_grp + pad(b_grp), o_gse = o_grw + pad(b_grw), o_gqr = o_gse + pad(b_gse),
+               o_srec = o_gqr + pad(b_gqr), o_sptr = o_srec + pad(b_srec), o_mrec = o_sptr + pad(b_sptr),
+               o_mptr = o_mrec + pad(b_mrec), lists_end = o_srec, total = o_mptr + pad(b_sptr) + 256;
   ListBlock blk{};
   hipError_t e = acquire_block(total, &blk);
   if (e != hipSuccess) return e;
@@ -170,12 +173,14 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   put(o_gir, L->gm_item_run.data(), b_gir);
   put(o_grp, L->gm_ref_pad.data(), b_grp);
   put(o_grw, L->gm_rows.data(), b_grw);
+  put(o_gse, L->gm_seg_ent.data(), b_gse);
+  put(o_gqr, L->gm_qrefs.data(), b_gqr);
   // the staging twin stays with the block, so nothing has to wait for the copy here; calls on
   // other streams are ordered behind it through the event
   hipEvent_t uploaded = nullptr;
   e = hipEventCreateWithFlags(&uploaded, hipEventDisableTiming);
   if (e == hipSuccess) {
-    // (the room behind lists_end is filled by the first call that uses a schedule)
+    // (the room behind lists_end is filled by the first calls that use a schedule)
     e = hipMemcpyAsync(blk.dev, blk.pinned, lists_end, hipMemcpyHostToDevice, stream);
     if (e == hipSuccess) e = hipEventRecord(uploaded, stream);
     if (e != hipSuccess) {
@@ -205,8 +210,12 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   L->dev.gm_item_run = reinterpret_cast<int32_t*>(b + o_gir);
   L->dev.gm_ref_pad = reinterpret_cast<int32_t*>(b + o_grp);
   L->dev.gm_rows = reinterpret_cast<int32_t*>(b + o_grw);
+  L->dev.gm_seg_ent = reinterpret_cast<int32_t*>(b + o_gse);
+  L->dev.gm_qrefs = reinterpret_cast<int32_t*>(b + o_gqr);
   L->dev.sched_rec = reinterpret_cast<int32_t*>(b + o_srec);
   L->dev.sched_ptr = reinterpret_cast<int32_t*>(b + o_sptr);
+  L->dev.mx_sched_rec = reinterpret_cast<int32_t*>(b + o_mrec);
+  L->dev.mx_sched_ptr = reinterpret_cast<int32_t*>(b + o_mptr);
   return hipSuccess;
 }
 
@@ -245,6 +254,7 @@ void free_device_lists(dbsa_layout* L) {
     }
     if (d.uploaded) (void)hipEventDestroy(static_cast<hipEvent_t>(d.uploaded));
     if (d.sched_uploaded) (void)hipEventDestroy(static_cast<hipEvent_t>(d.sched_uploaded));
+    if (d.mx_uploaded) (void)hipEventDestroy(static_cast<hipEvent_t>(d.mx_uploaded));
     release_block(blk);
     if (current != d.device) (void)hipSetDevice(current);
   }
@@ -280,32 +290,46 @@ int device_compute_units() {
   return cus[device];
 }
 
-// The layout's schedule for a persistent launch with n_classes workers per head block, on the
-// device and ordered before `stream`'s next work.  A layout keeps ONE schedule: false if it
+// One persistent-launch schedule of a layout: its host copy, its room in the device block, the
+// event behind its copy.
+struct ScheduleSlot {
+  int32_t* classes;
+  std::vector<int32_t>* ptr;
+  std::vector<int32_t>* rec;
+  bool* on_device;
+  int32_t* dev_rec;
+  int32_t* dev_ptr;
+  void** uploaded;
+  void** upload_stream;
+};
+
+// The schedule in `slot` for n_classes workers per head block, on the device and ordered before
+// `stream`'s next work; `balance` fills it on first use.  A slot keeps ONE schedule: false if it
 // already holds one for another number of workers, or if the schedule would have to be copied
-// while the stream is being captured into a graph (the caller then launches one workgroup per tile).
-bool ensure_schedule(const dbsa_layout* L, int32_t n_classes, hipStream_t stream) {
-  if (n_classes < 1 || n_classes > kMaxSchedClasses || !L->dev.sched_rec) return false;
+// while the stream is being captured into a graph (the caller then takes its other launch form).
+template <typename Balance>
+bool ensure_slot(const dbsa_layout* L, const ScheduleSlot& slot, int32_t n_classes, hipStream_t stream, Balance&& balance) {
+  if (n_classes < 1 || n_classes > kMaxSchedClasses || !slot.dev_rec) return false;
   std::lock_guard<std::mutex> lock(L->sched_mutex);
-  if (L->sched_classes != 0 && L->sched_classes != n_classes) return false;
-  if (!L->sched_on_device) {
+  if (*slot.classes != 0 && *slot.classes != n_classes) return false;
+  if (!*slot.on_device) {
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
       (void)hipGetLastError();
       return false;
     }
-    if (L->sched_classes == 0) {
-      dbsa_balance_schedule(L, n_classes, &L->sched_ptr, &L->sched_rec);
-      L->sched_classes = n_classes;
+    if (*slot.classes == 0) {
+      balance(n_classes, slot.ptr, slot.rec);
+      *slot.classes = n_classes;
     }
     // through the pinned twin of the device block, at the same offsets
     unsigned char* dev = static_cast<unsigned char*>(L->dev.base);
     unsigned char* pin = static_cast<unsigned char*>(L->dev.staging);
-    const size_t o_rec = reinterpret_cast<unsigned char*>(L->dev.sched_rec) - dev;
-    const size_t o_ptr = reinterpret_cast<unsigned char*>(L->dev.sched_ptr) - dev;
-    const size_t b_ptr = L->sched_ptr.size() * sizeof(int32_t);
-    std::memcpy(pin + o_rec, L->sched_rec.data(), L->sched_rec.size() * sizeof(int32_t));
-    std::memcpy(pin + o_ptr, L->sched_ptr.data(), b_ptr);
+    const size_t o_rec = reinterpret_cast<unsigned char*>(slot.dev_rec) - dev;
+    const size_t o_ptr = reinterpret_cast<unsigned char*>(slot.dev_ptr) - dev;
+    const size_t b_ptr = slot.ptr->size() * sizeof(int32_t);
+    std::memcpy(pin + o_rec, slot.rec->data(), slot.rec->size() * sizeof(int32_t));
+    std::memcpy(pin + o_ptr, slot.ptr->data(), b_ptr);
     hipEvent_t done = nullptr;
     if (hipEventCreateWithFlags(&done, hipEventDisableTiming) != hipSuccess) return false;
     if (hipMemcpyAsync(dev + o_rec, pin + o_rec, o_ptr + b_ptr - o_rec, hipMemcpyHostToDevice, stream) != hipSuccess ||
@@ -314,13 +338,32 @@ bool ensure_schedule(const dbsa_layout* L, int32_t n_classes, hipStream_t stream
       (void)hipEventDestroy(done);
       return false;
     }
-    L->dev.sched_uploaded = done;
-    L->dev.sched_stream = stream;
-    L->sched_on_device = true;
-  } else if (stream != L->dev.sched_stream) {
-    if (hipStreamWaitEvent(stream, static_cast<hipEvent_t>(L->dev.sched_uploaded), 0) != hipSuccess) return false;
+    *slot.uploaded = done;
+    *slot.upload_stream = stream;
+    *slot.on_device = true;
+  } else if (stream != *slot.upload_stream) {
+    if (hipStreamWaitEvent(stream, static_cast<hipEvent_t>(*slot.uploaded), 0) != hipSuccess) return false;
   }
   return true;
+}
+
+// the schedule of the prefill-shaped launches over the layout's Q tiles
+bool ensure_schedule(const dbsa_layout* L, int32_t n_classes, hipStream_t stream) {
+  const ScheduleSlot slot{&L->sched_classes, &L->sched_ptr, &L->sched_rec, &L->sched_on_device, L->dev.sched_rec,
+                          L->dev.sched_ptr, &L->dev.sched_uploaded, &L->dev.sched_stream};
+  return ensure_slot(L, slot, n_classes, stream, [&](int32_t n, std::vector<int32_t>* ptr, std::vector<int32_t>* rec) {
+    dbsa_balance_schedule(L, n, ptr, rec);
+  });
+}
+
+// the schedule of a decode step that runs its pool items as a contraction (dbsa_layout::mx_rec)
+bool ensure_matrix_schedule(const dbsa_layout* L, int32_t n_classes, hipStream_t stream) {
+  if (L->mx_rec.empty()) return false;
+  const ScheduleSlot slot{&L->mx_classes, &L->mx_sched_ptr, &L->mx_sched_rec, &L->mx_on_device, L->dev.mx_sched_rec,
+                          L->dev.mx_sched_ptr, &L->dev.mx_uploaded, &L->dev.mx_stream};
+  return ensure_slot(L, slot, n_classes, stream, [&](int32_t n, std::vector<int32_t>* ptr, std::vector<int32_t>* rec) {
+    dbsa_balance_records(L->mx_rec, n, ptr, rec);
+  });
 }
 
 bool tensor_ok(const dbsa_tensor& t, int dtype) {
@@ -351,6 +394,11 @@ int pick_heads_per_block(int r, int block_m) {
     }
   return best;
 }
+
+// share of a wave's 64 rows that must carry a query before a decode step runs its pool items as a
+// contraction (measured on a 90k-token pool, 8 KV heads: at 0.64-1.0 the step is 11-30 % faster than
+// with 32-column work items, at 0.5 it is even, below that slower)
+constexpr float kMatrixRowFill = 0.55f;
 
 // split query prefill: most runs per list, fewest tiles per run
 constexpr int64_t kMaxQuerySplit = 4;
@@ -650,6 +698,14 @@ int dbsa_layout_export_schedule(const dbsa_layout* L, int32_t n_classes, const i
   return DBSA_OK;
 }
 
+int dbsa_layout_export_matrix_records(const dbsa_layout* L, const int32_t** records, int64_t* n_records, float* row_fill) {
+  if (!L || !L->query_stage) return DBSA_ERR_INVALID_ARG;
+  if (records) *records = L->mx_rec.data();
+  if (n_records) *n_records = static_cast<int64_t>(L->mx_rec.size() / 4);
+  if (row_fill) *row_fill = L->mx_row_fill;
+  return DBSA_OK;
+}
+
 int32_t dbsa_pooled_list_blocks(void) {
   std::lock_guard<std::mutex> lock(g_pool_mutex);
   return static_cast<int32_t>(g_pool_blocks.size());
@@ -888,6 +944,24 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
       // to outweigh the barrier per half tile (measured over 16-256 queries at 10-100 % retrieval: 2
       // waves pay from ~1.5 walks per key on, 4 from ~2.3).
       p.decode_waves = pick_decode_waves(L, r);
+      // With four query heads per KV head and groups that serve many queries, the pool items run as a
+      // contraction: 64 queries per wave, the four heads as the four waves of a workgroup, one
+      // workgroup per compute unit walking a balanced share of the records (kernels.hpp:
+      // launch_decode_matrix_items).  Worth it once enough of the 64 rows carry a query.
+      if (r == 4 && !rope_table && L->mx_row_fill >= kMatrixRowFill) {
+        // one workgroup per compute unit, or per record where there are fewer
+        const int32_t classes = static_cast<int32_t>(
+            std::min<int64_t>(L->compute_units / n_kv_heads, static_cast<int64_t>(L->mx_rec.size() / 4)));
+        if (classes >= 1 && ensure_matrix_schedule(L, classes, s)) {
+          p.decode_matrix = 1;
+          p.decode_waves = 1;
+          p.mx_sched_rec = L->dev.mx_sched_rec;
+          p.mx_sched_ptr = L->dev.mx_sched_ptr;
+          p.mx_ent = L->dev.gm_seg_ent;
+          p.mx_classes = classes;
+          p.gather_refs = L->dev.gm_qrefs;
+        }
+      }
       fill_decode_rows(p, L, r / p.decode_waves);
       e = launch_decode_group(p, s);
     } else {

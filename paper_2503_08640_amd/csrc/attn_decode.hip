@@ -955,9 +955,35 @@ hipError_t launch_decode_group(const AttnParams& p_in, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
+  hipError_t e;
+  if (p.decode_matrix) {
+    // Many queries per group: the pool items as a contraction (64 query rows per wave, the four query
+    // heads of a KV head as the four waves of a workgroup, see attn_prefill64.hip), every query's own
+    // cache in the single-wave kernel, then the same merge.  The partial states land in the same slots.
+    AttnParams g = p;
+    g.sched_rec = p.mx_sched_rec;
+    g.sched_ptr = p.mx_sched_ptr;
+    g.sched_classes = p.mx_classes;
+    g.n_head_blocks = p.n_kv_heads;
+    g.list_ent = p.mx_ent;
+    g.heads_per_block = 4;
+    g.block_m = 64;
+    g.query_stage = 0;
+    g.q_split = 1;
+    g.lse = nullptr;
+    g.rope_table = nullptr;
+    e = launch_decode_matrix_items(g, stream);
+    if (e != hipSuccess) return e;
+    p.row_offset = p.gm_pool_rows;
+    p.launch_rows = p.gm_n_rows - p.gm_pool_rows;
+    decode_group_kernel<false><<<decode_grid(p), dim3(64), kLdsBytes, stream>>>(p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    decode_group_merge_kernel<<<dim3(p.n_queries * p.n_q_heads), dim3(kMergeThreads), 0, stream>>>(p);
+    return hipGetLastError();
+  }
   p.row_offset = 0;
   p.launch_rows = p.gm_n_rows;
-  hipError_t e;
   if (p.decode_waves == 4) {
     e = launch_shared<4>(p, stream);
   } else if (p.decode_waves == 2) {

@@ -107,8 +107,17 @@ struct StepCfg {
 // the host balanced (AttnParams::sched_*).  Its K/V tiles form ONE stream across Q tiles: while
 // the last tiles of a Q tile are being multiplied, the first tiles of the next one are already on
 // their way into the LDS ring, so that a Q tile costs no load latency beyond its own rows of Q.
-template <int NW, int SL, bool SELF, bool PERSIST>
+//
+// GATHER (with PERSIST): the rows of a "Q tile" are not consecutive tokens but the references
+// gather_refs[q_start .. q_start + q_len), pairs (row of q, slot): row i of the tile is q row
+// refs[i][0], and instead of a normalised output the kernel leaves the row's partial softmax state
+// (unnormalised accumulators, running maximum, row sum) in partial[slot][head].  This is how a
+// decode step with many queries per group runs as a contraction: a record is a run of a group's
+// tiles with up to 64 of the queries that selected the group, the four waves are the four query
+// heads of one KV head, and the merge pass of the decode step combines the slots.
+template <int NW, int SL, bool SELF, bool PERSIST, bool GATHER = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_prefill64_kernel(AttnParams p) {
+  static_assert(!GATHER || (PERSIST && !SELF), "gathered rows come with a schedule and pool tiles only");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   constexpr int kBlocksPerWave = 16 / NW;  // 1-KiB load blocks of one operand per wave
   constexpr int KS = 2 + SL, VS = 1 + SL;  // LDS stages of K and of V
@@ -309,6 +318,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
   // ---- per Q tile: rows, Q^T fragments, softmax state ----
   const float c2 = p.scale_log2e;
   int head[2], row_local[2], row_tok[2], q_pos[2];
+  int row_slot[2] = {0, 0};  // GATHER: where the row's partial state goes
   bool row_valid[2];
   auto place_rows = [&]() DBSA_INLINE {
 #pragma unroll
@@ -319,6 +329,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
       row_valid[rb] = row_local[rb] < q_len;
       row_tok[rb] = q_start + min(row_local[rb], q_len - 1);
       q_pos[rb] = q_start + row_local[rb];
+      if constexpr (GATHER) {
+        // (rows past the last reference repeat it: they compute on its row and store nothing)
+        typedef int intx2 __attribute__((ext_vector_type(2)));
+        const intx2 ref = *reinterpret_cast<const intx2*>(p.gather_refs + 2 * static_cast<int64_t>(row_tok[rb]));
+        row_tok[rb] = ref[0];
+        row_slot[rb] = ref[1];
+      }
     }
   };
   bf16x8 q_raw[2][kD / 16];
@@ -669,12 +686,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
     // the rows this Q tile writes; then the next Q tile's rows of Q are requested, and arrive
     // during the drain steps and the epilogue
     const int o_start = q_start, o_len = q_len;
-    int o_head[2], o_tok[2];
+    int o_head[2], o_tok[2], o_slot[2];
     bool o_valid[2];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
       o_head[rb] = head[rb];
       o_tok[rb] = row_tok[rb];
+      o_slot[rb] = row_slot[rb];
       o_valid[rb] = row_valid[rb];
     }
     const bool more = PERSIST && rec_k + 1 < rec_end;
@@ -698,13 +716,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
     l_run[1] += ls[1];
 
     // ---- epilogue ----
-    if (!PERSIST && gridDim.z > 1) {
+    if (GATHER || (!PERSIST && gridDim.z > 1)) {
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
         const float l_tot = half_swap_sum(l_run[rb]);
         if (!o_valid[rb]) continue;
-        float* part = p.partial + ((static_cast<int64_t>(o_tok[rb]) * p.n_q_heads + o_head[rb]) * gridDim.z + blockIdx.z) *
-                                      (kD + kPartialPad);
+        float* part = GATHER ? p.partial + (static_cast<int64_t>(o_slot[rb]) * p.n_q_heads + o_head[rb]) * (kD + kPartialPad)
+                             : p.partial + ((static_cast<int64_t>(o_tok[rb]) * p.n_q_heads + o_head[rb]) * gridDim.z + blockIdx.z) *
+                                               (kD + kPartialPad);
 #pragma unroll
         for (int ob = 0; ob < kD / 32; ++ob)
 #pragma unroll
@@ -765,12 +784,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
   }
 }
 
-template <int NW, int SL, bool SELF, bool PERSIST>
+template <int NW, int SL, bool SELF, bool PERSIST, bool GATHER = false>
 hipError_t launch_cfg64(const AttnParams& p, hipStream_t stream) {
   constexpr int lds_bytes = (3 + 2 * SL) * kTileBytes;
   static std::atomic<bool> attr_set{false};  // setting it twice from two threads is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill64_kernel<NW, SL, SELF, PERSIST>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill64_kernel<NW, SL, SELF, PERSIST, GATHER>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -778,7 +797,7 @@ hipError_t launch_cfg64(const AttnParams& p, hipStream_t stream) {
   const int n_split = p.q_split > 1 ? p.q_split : 1;
   const dim3 grid = PERSIST ? dim3(p.sched_classes * p.n_head_blocks)
                             : dim3(p.n_q_heads / p.heads_per_block, p.n_qtiles, n_split);
-  attn_prefill64_kernel<NW, SL, SELF, PERSIST><<<grid, dim3(NW * 64), lds_bytes, stream>>>(p);
+  attn_prefill64_kernel<NW, SL, SELF, PERSIST, GATHER><<<grid, dim3(NW * 64), lds_bytes, stream>>>(p);
   return hipGetLastError();
 }
 
@@ -803,4 +822,14 @@ hipError_t launch_prefill64(const AttnParams& p, hipStream_t stream) {
     case 8: return launch_stage64<4, 2>(p, stream);
     default: return hipErrorInvalidValue;
   }
+}
+
+// The pool items of a decode step as a contraction: p carries the schedule of the layout's matrix
+// records (sched_*), the segments' tile entries as list_ent, the flat references as gather_refs and
+// the decode step's q, pools and partial buffer; four query heads per KV head, 64-row tiles.
+hipError_t launch_decode_matrix_items(const AttnParams& p, hipStream_t stream) {
+  if (!p.sched_rec || !p.sched_ptr || !p.gather_refs || !p.partial || p.sched_classes < 1) return hipErrorInvalidValue;
+  if (p.heads_per_block != 4 || p.block_m != 64 || p.n_q_heads != 4 * p.n_kv_heads || p.n_head_blocks != p.n_kv_heads)
+    return hipErrorInvalidValue;
+  return launch_cfg64<4, 2, false, true, true>(p, stream);
 }

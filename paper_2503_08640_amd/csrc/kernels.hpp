@@ -62,6 +62,16 @@ struct AttnParams {
   const int32_t* sched_rec;
   const int32_t* sched_ptr;
   int32_t sched_classes, n_head_blocks;
+  // rows gathered through references (launch_decode_matrix_items): [n_refs][2] = (row of q, partial slot)
+  const int32_t* gather_refs;
+  // decode step: 1 = the pool items run as a contraction through launch_decode_matrix_items with the
+  // schedule mx_sched_* over list entries mx_ent, the self items in the ordinary kernel (gm_rows then
+  // holds the table of single-wave workgroups)
+  int32_t decode_matrix;
+  const int32_t* mx_sched_rec;
+  const int32_t* mx_sched_ptr;
+  const int32_t* mx_ent;
+  int32_t mx_classes;
   int32_t query_stage;        // prefill-shaped calls: 1 = query prefill (lists may name self tiles), 0 = pre-encode
   // re-positioning (null table: inputs carry their final positions already)
   const float* rope_table;    // [rope_n_pos][D/2][2] fp32 (cos, sin) of id * inv_freq
@@ -81,6 +91,9 @@ hipError_t launch_prefill_pipelined(const AttnParams& p, hipStream_t stream);
 // the same mathematics with 64 query rows per wave, one wave per SIMD (attn_prefill64.hip); kernel
 // only: launch_prefill_pipelined runs the merge pass of a split launch
 hipError_t launch_prefill64(const AttnParams& p, hipStream_t stream);
+// the same kernel over rows gathered through references, leaving partial softmax states: the pool
+// items of a decode step with many queries per group (attn_prefill64.hip)
+hipError_t launch_decode_matrix_items(const AttnParams& p, hipStream_t stream);
 // group-major split-KV decode + merge for head_dim 128 (attn_decode.hip)
 hipError_t launch_decode_group(const AttnParams& p, hipStream_t stream);
 // the same with pool K/V stored as fp8 (e4m3) bytes and per-KV-head scales

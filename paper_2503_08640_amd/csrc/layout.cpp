@@ -295,6 +295,27 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
 
   for (size_t i = 3; i < L->gm_items.size(); i += 4) L->gm_max_queries = std::max(L->gm_max_queries, L->gm_items[i]);
   for (const int32_t shift : L->gm_qshift) L->max_decode_shift = std::max<int64_t>(L->max_decode_shift, shift);
+  // The same runs with up to 64 queries each: consecutive items of one run (its batches of 32
+  // queries, whose references follow each other) are taken in pairs.  Slots do not change.
+  {
+    const size_t n_items = L->gm_items.size() / 4;
+    double rows = 0.0, used = 0.0;
+    for (size_t it = 0; it < n_items; ++it) {
+      const int32_t* a = &L->gm_items[4 * it];
+      int32_t n_q = a[3];
+      if (it + 1 < n_items) {
+        const int32_t* b = a + 4;
+        if (b[0] == a[0] && b[1] == a[1] && b[2] == a[2] + a[3] && a[3] == 32) {
+          n_q += b[3];
+          ++it;
+        }
+      }
+      L->mx_rec.insert(L->mx_rec.end(), {a[2], n_q, a[0], a[1]});
+      rows += 64.0 * a[1];
+      used += static_cast<double>(n_q) * a[1];
+    }
+    L->mx_row_fill = rows > 0.0 ? static_cast<float>(used / rows) : 0.f;
+  }
   {
     const size_t n_items = L->gm_items.size() / 4;
     L->gm_item_run.resize(n_items * 4);
@@ -365,36 +386,47 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
   return DBSA_OK;
 }
 
-void dbsa_balance_schedule(const dbsa_layout* L, int32_t n_classes, std::vector<int32_t>* class_ptr,
-                           std::vector<int32_t>* rec) {
-  constexpr int64_t kTileCost = 3;  // what a Q tile costs beyond its list, in list entries
-  const int64_t nt = L->n_qtiles();
+void dbsa_balance_records(const std::vector<int32_t>& rec_in, int32_t n_classes, std::vector<int32_t>* class_ptr,
+                          std::vector<int32_t>* rec) {
+  constexpr int64_t kTileCost = 3;  // what a record costs beyond its list, in list entries
+  const int64_t nt = static_cast<int64_t>(rec_in.size() / 4);
   std::vector<int64_t> load(static_cast<size_t>(n_classes), 0);
-  std::vector<std::vector<int32_t>> tiles_of(static_cast<size_t>(n_classes));
+  std::vector<std::vector<int32_t>> recs_of(static_cast<size_t>(n_classes));
   std::vector<int32_t> round, by_load(static_cast<size_t>(n_classes));
-  auto entries = [&](int32_t t) { return L->list_ptr[t + 1] - L->list_ptr[t]; };
+  auto entries = [&](int32_t t) { return static_cast<int64_t>(rec_in[4 * static_cast<size_t>(t) + 3]); };
   for (int64_t a = 0; a < nt; a += n_classes) {
     const int64_t b = std::min<int64_t>(nt, a + n_classes);
-    round.assign(L->order.begin() + a, L->order.begin() + b);
+    round.resize(static_cast<size_t>(b - a));
+    std::iota(round.begin(), round.end(), static_cast<int32_t>(a));
     std::stable_sort(round.begin(), round.end(), [&](int32_t x, int32_t y) { return entries(x) > entries(y); });
     std::iota(by_load.begin(), by_load.end(), 0);
     std::stable_sort(by_load.begin(), by_load.end(), [&](int32_t x, int32_t y) { return load[x] < load[y]; });
     for (size_t i = 0; i < round.size(); ++i) {
       const int32_t c = by_load[i];
-      tiles_of[c].push_back(round[i]);
+      recs_of[c].push_back(round[i]);
       load[c] += entries(round[i]) + kTileCost;
     }
   }
   class_ptr->assign(static_cast<size_t>(n_classes) + 1, 0);
   rec->clear();
-  rec->reserve(static_cast<size_t>(nt) * 4);
+  rec->reserve(rec_in.size());
   for (int32_t c = 0; c < n_classes; ++c) {
-    for (int32_t t : tiles_of[c]) {
-      rec->push_back(L->qtile_tab[4 * t + 0]);
-      rec->push_back(L->qtile_tab[4 * t + 1]);
-      rec->push_back(static_cast<int32_t>(L->list_ptr[t]));
-      rec->push_back(static_cast<int32_t>(entries(t)));
-    }
+    for (int32_t t : recs_of[c]) rec->insert(rec->end(), rec_in.begin() + 4 * static_cast<size_t>(t), rec_in.begin() + 4 * static_cast<size_t>(t) + 4);
     (*class_ptr)[c + 1] = static_cast<int32_t>(rec->size() / 4);
   }
+}
+
+void dbsa_balance_schedule(const dbsa_layout* L, int32_t n_classes, std::vector<int32_t>* class_ptr,
+                           std::vector<int32_t>* rec) {
+  const int64_t nt = L->n_qtiles();
+  std::vector<int32_t> in_order;
+  in_order.reserve(static_cast<size_t>(nt) * 4);
+  for (int64_t i = 0; i < nt; ++i) {
+    const int32_t t = L->order[static_cast<size_t>(i)];
+    in_order.push_back(L->qtile_tab[4 * t + 0]);
+    in_order.push_back(L->qtile_tab[4 * t + 1]);
+    in_order.push_back(static_cast<int32_t>(L->list_ptr[t]));
+    in_order.push_back(static_cast<int32_t>(L->list_ptr[t + 1] - L->list_ptr[t]));
+  }
+  dbsa_balance_records(in_order, n_classes, class_ptr, rec);
 }

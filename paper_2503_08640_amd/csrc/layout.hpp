@@ -31,6 +31,15 @@ struct dbsa_device_lists {
   int32_t* sched_ptr = nullptr;   // [kMaxSchedClasses + 1]
   void* sched_uploaded = nullptr; // event recorded behind the schedule's copy
   void* sched_stream = nullptr;   // stream of that copy
+  // decode steps that run their pool items as a contraction (dbsa_layout::mx_rec): the segments'
+  // tile entries, the flat references, and room for that launch's schedule, filled by the first
+  // decode call that uses it
+  int32_t* gm_seg_ent = nullptr;   // [n_seg_ent][2]
+  int32_t* gm_qrefs = nullptr;     // [n_qrefs][2]
+  int32_t* mx_sched_rec = nullptr; // [n_mx][4]
+  int32_t* mx_sched_ptr = nullptr; // [kMaxSchedClasses + 1]
+  void* mx_uploaded = nullptr;
+  void* mx_stream = nullptr;
   // ordering of the asynchronous upload against the calls that read the lists (HIP handles kept
   // as plain pointers so that host-only code can include this header)
   void* upload_stream = nullptr;  // stream the lists were copied on
@@ -80,6 +89,12 @@ struct dbsa_layout {
   int32_t gm_rows_off[7] = {0, 0, 0, 0, 0, 0, 0};   // table k is gm_rows[off[k] .. off[k+1])
   int32_t gm_pool_rows[6] = {0, 0, 0, 0, 0, 0};     // rows of table k that belong to pool items
   float gm_walks_per_key[6] = {1, 1, 1, 1, 1, 1};   // batches per pool item at 32 >> k queries per wave, weighted by keys
+  // The decode schedule's runs with up to 64 queries each, for steps that run as a contraction
+  // (64 query rows per wave): [n_mx][4] = (first reference in gm_qrefs, references, first tile entry
+  // in gm_seg_ent, entries), in the order of gm_items.  mx_row_fill: share of the 64 rows that carry
+  // a query, weighted by tiles.
+  std::vector<int32_t> mx_rec;
+  float mx_row_fill = 0.f;
   // figures the attention calls need on every launch, taken once at build time
   int32_t gm_max_queries = 1;       // most queries any schedule item serves
   int64_t shortest_list = 0;        // fewest entries any Q tile lists
@@ -97,6 +112,10 @@ struct dbsa_layout {
   mutable int32_t sched_classes = 0;
   mutable std::vector<int32_t> sched_ptr, sched_rec;
   mutable bool sched_on_device = false;
+  // the same for the records of mx_rec (a second, independent schedule)
+  mutable int32_t mx_classes = 0;
+  mutable std::vector<int32_t> mx_sched_ptr, mx_sched_rec;
+  mutable bool mx_on_device = false;
 
   mutable dbsa_device_lists dev;
   // direction of the last walk over the pool's keys by an attention call on this layout (the
@@ -120,6 +139,10 @@ constexpr int32_t kMaxSchedClasses = 512;
 // cost per tile.  Pure host integer work.
 void dbsa_balance_schedule(const dbsa_layout* L, int32_t n_classes, std::vector<int32_t>* class_ptr,
                            std::vector<int32_t>* rec);
+// The dealing rule itself, over records of four words in launch order whose last word is the
+// number of list entries.
+void dbsa_balance_records(const std::vector<int32_t>& rec_in, int32_t n_classes, std::vector<int32_t>* class_ptr,
+                          std::vector<int32_t>* rec);
 
 // Pure host integer work; returns a DBSA_* code and fills `L` on success.
 // first_group < 0: every segment; >= 0 (pre-encode only): Q tiles of groups first_group.. alone

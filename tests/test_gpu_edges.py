@@ -235,3 +235,28 @@ def test_default_decode_chunk_uses_the_devices_compute_unit_count():
     batches = int(np.diff(got["seg_ptr"]).sum()) * ((nq + 31) // 32)
     run_slots = max(1, cus * 6 // 8 * 3 // 4)
     assert got["chunk_tiles"] == max(1, min(32, -(-batches // run_slots)))
+
+
+@pytest.mark.parametrize("n_queries,n_select,groups", [(70, 2, 3), (130, 3, 3), (64, 2, 2), (200, 4, 5)])
+def test_decode_with_many_queries_per_group_as_a_contraction(n_queries, n_select, groups):
+    """Four query heads per KV head and groups that each serve dozens of queries: the step runs its pool items
+    with 64 queries per wave (batches of 64 + a ragged rest) and the queries' own caches in the single-wave
+    kernel.  Every query, two steps (own caches of 10 and 11 keys ... and longer), against the oracle."""
+    pc = small_pool_case("mxpool", 3500 + n_queries, hq=8, hkv=2, pool_tokens=2600, groups=groups, lens=(30, 140), sigma=0.5)
+    rng = np.random.default_rng(n_queries)
+    q_len = rng.integers(1, 80, size=n_queries).tolist()
+    qc = synth.make_query_case("mxq", 3501, pc, n_queries=n_queries, q_len=q_len, n_select=n_select, n_decode=2)
+    lay, kp, vp = _query_setup(pc, qc, 32, 0)
+    rec, fill = lay.export_matrix_records()
+    assert fill >= 0.55 and rec[:, 1].max() > 32, "this case is meant to take the contraction path"
+    _run_decode_steps(pc, qc, lay, kp, vp, range(2), f"{n_queries} queries x {n_select} of {groups} groups")
+    # twice the same step on twin layouts: bitwise equal (static schedule, no atomics)
+    lay2, _, _ = _query_setup(pc, qc, 32, 0)
+    shp = qc.k_cache.shape
+    kc = to_dev(qc.k_cache.reshape(-1, shp[2], shp[3])).view(shp)
+    vc = to_dev(qc.v_cache.reshape(-1, shp[2], shp[3])).view(shp)
+    sl = torch.from_numpy((np.diff(qc.cu_qlens) + 1).astype(np.int32)).cuda()
+    lay3, _, _ = _query_setup(pc, qc, 32, 0)
+    a = B.dbsa_decode_attn(lay2, to_dev(qc.dec_q[0]), kc, vc, sl, kp, vp, pc.scale)
+    b = B.dbsa_decode_attn(lay3, to_dev(qc.dec_q[0]), kc, vc, sl, kp, vp, pc.scale)
+    assert torch.equal(a, b)

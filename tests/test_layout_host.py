@@ -454,3 +454,29 @@ def test_persistent_schedule_deals_every_tile_once_and_balances(n_classes):
     assert B.lib().dbsa_layout_export_schedule(lay.handle, n_classes, None, None) == B.DBSA_OK
     assert B.lib().dbsa_layout_export_schedule(lay.handle, 0, None, None) == B.DBSA_ERR_INVALID_ARG
     assert B.lib().dbsa_layout_export_schedule(None, 4, None, None) == B.DBSA_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("n_queries,n_select", [(5, 2), (70, 2), (130, 3), (300, 1)])
+def test_matrix_records_cover_every_item_query_pair_once(n_queries, n_select):
+    """The decode schedule's runs with up to 64 queries per record: each (item, query) pair of the 32-query
+    schedule appears in exactly one record with the same tiles and the same slot; references are contiguous."""
+    pc = synth.make_pool_case("mxhost", 21, dtype="bf16", n_q_heads=2, n_kv_heads=1, head_dim=16, sink_len=70,
+                              pool_tokens=9000, demo_len_range=(30, 140), n_groups=4).pool
+    rng = np.random.default_rng(n_queries)
+    sel_ptr, sel_idx = synth.draw_selections(rng, n_queries, pc.n_groups, n_select)
+    cu = np.arange(n_queries + 1, dtype=np.int32)
+    lay = B.dbsa_layout_build(pc.sink_len, pc.demo_offsets, pc.group_demo_offsets, cu_qlens=cu, sel_ptr=sel_ptr,
+                              sel_idx=sel_idx, n_split=0, block_m=32, block_n=64, host_only=True)
+    got = lay.export_decode_groups(pc.n_groups, n_queries)
+    rec, fill = lay.export_matrix_records()
+    items, qrefs = got["items"], got["qrefs"]
+    assert np.all(rec[:, 1] >= 1) and np.all(rec[:, 1] <= 64)
+    # references of the records tile the reference array in order, without gaps
+    assert rec[0, 0] == 0 and np.array_equal(rec[1:, 0], (rec[:, 0] + rec[:, 1])[:-1]) and rec[-1, 0] + rec[-1, 1] == len(qrefs)
+    pairs_items = sorted((int(e0), int(en), int(q), int(s)) for e0, en, r0, nq in items for q, s in qrefs[r0:r0 + nq])
+    pairs_rec = sorted((int(e0), int(en), int(q), int(s)) for r0, nq, e0, en in rec for q, s in qrefs[r0:r0 + nq])
+    assert pairs_items == pairs_rec
+    want_fill = float((rec[:, 1] * rec[:, 3]).sum()) / float((64 * rec[:, 3]).sum())
+    assert abs(fill - want_fill) < 1e-6
+    # a record is one item or two consecutive ones of the same run
+    assert len(rec) >= (len(items) + 1) // 2
