@@ -151,9 +151,10 @@ def cmd_traffic(args) -> int:
     w_fac, w_cal = calibration(write, "WRITE_SIZE")
     print(f"calibration copy: FETCH_SIZE raw {f_cal[1]:.1f} -> factor {f_fac:.3f}; WRITE_SIZE raw {w_cal[1]:.1f} -> factor {w_fac:.3f}")
 
+    # attn_prefill64_kernel<waves, slack, SELF, PERSIST, GATHER>: SELF = false is the pre-encode launch
     groups = {
-        "preencode": [("attn_prefill64_kernel", ",false,")],
-        "query_prefill": [("attn_prefill64_kernel", ",true,"), ("prefill_merge_kernel",)],
+        "preencode": [("attn_prefill64_kernel<", "SELF=false")],
+        "query_prefill": [("attn_prefill64_kernel<", "SELF=true"), ("prefill_merge_kernel",)],
         "decode_step": [("decode_group_kernel",), ("decode_group_merge_kernel",)],
     }
     rec = {"_doc": "HBM bytes per launch from two rocprofv3 --pmc runs of bench.py --calib-copy (FETCH_SIZE, then "
@@ -165,7 +166,12 @@ def cmd_traffic(args) -> int:
     for name, parts in groups.items():
         # a kernel whose name contains another's (decode_group_merge_kernel / decode_group_kernel) is matched exactly
         def mean_of(table, needles):
-            hits = [k for k in table if all(n in k for n in needles)]
+            def has(k, n):
+                if n.startswith("SELF="):
+                    m = re.search(r"attn_prefill64_kernel<\d+,\d+,(true|false)", k)
+                    return bool(m) and m.group(1) == n[5:]
+                return n in k
+            hits = [k for k in table if all(has(k, n) for n in needles)]
             if needles == ("decode_group_kernel",):
                 hits = [k for k in hits if "merge" not in k]
             tot = sum(table[k][0] * table[k][1] for k in hits)
