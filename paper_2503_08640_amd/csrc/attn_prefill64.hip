@@ -381,13 +381,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
     asm volatile("" : "+v"(key0));  // keeps loop-invariant key indices out of registers: this path is rare
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-      const int limit = t.causal ? (q_pos[rb] - t.start) : kBN;  // visible iff key_local <= limit
+      // element i holds key key0 + 8 * (i / 4) + i % 4 of the tile; it is visible iff that index is below the
+      // tile's length and (causal tiles) not beyond the row's own position: one bound per lane, relative to key0
+      const int last = min(t.causal ? (q_pos[rb] - t.start) : kBN, t.len - 1) - key0;
+      // (a row block that sees all 32 keys of this half needs nothing: 27 is the largest element offset)
+      if (__builtin_amdgcn_ballot_w64(last < 27) == 0) continue;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key_local = key0 + (8 * (i / 4) + (i % 4));
-        const bool vis = key_local < t.len && key_local <= limit;
-        s[rb][i] = vis ? s[rb][i] : -INFINITY;
-      }
+      for (int i = 0; i < 16; ++i) s[rb][i] = (8 * (i / 4) + (i % 4)) <= last ? s[rb][i] : -INFINITY;
     }
   };
 

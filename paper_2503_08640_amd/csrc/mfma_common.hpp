@@ -75,6 +75,10 @@ __device__ inline uint64_t uniform64(uint64_t x) {
 // asynchronous: the kernels wait for it explicitly (vmcnt) where the data is needed, instead
 // of before the next LDS read of any kind.  gbase and lds_addr are wave-uniform and must reach
 // the instruction in scalar registers (uniform64, readfirstlane); m0 carries the LDS address.
+// m0 cannot be named as a clobber (it is a reserved register: the compiler warns and ignores the
+// entry), so the kernels that include this header use nothing for which the COMPILER keeps a value
+// of its own in m0 across statements: no LDS-DMA or LDS-direct builtins, no sendmsg, no indirect
+// register indexing.  The assembly re-loads m0 before every transfer and relies on no earlier value.
 __device__ inline void dma16(uint64_t gbase, unsigned byte_off, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
