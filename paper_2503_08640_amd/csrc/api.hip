@@ -395,11 +395,6 @@ int pick_heads_per_block(int r, int block_m) {
   return best;
 }
 
-// share of a wave's 64 rows that must carry a query before a decode step runs its pool items as a
-// contraction (measured on a 90k-token pool, 8 KV heads: at 0.64-1.0 the step is 11-30 % faster than
-// with 32-column work items, at 0.5 it is even, below that slower)
-constexpr float kMatrixRowFill = 0.55f;
-
 // split query prefill: most runs per list, fewest tiles per run
 constexpr int64_t kMaxQuerySplit = 4;
 constexpr int64_t kMinRun = 16;

@@ -716,14 +716,52 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
     l_run[1] += ls[1];
 
     // ---- epilogue ----
-    if (GATHER || (!PERSIST && gridDim.z > 1)) {
+    if constexpr (GATHER) {
+      // Partial states, 528-byte rows of fp32: like the normalised outputs below they go through LDS
+      // so that a store instruction writes whole 256-byte pieces of four rows instead of 16 bytes of
+      // each of 32 rows; a row block passes in two halves of 64 channels, 8 KiB of staging per wave.
+      __builtin_amdgcn_s_barrier();
+      const int k_last = (k_rd == 0 ? KS : k_rd) - 1, v_last = (v_rd == 0 ? VS : v_rd) - 1;
+      const bool in_k = (NW == 4 ? wave / 2 : wave) == 0;
+      const unsigned stag = lds0 + (in_k ? k_last : KS + v_last) * kTileBytes + (NW == 4 ? (wave % 2) * 8192 : 0);
+      typedef __attribute__((address_space(3))) floatx4* lds_f128;
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        const float l_tot = half_swap_sum(l_run[rb]);
+        float* head_base = p.partial + static_cast<int64_t>(o_head[rb]) * (kD + kPartialPad) + (lane % 16) * 4;
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+#pragma unroll
+          for (int ob2 = 0; ob2 < 2; ++ob2)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              const int ob = 2 * h2 + ob2;
+              *(lds_f128)(static_cast<uintptr_t>(stag + l32 * kRowBytes + (((8 * ob2 + 2 * g + half) ^ (l32 % 16)) * 16))) =
+                  floatx4{o[rb][ob][4 * g], o[rb][ob][4 * g + 1], o[rb][ob][4 * g + 2], o[rb][ob][4 * g + 3]};
+            }
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int row = 4 * i + lane / 16;
+            const floatx4 piece = *(lds_f128)(static_cast<uintptr_t>(stag + row * kRowBytes + (((lane % 16) ^ (row % 16)) * 16)));
+            // the slot of that row is held by the lane that owns the row
+            const int slot = __builtin_amdgcn_ds_bpermute(4 * row, o_slot[rb]);
+            if (32 * rb + row < o_len)
+              *reinterpret_cast<floatx4*>(head_base + static_cast<int64_t>(slot) * p.n_q_heads * (kD + kPartialPad) + 64 * h2) = piece;
+          }
+        }
+        if (half == 0 && o_valid[rb]) {
+          float* part = p.partial + (static_cast<int64_t>(o_slot[rb]) * p.n_q_heads + o_head[rb]) * (kD + kPartialPad);
+          part[kD] = seen[rb] ? m_run[rb] : -1.0e30f;
+          part[kD + 1] = l_tot;
+        }
+      }
+    } else if (!PERSIST && gridDim.z > 1) {
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
         const float l_tot = half_swap_sum(l_run[rb]);
         if (!o_valid[rb]) continue;
-        float* part = GATHER ? p.partial + (static_cast<int64_t>(o_slot[rb]) * p.n_q_heads + o_head[rb]) * (kD + kPartialPad)
-                             : p.partial + ((static_cast<int64_t>(o_tok[rb]) * p.n_q_heads + o_head[rb]) * gridDim.z + blockIdx.z) *
-                                               (kD + kPartialPad);
+        float* part = p.partial + ((static_cast<int64_t>(o_tok[rb]) * p.n_q_heads + o_head[rb]) * gridDim.z + blockIdx.z) *
+                                      (kD + kPartialPad);
 #pragma unroll
         for (int ob = 0; ob < kD / 32; ++ob)
 #pragma unroll

@@ -243,6 +243,44 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
     int64_t chunk = sel->n_split > 0 ? (max_tiles + sel->n_split - 1) / sel->n_split
                                      : std::min<int64_t>(32, (tile_batches + run_slots - 1) / run_slots);
     chunk = std::max<int64_t>(1, chunk);
+    if (sel->n_split == 0) {
+      // Steps that will run their pool items as a contraction (64 queries per wave, one persistent
+      // workgroup per compute unit and KV head: mx_rec below) are bound by arithmetic, and what
+      // counts is how evenly whole records fill the workers: with W workers per KV head (8 KV heads
+      // assumed, as above) a step takes ceil(records / W) rounds of one record each.  Among the run
+      // lengths of 12..64 tiles take the one with the smallest estimate rounds x (tiles of a run x
+      // cycles per tile + cycles per record), the longer run on a tie (fewer partial states to merge).
+      double rows = 0.0, used = 0.0;
+      for (int32_t s = 0; s <= G; ++s) {
+        const int64_t t = L->gm_seg_ptr[s + 1] - L->gm_seg_ptr[s];
+        const int64_t n_u = static_cast<int64_t>(users[s].size());
+        if (n_u == 0 || t == 0) continue;
+        rows += 64.0 * static_cast<double>(t) * static_cast<double>((n_u + 63) / 64);
+        used += static_cast<double>(t) * static_cast<double>(n_u);
+      }
+      if (rows > 0.0 && used / rows >= kMatrixRowFill) {
+        constexpr double kCyclesPerTile = 3200.0, kCyclesPerRecord = 13000.0;
+        const int64_t workers = std::max<int64_t>(1, L->compute_units / 8);
+        double best = 0.0;
+        for (int64_t c = 12; c <= 64; ++c) {
+          int64_t records = 0;
+          double longest = 0.0;
+          for (int32_t s = 0; s <= G; ++s) {
+            const int64_t t = L->gm_seg_ptr[s + 1] - L->gm_seg_ptr[s];
+            const int64_t n_u = static_cast<int64_t>(users[s].size());
+            if (n_u == 0 || t == 0) continue;
+            const int64_t n_runs = (t + c - 1) / c;
+            records += n_runs * ((n_u + 63) / 64);
+            longest = std::max(longest, static_cast<double>((t + n_runs - 1) / n_runs));
+          }
+          const double est = static_cast<double>((records + workers - 1) / workers) * (longest * kCyclesPerTile + kCyclesPerRecord);
+          if (best == 0.0 || est <= best) {
+            best = est;
+            chunk = c;
+          }
+        }
+      }
+    }
     L->gm_chunk_tiles = static_cast<int32_t>(chunk);
     // displacement of segment s for user u, as in list_shift but without a tile offset
     std::vector<int32_t> seg_shift(static_cast<size_t>(B) * (G + 1), 0);

@@ -222,19 +222,19 @@ def test_list_blocks_of_destroyed_layouts_are_recycled_and_the_pool_stays_bounde
 
 
 def test_default_decode_chunk_uses_the_devices_compute_unit_count():
+    from test_layout_host import expected_decode_chunk
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     pc = synth.make_pool_case("chunkdev", 12, dtype="bf16", n_q_heads=2, n_kv_heads=1, head_dim=128, sink_len=64,
                               pool_tokens=60000, demo_len_range=(200, 600), n_groups=6).pool
-    nq = 40
-    cu = np.arange(nq + 1, dtype=np.int32)
-    sel_ptr = (np.arange(nq + 1) * pc.n_groups).astype(np.int32)
-    sel_idx = np.tile(np.arange(pc.n_groups, dtype=np.int32), nq)
-    lay = B.dbsa_layout_build(pc.sink_len, pc.demo_offsets, pc.group_demo_offsets, cu_qlens=cu, sel_ptr=sel_ptr,
-                              sel_idx=sel_idx, n_split=0, block_m=64, block_n=64)
-    got = lay.export_decode_groups(pc.n_groups, nq)
-    batches = int(np.diff(got["seg_ptr"]).sum()) * ((nq + 31) // 32)
-    run_slots = max(1, cus * 6 // 8 * 3 // 4)
-    assert got["chunk_tiles"] == max(1, min(32, -(-batches // run_slots)))
+    for nq in (20, 100):
+        cu = np.arange(nq + 1, dtype=np.int32)
+        sel_ptr = (np.arange(nq + 1) * pc.n_groups).astype(np.int32)
+        sel_idx = np.tile(np.arange(pc.n_groups, dtype=np.int32), nq)
+        lay = B.dbsa_layout_build(pc.sink_len, pc.demo_offsets, pc.group_demo_offsets, cu_qlens=cu, sel_ptr=sel_ptr,
+                                  sel_idx=sel_idx, n_split=0, block_m=64, block_n=64)
+        got = lay.export_decode_groups(pc.n_groups, nq)
+        tiles = np.diff(got["seg_ptr"]).tolist()
+        assert got["chunk_tiles"] == expected_decode_chunk(tiles, [nq] * len(tiles), cus)
 
 
 @pytest.mark.parametrize("n_queries,n_select,groups", [(70, 2, 3), (130, 3, 3), (64, 2, 2), (200, 4, 5)])

@@ -351,12 +351,15 @@ def test_group_major_schedule_batches_users_and_defaults_to_a_bounded_chunk():
                                     got["chunk_tiles"])
     for key in ("seg_ptr", "seg_ent", "items", "qrefs", "slot_ptr"):
         assert np.array_equal(got[key], want[key]), key
-    assert 1 <= got["chunk_tiles"] <= 32
-    assert sorted(got["items"][:, 3].tolist()) == [8, 8, 8, 32, 32, 32]  # the sink tile and the two tiles of group 1
+    assert 1 <= got["chunk_tiles"] <= 64
+    # 40 of 64 rows filled: the group's two tiles stay one run (see expected_decode_chunk); the sink tile is another
+    assert sorted(got["items"][:, 3].tolist()) == [8, 8, 32, 32]
+    assert sorted(got["items"][:, 1].tolist()) == [1, 1, 2, 2]
     slots = np.sort(got["qrefs"][:, 1])
     own = got["slot_ptr"][1:] - 1
     assert np.array_equal(np.sort(np.concatenate([slots, own])), np.arange(got["slot_ptr"][-1]))
-    assert lay.workspace_bytes(4, 64) == int(got["slot_ptr"][-1]) * 4 * 68 * 4
+    # the larger of the decode step's partial states and the split prefill's (up to 4 runs per prompt token)
+    assert lay.workspace_bytes(4, 64) == max(int(got["slot_ptr"][-1]), 4 * nq) * 4 * 68 * 4
 
 
 def test_rotary_calls_reject_bad_arguments_before_touching_the_device():
@@ -395,30 +398,51 @@ def test_rotation_ids_known_to_the_host_must_lie_inside_the_table():
         B.DBSA_ERR_INVALID_ARG                                                                               # no 32-bit wrap
 
 
+def expected_decode_chunk(tiles, users, compute_units):
+    """The default run length of the decode schedule, restated: tiles[s] / users[s] = tiles of segment s and
+    queries that use it (segments without users or tiles left out)."""
+    run_slots = max(1, compute_units * 6 // 8 * 3 // 4)
+    batches = sum(t * -(-u // 32) for t, u in zip(tiles, users))
+    chunk = max(1, min(32, -(-batches // run_slots)))
+    rows = sum(64.0 * t * -(-u // 64) for t, u in zip(tiles, users))
+    used = sum(float(t) * u for t, u in zip(tiles, users))
+    if rows > 0 and used / rows >= 0.55:
+        # contraction-eligible: fewest rounds of whole records over compute_units / 8 workers per KV head
+        workers = max(1, compute_units // 8)
+        best = 0.0
+        for c in range(12, 65):
+            records = sum(-(-t // c) * -(-u // 64) for t, u in zip(tiles, users))
+            longest = max(float(-(-t // -(-t // c))) for t in tiles)
+            est = float(-(-records // workers)) * (longest * 3200.0 + 13000.0)
+            if best == 0.0 or est <= best:
+                best, chunk = est, c
+    return chunk
+
+
 def test_default_decode_chunk_follows_the_compute_unit_count():
-    """A layout built without a device is sized for 256 compute units: runs of pool tiles are cut so that
-    about 144 single-wave workgroups per KV head (six per compute unit over eight KV heads, three
-    quarters of them for pool runs) cover the step, and never longer than 32 tiles."""
+    """A layout built without a device is sized for 256 compute units.  Few queries per group: runs of pool
+    tiles are cut so that about 144 single-wave workgroups per KV head (six per compute unit over eight KV
+    heads, three quarters of them for pool runs) cover the step, never longer than 32 tiles.  Most of 64 rows
+    filled: the run length that lets whole records fill 32 workers per KV head in the fewest rounds."""
     pc = synth.make_pool_case("chunkpool", 11, dtype="bf16", n_q_heads=2, n_kv_heads=1, head_dim=16, sink_len=64,
                               pool_tokens=60000, demo_len_range=(200, 600), n_groups=6).pool
-    run_slots = 256 * 6 // 8 * 3 // 4
-    assert run_slots == 144
+    assert 256 * 6 // 8 * 3 // 4 == 144
     seen = set()
-    for nq in (1, 8, 40, 100, 200):
+    for nq in (1, 8, 20, 34, 40, 100, 200):
         cu = np.arange(nq + 1, dtype=np.int32)
         sel_ptr = (np.arange(nq + 1) * pc.n_groups).astype(np.int32)
         sel_idx = np.tile(np.arange(pc.n_groups, dtype=np.int32), nq)
         lay = B.dbsa_layout_build(pc.sink_len, pc.demo_offsets, pc.group_demo_offsets, cu_qlens=cu, sel_ptr=sel_ptr,
                                   sel_idx=sel_idx, n_split=0, block_m=64, block_n=64, host_only=True)
         got = lay.export_decode_groups(pc.n_groups, nq)
-        tiles = np.diff(got["seg_ptr"])
-        batches = int(tiles.sum()) * ((nq + 31) // 32)       # every segment serves all nq queries
-        want = max(1, min(32, -(-batches // run_slots)))
+        tiles = np.diff(got["seg_ptr"]).tolist()
+        want = expected_decode_chunk(tiles, [nq] * len(tiles), 256)     # every segment serves all nq queries
         assert got["chunk_tiles"] == want, (nq, got["chunk_tiles"], want)
         seen.add(want)
-        # no run is longer than the chunk, and a segment's runs differ by at most one tile
-        assert got["items"][:, 1].max() <= want
-    assert len(seen) >= 3 and 32 in seen
+        assert got["items"][:, 1].max() <= want                         # no run is longer than the chunk
+        _, fill = lay.export_matrix_records()
+        assert (fill >= 0.55) == (nq in (40, 100, 200)), (nq, fill)
+    assert len(seen) >= 3
 
 
 @pytest.mark.parametrize("n_classes", [1, 7, 64, 512])
