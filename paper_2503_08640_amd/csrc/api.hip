@@ -939,14 +939,15 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
       // to outweigh the barrier per half tile (measured over 16-256 queries at 10-100 % retrieval: 2
       // waves pay from ~1.5 walks per key on, 4 from ~2.3).
       p.decode_waves = pick_decode_waves(L, r);
-      // With four query heads per KV head and groups that serve many queries, the pool items run as a
-      // contraction: 64 queries per wave, the four heads as the four waves of a workgroup, one
-      // workgroup per compute unit walking a balanced share of the records (kernels.hpp:
-      // launch_decode_matrix_items).  Worth it once enough of the 64 rows carry a query.
-      if (r == 4 && !rope_table && L->mx_row_fill >= kMatrixRowFill) {
+      // With query heads in fours per KV head and groups that serve many queries, the pool items run
+      // as a contraction: 64 queries per wave, four heads of a KV head as the four waves of a
+      // workgroup, one workgroup per compute unit walking a balanced share of the records
+      // (kernels.hpp: launch_decode_matrix_items).  Worth it once enough of the 64 rows carry a query.
+      if (r % 4 == 0 && !rope_table && L->mx_row_fill >= kMatrixRowFill) {
         // one workgroup per compute unit, or per record where there are fewer
+        const int32_t head_blocks = n_q_heads / 4;
         const int32_t classes = static_cast<int32_t>(
-            std::min<int64_t>(L->compute_units / n_kv_heads, static_cast<int64_t>(L->mx_rec.size() / 4)));
+            std::min<int64_t>(L->compute_units / head_blocks, static_cast<int64_t>(L->mx_rec.size() / 4)));
         if (classes >= 1 && ensure_matrix_schedule(L, classes, s)) {
           p.decode_matrix = 1;
           p.decode_waves = 1;

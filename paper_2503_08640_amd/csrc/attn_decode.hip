@@ -957,14 +957,14 @@ hipError_t launch_decode_group(const AttnParams& p_in, hipStream_t stream) {
   }
   hipError_t e;
   if (p.decode_matrix) {
-    // Many queries per group: the pool items as a contraction (64 query rows per wave, the four query
-    // heads of a KV head as the four waves of a workgroup, see attn_prefill64.hip), every query's own
-    // cache in the single-wave kernel, then the same merge.  The partial states land in the same slots.
+    // Many queries per group: the pool items as a contraction (64 query rows per wave, four query heads
+    // of a KV head as the four waves of a workgroup, see attn_prefill64.hip), every query's own cache
+    // in the single-wave kernel, then the same merge.  The partial states land in the same slots.
     AttnParams g = p;
     g.sched_rec = p.mx_sched_rec;
     g.sched_ptr = p.mx_sched_ptr;
     g.sched_classes = p.mx_classes;
-    g.n_head_blocks = p.n_kv_heads;
+    g.n_head_blocks = p.n_q_heads / 4;
     g.list_ent = p.mx_ent;
     g.heads_per_block = 4;
     g.block_m = 64;

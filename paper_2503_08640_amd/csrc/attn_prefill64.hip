@@ -113,8 +113,8 @@ struct StepCfg {
 // refs[i][0], and instead of a normalised output the kernel leaves the row's partial softmax state
 // (unnormalised accumulators, running maximum, row sum) in partial[slot][head].  This is how a
 // decode step with many queries per group runs as a contraction: a record is a run of a group's
-// tiles with up to 64 of the queries that selected the group, the four waves are the four query
-// heads of one KV head, and the merge pass of the decode step combines the slots.
+// tiles with up to 64 of the queries that selected the group, the four waves are four query heads
+// of one KV head, and the merge pass of the decode step combines the slots.
 template <int NW, int SL, bool SELF, bool PERSIST, bool GATHER = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_prefill64_kernel(AttnParams p) {
   static_assert(!GATHER || (PERSIST && !SELF), "gathered rows come with a schedule and pool tiles only");
@@ -864,10 +864,10 @@ hipError_t launch_prefill64(const AttnParams& p, hipStream_t stream) {
 
 // The pool items of a decode step as a contraction: p carries the schedule of the layout's matrix
 // records (sched_*), the segments' tile entries as list_ent, the flat references as gather_refs and
-// the decode step's q, pools and partial buffer; four query heads per KV head, 64-row tiles.
+// the decode step's q, pools and partial buffer; query heads in fours per KV head, 64-row tiles.
 hipError_t launch_decode_matrix_items(const AttnParams& p, hipStream_t stream) {
   if (!p.sched_rec || !p.sched_ptr || !p.gather_refs || !p.partial || p.sched_classes < 1) return hipErrorInvalidValue;
-  if (p.heads_per_block != 4 || p.block_m != 64 || p.n_q_heads != 4 * p.n_kv_heads || p.n_head_blocks != p.n_kv_heads)
+  if (p.heads_per_block != 4 || p.block_m != 64 || p.n_q_heads % (4 * p.n_kv_heads) != 0 || p.n_head_blocks != p.n_q_heads / 4)
     return hipErrorInvalidValue;
   return launch_cfg64<4, 2, false, true, true>(p, stream);
 }

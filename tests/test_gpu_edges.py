@@ -237,12 +237,13 @@ def test_default_decode_chunk_uses_the_devices_compute_unit_count():
         assert got["chunk_tiles"] == expected_decode_chunk(tiles, [nq] * len(tiles), cus)
 
 
-@pytest.mark.parametrize("n_queries,n_select,groups", [(70, 2, 3), (130, 3, 3), (64, 2, 2), (200, 4, 5)])
-def test_decode_with_many_queries_per_group_as_a_contraction(n_queries, n_select, groups):
-    """Four query heads per KV head and groups that each serve dozens of queries: the step runs its pool items
+@pytest.mark.parametrize("n_queries,n_select,groups,hq,hkv", [(70, 2, 3, 8, 2), (130, 3, 3, 8, 2), (64, 2, 2, 8, 2),
+                                                              (200, 4, 5, 8, 2), (100, 2, 3, 16, 2), (100, 3, 3, 8, 1)])
+def test_decode_with_many_queries_per_group_as_a_contraction(n_queries, n_select, groups, hq, hkv):
+    """Four (or eight) query heads per KV head and groups that each serve dozens of queries: the step runs its pool items
     with 64 queries per wave (batches of 64 + a ragged rest) and the queries' own caches in the single-wave
     kernel.  Every query, two steps (own caches of 10 and 11 keys ... and longer), against the oracle."""
-    pc = small_pool_case("mxpool", 3500 + n_queries, hq=8, hkv=2, pool_tokens=2600, groups=groups, lens=(30, 140), sigma=0.5)
+    pc = small_pool_case("mxpool", 3500 + n_queries + hq, hq=hq, hkv=hkv, pool_tokens=2600, groups=groups, lens=(30, 140), sigma=0.5)
     rng = np.random.default_rng(n_queries)
     q_len = rng.integers(1, 80, size=n_queries).tolist()
     qc = synth.make_query_case("mxq", 3501, pc, n_queries=n_queries, q_len=q_len, n_select=n_select, n_decode=2)
