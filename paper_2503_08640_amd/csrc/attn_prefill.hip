@@ -33,7 +33,6 @@
 //     row of the wave outgrows it, which is rare once a few tiles have been seen.
 #include <atomic>
 #include <cstdint>
-#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
