@@ -261,3 +261,56 @@ def test_decode_with_many_queries_per_group_as_a_contraction(n_queries, n_select
     a = B.dbsa_decode_attn(lay2, to_dev(qc.dec_q[0]), kc, vc, sl, kp, vp, pc.scale)
     b = B.dbsa_decode_attn(lay3, to_dev(qc.dec_q[0]), kc, vc, sl, kp, vp, pc.scale)
     assert torch.equal(a, b)
+
+
+# ---------------------------------------------------------------------------
+# persistent prefill launches on ragged mid-size inputs (the full-size configs have regular shapes)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("hq,hkv,block_m,window", [(8, 2, 32, 0), (8, 2, 64, 0), (8, 2, 64, 2), (4, 4, 128, 0)])
+def test_persistent_preencode_on_a_pool_of_many_short_groups(hq, hkv, block_m, window):
+    """Enough Q tiles for the launch to run persistently (at least two per workgroup place), groups of a few
+    hundred tokens with ragged ends: lists of 1 to ~10 tiles, short last Q tiles, a new owner every few records.
+    Sampled rows (all of the sink, the first and last rows of many groups, random others) against the oracle."""
+    tokens = {32: 18000, 64: 18000, 128: 34000}[block_m]
+    pc = synth.make_pool_case("persist", 3600 + block_m + hq + window, dtype="bf16", n_q_heads=hq, n_kv_heads=hkv, head_dim=128,
+                              sink_len=37, pool_tokens=tokens, demo_len_range=(20, 150), n_groups=45, k_channel_sigma=0.5,
+                              prev_window=window)
+    p = pc.pool
+    lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, window, block_m=block_m, block_n=64)
+    tab, _, _ = lay.export()
+    heads_per_block = {(8, 2, 32): 4, (8, 2, 64): 4, (4, 4, 128): 1}[(hq, hkv, block_m)]
+    places = torch.cuda.get_device_properties(0).multi_processor_count * (1 if heads_per_block * block_m // 32 == 8 else 2)
+    classes = places // (hq // heads_per_block)
+    assert tab.shape[0] >= 2 * classes, "this case is meant to launch persistently"
+    o = B.dbsa_preencode_attn(lay, to_dev(pc.q), to_dev(pc.k), to_dev(pc.v), pc.scale)
+    rng = np.random.default_rng(5)
+    gb = p.group_token_bounds()
+    rows = set(range(p.sink_len)) | set(rng.choice(p.n_tokens, size=700, replace=False).tolist())
+    for g in range(0, p.n_groups, 3):
+        rows |= set(range(int(gb[g]), int(gb[g]) + 3)) | set(range(int(gb[g + 1]) - 3, int(gb[g + 1])))
+    rows = np.array(sorted(rows))
+    ref = orc.preencode_attn(synth.as_f64(pc.q), synth.as_f64(pc.k), synth.as_f64(pc.v), p.sink_len, p.demo_offsets,
+                             p.group_demo_offsets, pc.scale, window, rows=rows)
+    assert_close(to_f64(o)[rows], ref, f"persistent pre-encode bm={block_m} Hq={hq} Hkv={hkv} w={window}")
+    o2 = B.dbsa_preencode_attn(lay, to_dev(pc.q), to_dev(pc.k), to_dev(pc.v), pc.scale)
+    assert torch.equal(o, o2)
+
+
+def test_persistent_query_prefill_with_hundreds_of_ragged_queries():
+    """700 queries of 1 to 64 tokens with selections of 0 to 4 groups (some empty, some all): one Q tile or two per
+    query, more than two Q tiles per workgroup place, so the launch is persistent and its records end in tiles of
+    the queries' own keys.  Every 7th query against the oracle."""
+    pc = small_pool_case("persistq", 3700, hq=8, hkv=2, pool_tokens=3000, groups=4, lens=(30, 200), sigma=0.5)
+    rng = np.random.default_rng(11)
+    n_q = 700
+    q_len = rng.integers(1, 65, size=n_q).tolist()
+    sels = [sorted(rng.choice(4, size=int(rng.integers(0, 5)), replace=False).tolist()) for _ in range(n_q)]
+    qc = synth.make_query_case("persistqq", 3701, pc, n_queries=n_q, q_len=q_len, selections=sels)
+    lay, kp, vp = _query_setup(pc, qc, 32, 0)
+    tab, _, _ = lay.export()
+    assert tab.shape[0] >= 2 * (2 * torch.cuda.get_device_properties(0).multi_processor_count // 2)
+    queries = list(range(0, n_q, 7))
+    oq = B.dbsa_query_attn(lay, to_dev(qc.q), to_dev(qc.k), to_dev(qc.v), kp, vp, pc.scale, workspace=False)
+    ref = _oracle_query(pc, qc, queries=queries)
+    rows = np.concatenate([np.arange(qc.cu_qlens[u], qc.cu_qlens[u + 1]) for u in queries])
+    assert_close(to_f64(oq)[rows], ref[rows], "persistent query prefill, 700 ragged queries")
