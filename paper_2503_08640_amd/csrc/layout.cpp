@@ -413,11 +413,29 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
   // launch order: owner by owner (a group at pre-encoding, a query at the query stage), the
   // longest list of an owner first.  Q tiles of one owner walk the same KV, so keeping them
   // adjacent keeps that KV in the L2 of the XCD that runs them.
+  // At the query stage the owners themselves are put in the order of their selections (the lists
+  // of selected groups compared word by word, then the query index): queries that start with the
+  // same groups then run side by side and walk the same keys at about the same time, which is what
+  // lets many queries with small selections share the L2 of the XCD that serves a KV head.
   const int64_t nt = L->n_qtiles();
+  std::vector<int32_t> owner_rank;
+  if (L->query_stage && sel) {
+    std::vector<int32_t> by_sel(static_cast<size_t>(sel->n_queries));
+    std::iota(by_sel.begin(), by_sel.end(), 0);
+    std::stable_sort(by_sel.begin(), by_sel.end(), [&](int32_t a, int32_t b) {
+      return std::lexicographical_compare(sel->sel_idx + sel->sel_ptr[a], sel->sel_idx + sel->sel_ptr[a + 1],
+                                          sel->sel_idx + sel->sel_ptr[b], sel->sel_idx + sel->sel_ptr[b + 1]);
+    });
+    owner_rank.resize(by_sel.size());
+    for (size_t i = 0; i < by_sel.size(); ++i) owner_rank[static_cast<size_t>(by_sel[i])] = static_cast<int32_t>(i);
+  }
+  auto rank_of = [&](int32_t owner) {
+    return owner >= 0 && static_cast<size_t>(owner) < owner_rank.size() ? owner_rank[static_cast<size_t>(owner)] : owner;
+  };
   L->order.resize(nt);
   std::iota(L->order.begin(), L->order.end(), 0);
   std::stable_sort(L->order.begin(), L->order.end(), [&](int32_t a, int32_t b) {
-    const int32_t oa = L->qtile_tab[4 * a + 2], ob = L->qtile_tab[4 * b + 2];
+    const int32_t oa = rank_of(L->qtile_tab[4 * a + 2]), ob = rank_of(L->qtile_tab[4 * b + 2]);
     if (oa != ob) return oa < ob;
     return (L->list_ptr[a + 1] - L->list_ptr[a]) > (L->list_ptr[b + 1] - L->list_ptr[b]);
   });

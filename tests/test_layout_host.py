@@ -504,3 +504,28 @@ def test_matrix_records_cover_every_item_query_pair_once(n_queries, n_select):
     assert abs(fill - want_fill) < 1e-6
     # a record is one item or two consecutive ones of the same run
     assert len(rec) >= (len(items) + 1) // 2
+
+
+def test_query_stage_launch_order_groups_queries_by_their_selections():
+    """The order is a permutation; an owner's tiles stay together, longest list first; owners follow each other in
+    the order of their selection lists (word by word, ties by query index)."""
+    pc = synth.make_pool_case("ordpool", 31, dtype="bf16", n_q_heads=2, n_kv_heads=1, head_dim=16, sink_len=10,
+                              pool_tokens=3000, demo_len_range=(30, 140), n_groups=6).pool
+    rng = np.random.default_rng(3)
+    n_q = 40
+    sels = [sorted(rng.choice(6, size=int(rng.integers(0, 4)), replace=False).tolist()) for _ in range(n_q)]
+    sel_ptr = np.concatenate([[0], np.cumsum([len(s) for s in sels])]).astype(np.int32)
+    sel_idx = np.array([g for s in sels for g in s], dtype=np.int32)
+    q_len = rng.integers(1, 150, size=n_q)
+    cu = np.concatenate([[0], np.cumsum(q_len)]).astype(np.int32)
+    lay = B.dbsa_layout_build(pc.sink_len, pc.demo_offsets, pc.group_demo_offsets, cu_qlens=cu, sel_ptr=sel_ptr,
+                              sel_idx=sel_idx, n_split=0, block_m=64, block_n=64, host_only=True)
+    order = lay.export_order()
+    tab, ptr, _ = lay.export()
+    assert sorted(order.tolist()) == list(range(len(tab)))
+    owners, lens = tab[order, 2], np.diff(ptr)[order]
+    firsts = [int(o) for i, o in enumerate(owners) if i == 0 or owners[i - 1] != o]
+    assert sorted(firsts) == list(range(n_q))                                   # every owner is one contiguous stretch
+    assert firsts == sorted(range(n_q), key=lambda u: (sels[u], u))
+    same = owners[:-1] == owners[1:]
+    assert np.all(lens[:-1][same] >= lens[1:][same])
