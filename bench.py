@@ -121,12 +121,17 @@ def extra_setting(torch, B, pc, qc, workload: str, bm_pre: int, bm_query: int, i
     # adding the last group to a pool that already holds the others (Sec. 1: constant cost per addition)
     lay_app = B.dbsa_layout_build_append(p.sink_len, p.demo_offsets, p.group_demo_offsets, w, p.n_groups - 1,
                                          block_m=bm_pre, block_n=64)
+    # the same pre-encode call on head-major storage ([heads, tokens, D] behind the same [tokens, heads, D] strides:
+    # how caches are often kept); a 64-key tile then spans 16 KiB of addresses instead of 64 x heads x 256 bytes
+    qh, kh, vh = (t.permute(1, 0, 2).contiguous().permute(1, 0, 2) for t in (q, k, v))
+    oh = torch.empty_like(qh)
     calls = (lambda: B.dbsa_preencode_attn(lay, q, k, v, pc.scale, out=o),
              lambda: B.dbsa_query_attn(layq, qs, ks, vs, k, v, pc.scale, out=oq, workspace=ws),
              lambda: B.dbsa_decode_attn(layq, dq[0], kc, vc, self_len, k, v, pc.scale, out=od, workspace=ws),
-             lambda: B.dbsa_preencode_attn(lay_app, q, k, v, pc.scale, out=o))
+             lambda: B.dbsa_preencode_attn(lay_app, q, k, v, pc.scale, out=o),
+             lambda: B.dbsa_preencode_attn(lay, qh, kh, vh, pc.scale, out=oh))
     # medians over single launches (the inputs above were drawn on the host: the warm-up lets the clocks come back up)
-    st = [stats(launch_samples(torch, fn, max(n, MIN_STAGE_LAUNCHES))) for fn, n in zip(calls, (iters, 4 * iters, 20 * iters, 4 * iters))]
+    st = [stats(launch_samples(torch, fn, max(n, MIN_STAGE_LAUNCHES))) for fn, n in zip(calls, (iters, 4 * iters, 20 * iters, 4 * iters, iters))]
     ms = [x["median_ms"] for x in st]
     keys = selected_keys(p, qc)
     flops_pre = 4.0 * d * visible_pairs_pre(p, w) * hq
@@ -137,11 +142,12 @@ def extra_setting(torch, B, pc, qc, workload: str, bm_pre: int, bm_query: int, i
         "pool_tokens": int(p.n_tokens), "sink_len": int(p.sink_len), "n_groups": int(p.n_groups), "prev_window": w,
         "preencode_ms": ms[0], "preencode_useful_tflops": flops_pre / ms[0] / 1e9,
         "preencode_frac_of_mfma_peak": flops_pre / ms[0] / 1e9 / PEAK_BF16_TFLOPS,
+        "preencode_head_major_ms": ms[4], "preencode_head_major_frac_of_mfma_peak": flops_pre / ms[4] / 1e9 / PEAK_BF16_TFLOPS,
         "query_prefill_ms": ms[1], "query_prefill_useful_tflops": flops_query / ms[1] / 1e9,
         "query_prefill_frac_of_mfma_peak": flops_query / ms[1] / 1e9 / PEAK_BF16_TFLOPS,
         "decode_step_ms": ms[2], "decode_per_query_gbs": bytes_dec / ms[2] / 1e6,
         "append_last_group_ms": ms[3],
-        "timing": "median of single launches", "launch_stats": dict(zip(("preencode", "query_prefill", "decode_step", "append"), st)),
+        "timing": "median of single launches", "launch_stats": dict(zip(("preencode", "query_prefill", "decode_step", "append", "preencode_head_major"), st)),
     }
 
 
