@@ -533,8 +533,7 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
     // chip holds (one of four waves or two of two per compute unit), each walking a balanced share
     // of the Q tiles of its head block.
     const int row_blocks = p.heads_per_block * (L->block_m / 32);
-    if (d == 128 && max_stride < (int64_t{1} << 24) && !rope_table && p.q_split == 1 &&
-        (row_blocks == 4 || row_blocks == 8)) {
+    if (d == 128 && max_stride < (int64_t{1} << 24) && p.q_split == 1 && (row_blocks == 4 || row_blocks == 8)) {
       const int64_t head_blocks = hq / p.heads_per_block;
       const int64_t places = static_cast<int64_t>(L->compute_units) * (row_blocks == 8 ? 1 : 2);
       const int64_t classes = places / head_blocks;

@@ -542,9 +542,9 @@ hipError_t launch_stage(const AttnParams& p, hipStream_t stream) {
 hipError_t launch_prefill_pipelined(const AttnParams& p, hipStream_t stream) {
   if (p.n_qtiles == 0) return hipSuccess;
   const int row_blocks = p.heads_per_block * (p.block_m / 32);
-  // four or eight row blocks, inputs at their final positions: the kernel with 64 rows per wave, one
-  // wave per SIMD (persistent if the call carries a schedule, else one workgroup per Q tile and run)
-  if (!p.rope_table && (row_blocks == 4 || row_blocks == 8)) {
+  // four or eight row blocks: the kernel with 64 rows per wave, one wave per SIMD (persistent if
+  // the call carries a schedule, else one workgroup per Q tile and run)
+  if (row_blocks == 4 || row_blocks == 8) {
     hipError_t e = launch_prefill64(p, stream);
     const int n_split = p.q_split > 1 ? p.q_split : 1;
     if (e != hipSuccess || n_split == 1) return e;

@@ -115,9 +115,16 @@ struct StepCfg {
 // decode step with many queries per group runs as a contraction: a record is a run of a group's
 // tiles with up to 64 of the queries that selected the group, the four waves are four query heads
 // of one KV head, and the merge pass of the decode step combines the slots.
-template <int NW, int SL, bool SELF, bool PERSIST, bool GATHER = false>
+//
+// ROPE (query prefill only): Q is un-rotated; the keys carry the rotation of the id they were encoded
+// with.  A row is rotated at the id list_shift[e] + (its index inside the Q tile) before it meets
+// the keys of list entry e (Sec. 2.2: the retrieved caches get new in-order positions; rotating the
+// row instead of the keys lets all queries read the same key bytes).  Entries of one segment share
+// the shift, so the fragments are rebuilt only where it changes, from the rows in memory.
+template <int NW, int SL, bool SELF, bool PERSIST, bool GATHER = false, bool ROPE = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_prefill64_kernel(AttnParams p) {
   static_assert(!GATHER || (PERSIST && !SELF), "gathered rows come with a schedule and pool tiles only");
+  static_assert(!ROPE || (SELF && !GATHER), "rows are re-positioned at the query prefill only");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   constexpr int kBlocksPerWave = 16 / NW;  // 1-KiB load blocks of one operand per wave
   constexpr int KS = 2 + SL, VS = 1 + SL;  // LDS stages of K and of V
@@ -159,6 +166,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
   }
   const const_words sched = (const_words)(reinterpret_cast<uintptr_t>(p.sched_rec));
   const const_words all_ent = (const_words)(reinterpret_cast<uintptr_t>(p.list_ent));
+  const const_words all_shift = (const_words)(reinterpret_cast<uintptr_t>(p.list_shift));
   const int hk = (hb * p.heads_per_block) / r;
 
   const uint64_t kpool = uniform64(reinterpret_cast<uint64_t>(static_cast<const __bf16*>(p.k_pool.ptr) + hk * p.k_pool.stride_head));
@@ -266,6 +274,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
   // its last entry: every period loads one K and one V tile, the last ones into stages nobody
   // reads any more, so that the waits can count on a fixed number of loads in flight.
   const_words f_ent = all_ent + 2 * static_cast<int64_t>(e0);
+  const_words f_sh = all_shift + (ROPE ? static_cast<int64_t>(e0) : 0);  // ROPE: the entries' rotation ids, in step with f_ent
   int f_left = n_tiles, f_k = rec_k;
   int nx_e0 = 0, nx_n = 0;  // PERSIST: list of record f_k + 1 (requested when the stream entered record f_k)
   if constexpr (PERSIST) {
@@ -274,12 +283,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
       nx_n = sched[4 * (f_k + 1) + 3];
     }
   }
-  int in_w0 = 0, in_w1 = 0;  // the entry requested last
+  int in_w0 = 0, in_w1 = 0, in_w2 = 0;  // the entry requested last (ROPE: and its rotation id)
   auto request_entry = [&]() DBSA_INLINE {
     if (__builtin_expect(f_left == 0, 0)) {
       if (PERSIST && f_k + 1 < rec_end) {
         f_k += 1;
         f_ent = all_ent + 2 * static_cast<int64_t>(nx_e0);
+        if constexpr (ROPE) f_sh = all_shift + static_cast<int64_t>(nx_e0);
         f_left = nx_n;
         if (f_k + 1 < rec_end) {
           nx_e0 = sched[4 * (f_k + 1) + 2];
@@ -287,22 +297,28 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
         }
       } else {
         f_ent -= 2;
+        if constexpr (ROPE) f_sh -= 1;
         f_left = 1;
       }
     }
     in_w0 = f_ent[0];
     in_w1 = f_ent[1];
     f_ent += 2;
+    if constexpr (ROPE) {
+      in_w2 = f_sh[0];
+      f_sh += 1;
+    }
     f_left -= 1;
   };
 
   // (rw0, rw1)[i] = words of the entry i tiles ahead of the one whose scores the current period computes
-  int rw0[2 + SL], rw1[2 + SL];
+  int rw0[2 + SL], rw1[2 + SL], rw2[2 + SL];
 #pragma unroll
   for (int i = 0; i < 2 + SL; ++i) {
     request_entry();
     rw0[i] = in_w0;
     rw1[i] = in_w1;
+    rw2[i] = in_w2;
   }
   // K(0 .. SL) and V(0 .. SL-2) of the stream go out now, in the order later periods keep
   // (K(i), V(i-2)); the period of tile j issues K(j+1+SL) and V(j-1+SL)
@@ -367,8 +383,29 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
       }
     valu_result_fence();
   };
+  // ROPE: the fragments of both row blocks from the rows in memory, rotated at shift + row index and
+  // pre-multiplied like scale_q's (rare: once per segment of a list)
+  int cur_shift = 0;
+  auto rotate_q = [&](int shift) DBSA_INLINE {
+    cur_shift = shift;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(row_tok[rb]) * p.q.stride_tok +
+                         static_cast<int64_t>(head[rb]) * p.q.stride_head + 8 * half;
+      const int id = min(max(shift + row_local[rb], 0), p.rope_n_pos - 1);
+      const float* rot = p.rope_table + static_cast<int64_t>(id) * kD + 16 * half;
+      bf16x8 frag[kD / 16];
+      load_query_fragments<true>(qp, rot, c2, frag);
+#pragma unroll
+      for (int c = 0; c < kD / 16; ++c) {
+        qf[rb][c] = __builtin_bit_cast(intx4, frag[c]);
+        asm volatile("" : "+a"(qf[rb][c]));
+      }
+    }
+    valu_result_fence();
+  };
   place_rows();
-  load_q();
+  if constexpr (!ROPE) load_q();
 
   floatx16 o[2][kD / 32];
   floatx16 neg_m[2];                     // minus the running maximum in every element: C operand of a score block's first product
@@ -612,9 +649,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
     for (int i = 0; i < 1 + SL; ++i) {
       rw0[i] = rw0[i + 1];
       rw1[i] = rw1[i + 1];
+      if constexpr (ROPE) rw2[i] = rw2[i + 1];
     }
     rw0[1 + SL] = in_w0;
     rw1[1 + SL] = in_w1;
+    if constexpr (ROPE) rw2[1 + SL] = in_w2;
     k_wr = (k_wr + 1 == KS) ? 0 : k_wr + 1;
     v_wr = (v_wr + 1 == VS) ? 0 : v_wr + 1;
   };
@@ -630,7 +669,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
 
   for (;;) {
     // ---- a Q tile: its rows of Q are in q_raw (requested before the previous tile's epilogue) ----
-    scale_q();
+    if constexpr (ROPE)
+      rotate_q(rw2[0]);
+    else
+      scale_q();
     int nq_start = 0, nq_len = 0, nq_e0 = 0, nq_n = 0;  // PERSIST: the record after this one
     if constexpr (PERSIST) {
       if (rec_k + 1 < rec_end) {
@@ -674,6 +716,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
       period_barrier();
       request_entry();  // before this period's loads: it has returned when the period ends
       const TileRef tq = decode_ref(rw0[0], rw1[0]);
+      if constexpr (ROPE) {
+        // this period computes the scores of an entry of another segment: rebuild Q for it (every matrix
+        // instruction that read the old fragments was issued a period ago)
+        if (__builtin_expect(rw2[0] != cur_shift, 0)) rotate_q(rw2[0]);
+      }
       aim_k();
       step(StepCfg<true, true, true, 0, 0, true, true, 1, true>{}, s_e, s_o, p_o, p_e, tq);
       aim_v();
@@ -703,7 +750,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
       e0 = nq_e0;
       n_tiles = nq_n;
       place_rows();
-      load_q();
+      if constexpr (!ROPE) load_q();
     }
     {
       const TileRef none{0, kBN, false, false};
@@ -822,12 +869,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
   }
 }
 
-template <int NW, int SL, bool SELF, bool PERSIST, bool GATHER = false>
+template <int NW, int SL, bool SELF, bool PERSIST, bool GATHER = false, bool ROPE = false>
 hipError_t launch_cfg64(const AttnParams& p, hipStream_t stream) {
   constexpr int lds_bytes = (3 + 2 * SL) * kTileBytes;
   static std::atomic<bool> attr_set{false};  // setting it twice from two threads is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill64_kernel<NW, SL, SELF, PERSIST, GATHER>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill64_kernel<NW, SL, SELF, PERSIST, GATHER, ROPE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -835,12 +882,17 @@ hipError_t launch_cfg64(const AttnParams& p, hipStream_t stream) {
   const int n_split = p.q_split > 1 ? p.q_split : 1;
   const dim3 grid = PERSIST ? dim3(p.sched_classes * p.n_head_blocks)
                             : dim3(p.n_q_heads / p.heads_per_block, p.n_qtiles, n_split);
-  attn_prefill64_kernel<NW, SL, SELF, PERSIST, GATHER><<<grid, dim3(NW * 64), lds_bytes, stream>>>(p);
+  attn_prefill64_kernel<NW, SL, SELF, PERSIST, GATHER, ROPE><<<grid, dim3(NW * 64), lds_bytes, stream>>>(p);
   return hipGetLastError();
 }
 
 template <int NW, int SL>
 hipError_t launch_stage64(const AttnParams& p, hipStream_t stream) {
+  if (p.rope_table) {
+    if (!p.query_stage || !p.list_shift) return hipErrorInvalidValue;
+    return p.sched_rec ? launch_cfg64<NW, SL, true, true, false, true>(p, stream)
+                       : launch_cfg64<NW, SL, true, false, false, true>(p, stream);
+  }
   if (p.sched_rec)
     return p.query_stage ? launch_cfg64<NW, SL, true, true>(p, stream) : launch_cfg64<NW, SL, false, true>(p, stream);
   return p.query_stage ? launch_cfg64<NW, SL, true, false>(p, stream) : launch_cfg64<NW, SL, false, false>(p, stream);

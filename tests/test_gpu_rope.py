@@ -98,9 +98,12 @@ def test_repositioned_query_and_decode_small(hq, hkv, block_m, base):
 def test_repositioned_decode_with_many_queries_per_group(hq, hkv):
     """40 queries on 3 groups: every group serves several batches of 32 / r queries, so the
     decode step runs the kernel whose waves share an item's tiles (2 or 4 waves per workgroup)."""
+    # (channel scales of sigma 0.35: with 0.5 one of the 16 heads of the third case gets scores beyond +-60,
+    # where rounding the rotated, pre-scaled Q to bf16 alone moves single outputs by up to 2e-2, the whole
+    # tolerance; the kernels agree with each other there to 7e-3)
     pc = synth.make_pool_case("ropemany", 4020 + hq, dtype="bf16", n_q_heads=hq, n_kv_heads=hkv, head_dim=128,
                               sink_len=40, pool_tokens=2500, demo_len_range=(30, 120), n_groups=3,
-                              k_channel_sigma=0.5)
+                              k_channel_sigma=0.35)
     qc = synth.make_query_case("ropemanyq", 4021, pc, n_queries=40, q_len=9, n_select=2, n_decode=2)
     _repositioned_case(pc, qc, 32, 10000.0, decode_steps=range(2), what=f"many queries Hq={hq} Hkv={hkv}")
 
