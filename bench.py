@@ -212,7 +212,7 @@ def config4_sweep(torch, B, pc, k, v, iters: int = 20):
                             "query_stage": affine_fit(mk, [r["query_stage_ms"] for r in rows])},
             # at 100 % retrieval every one of the 128 queries scores the whole pool: a dense contraction
             "roofline_decode_many_queries": {
-                "kernel": "attn_prefill64_kernel<4,2,false,true,true> (pool items as a contraction: 64 queries per wave, rows "
+                "kernel": "attn_prefill64_kernel<4,2,false,true,true,false> (pool items as a contraction: 64 queries per wave, rows "
                           "gathered through the schedule's references) + decode_group_kernel (own caches) + "
                           "decode_group_merge_kernel, 100 % retrieval", "bound": "mfma", "achieved": full["decode_useful_tflops"],
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": full["decode_frac_of_mfma_peak"], "traffic": None,
@@ -488,8 +488,8 @@ def main() -> int:
             "launch_stats": {"preencode": stats(pre_s), "query_prefill": stats(query_s), "decode_step": stats(decode_s)},
         },
         "roofline": {
-            "kernel": "attn_prefill64_kernel<4,2,false,true,false> (pre-encode launch: persistent, four waves of 64 query rows "
-                      "per workgroup, one workgroup per compute unit; the <4,2,true,*,false> instances serve the query prefill)",
+            "kernel": "attn_prefill64_kernel<4,2,false,true,false,false> (pre-encode launch: persistent, four waves of 64 query rows "
+                      "per workgroup, one workgroup per compute unit; the <4,2,true,*,false,*> instances serve the query prefill)",
             "bound": "mfma", "achieved": pre_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": pre_tflops / PEAK_BF16_TFLOPS, "traffic": traffic.get("preencode"),
             "traffic_measured_at": traffic_at,
@@ -498,7 +498,7 @@ def main() -> int:
                             "frac_at_median": flops_pre / stats(pre_s)["median_ms"] / 1e9 / PEAK_BF16_TFLOPS},
         },
         "roofline_query_prefill": {
-            "kernel": "attn_prefill64_kernel<4,2,true,false,false> + prefill_merge_kernel (16 Q tiles x 8 head blocks, lists cut in two)",
+            "kernel": "attn_prefill64_kernel<4,2,true,false,false,false> + prefill_merge_kernel (16 Q tiles x 8 head blocks, lists cut in two)",
             "bound": "mfma", "achieved": flops_query / query_ms / 1e9, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": flops_query / query_ms / 1e9 / PEAK_BF16_TFLOPS, "traffic": traffic.get("query_prefill"),
             "algorithmic": {"useful_tflop_per_launch": flops_query / 1e12, "launch_ms": query_ms,

@@ -8,8 +8,8 @@ import types
 
 from paper_2503_08640_amd import profsum as ps
 
-PRE = "void (anonymous namespace)::attn_prefill64_kernel<4, 2, false, true, false>(AttnParams)"
-QRY = "void (anonymous namespace)::attn_prefill64_kernel<4, 2, true, false, false>(AttnParams)"
+PRE = "void (anonymous namespace)::attn_prefill64_kernel<4, 2, false, true, false, false>(AttnParams)"
+QRY = "void (anonymous namespace)::attn_prefill64_kernel<4, 2, true, false, false, false>(AttnParams)"
 MRG = "void (anonymous namespace)::prefill_merge_kernel(AttnParams, int, int)"
 DEC = "void (anonymous namespace)::decode_group_kernel<false>(AttnParams)"
 DMG = "void (anonymous namespace)::decode_group_merge_kernel(AttnParams)"
@@ -28,7 +28,7 @@ def counter_csv(path, counter, rows):
 
 
 def test_names_and_duration_groups():
-    assert ps.short_name(PRE) == "attn_prefill64_kernel<4,2,false,true,false>"
+    assert ps.short_name(PRE) == "attn_prefill64_kernel<4,2,false,true,false,false>"
     assert ps.short_name(MRG) == "prefill_merge_kernel"
     assert len(ps.short_name("x" * 200)) == 64
     groups = ps.clusters({1: 100.0, 2: 110.0, 3: 400.0, 4: 390.0, 5: 1000.0})
