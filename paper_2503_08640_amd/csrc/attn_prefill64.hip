@@ -39,8 +39,11 @@ constexpr int kD = 128;
 constexpr int kBN = 64;                       // keys per KV tile
 constexpr int kRowBytes = kD * 2;             // 256
 constexpr int kTileBytes = kBN * kRowBytes;   // 16 KiB per K or V tile
-constexpr int kRing = 4;                      // operand fragments in flight per wave
-constexpr int kDist = kRing - 1;              // a fragment is read this many fragments (two matrix instructions each) early
+// Operand fragments are read from LDS kDist fragments (two matrix instructions each) before their use, into
+// slot (index in the step) % kRing of a ring; kRing divides the fragments of every step, so that the fragments
+// one step reads for the next land where that step looks for them.
+constexpr int kRing = 8;
+constexpr int kDist = 5;
 // a lane's sum of the 16 probabilities of one step above which the step is redone around the true
 // row maximum: below it every probability is under 2^10, far inside bf16 and fp32
 constexpr float kOverflowSum = 1024.f;
@@ -92,7 +95,9 @@ template <bool QK_, bool SM_, bool PV_, int KBQ_, int KBP_, bool PRE_IN_, bool P
 struct StepCfg {
   static constexpr bool QK = QK_, SM = SM_, PV = PV_, PRE_IN = PRE_IN_, PRE_OUT = PRE_OUT_, MASK = MASK_;
   static constexpr int KBQ = KBQ_, KBP = KBP_;  // key half of the score block / of the product block
-  static constexpr int DMA = DMA_;              // loads spread over the step: 0 none, 1 a K tile, 2 a V tile
+  // loads spread over the step: 0 none, 1 a K tile, 2 a V tile, 3 / 4 the rows of Q of the next Q tile's
+  // first / second row block
+  static constexpr int DMA = DMA_;
 };
 
 // NW wavefronts per workgroup, each owning row blocks 2*wave and 2*wave+1 of the workgroup's
@@ -354,15 +359,23 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
       }
     }
   };
+  // A lane's row of Q arrives as eight 16-byte pieces (32 rows per load instruction, two pieces each: the
+  // address unit spends tens of cycles on every one).  The first Q tile's are requested in one go; those
+  // of a following Q tile ride on the drain steps of the one before, one piece every other matrix instruction.
   bf16x8 q_raw[2][kD / 16];
+  const __bf16* q_next[2];
+  auto aim_q = [&]() DBSA_INLINE {
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+      q_next[rb] = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(row_tok[rb]) * p.q.stride_tok +
+                   static_cast<int64_t>(head[rb]) * p.q.stride_head + 8 * half;
+  };
   auto load_q = [&]() DBSA_INLINE {
+    aim_q();
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(row_tok[rb]) * p.q.stride_tok +
-                         static_cast<int64_t>(head[rb]) * p.q.stride_head + 8 * half;
+    for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-      for (int c = 0; c < kD / 16; ++c) q_raw[rb][c] = *reinterpret_cast<const bf16x8*>(qp + 16 * c);
-    }
+      for (int c = 0; c < kD / 16; ++c) q_raw[rb][c] = *reinterpret_cast<const bf16x8*>(q_next[rb] + 16 * c);
   };
   intx4 qf[2][kD / 16];  // Q^T fragments pre-multiplied by scale*log2(e), in accumulation registers
   auto scale_q = [&]() DBSA_INLINE {
@@ -450,12 +463,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
   // KBP of the V stage); on entry S_w still holds the scores P_r was made from.  PRE_IN: the ring
   // already holds the step's first kDist fragments.  PRE_OUT: on exit it holds the first kDist K
   // fragments of the next step.  DMA: 1 = spread this wave's share of a K tile (dma_base, dma_dst)
-  // over the step, 2 = of a V tile.  MASK: the scores of this step may need the mask of tile tq.
+  // over the step, 2 = of a V tile, 3 / 4 = the rows of Q at q_next[0] / q_next[1] into q_raw.  MASK: the
+  // scores of this step may need the mask of tile tq.
   auto step = [&](auto CFG, floatx16 (&S_w)[2], floatx16 (&S_r)[2], bf16x2 (&P_w)[2][8], bf16x2 (&P_r)[2][8],
                   const TileRef& tq) DBSA_INLINE {
     using C = decltype(CFG);
     constexpr int nK = C::QK ? 8 : 0, nV = C::PV ? 8 : 0, nF = nK + nV, nSlots = 2 * nF;
     constexpr int nRead = nF + (C::PRE_OUT ? kDist : 0);  // fragments this step reads from LDS, its own first
+    static_assert(nF % kRing == 0 && kDist < kRing, "ring slots carry over from step to step");
 
     // No row maxima are taken on the way: a row's running maximum only has to bound its scores
     // to within what bf16 and fp32 hold, and the sum of a step's probabilities shows when it no
@@ -568,25 +583,43 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
         if constexpr (f + kDist < nRead) read_frag(std::integral_constant<int, f + kDist>{});
       }
       // ---- this wave's loads of the period, one every few matrix instructions ----
-      if constexpr (C::DMA != 0) {
+      if constexpr (C::DMA == 1 || C::DMA == 2) {
         constexpr int every = nSlots / kBlocksPerWave;
         if constexpr (t % every == every - 1)
           dma16(dma_base, C::DMA == 1 ? k_lane_off[t / every] : v_lane_off[t / every], dma_dst + (t / every) * 1024);
       }
+      if constexpr (C::DMA == 3 || C::DMA == 4) {
+        static_assert(C::DMA < 3 || nSlots == 2 * (kD / 16), "one piece of Q every other slot");
+        if constexpr (t % 2 == 1) q_raw[C::DMA - 3][t / 2] = *reinterpret_cast<const bf16x8*>(q_next[C::DMA - 3] + 16 * (t / 2));
+      }
       // ---- vector work in the shadow of the matrix instruction ----
       if constexpr (C::SM) {
-        // 16 units (8 per row block) of two exponentials: one per slot in the short steps, every
-        // other slot in a full step
-        constexpr int per = nSlots >= 32 ? 32 : 16;
-        constexpr int u_now = (t * 16 + per - 1) / per;         // first unit not issued before slot t
-        constexpr int u_next = ((t + 1) * 16 + per - 1) / per;
-        if constexpr (u_now < u_next && u_now < 16) {
-          constexpr int u = u_now;
+        // 16 units (8 per row block) of two exponentials.  A full step has two slots per unit: one
+        // exponential in each, and behind it one half of the previous unit's packing (a result of the
+        // transcendental unit cannot be used by the very next instructions), so that every matrix
+        // instruction shadows about the same vector work.  A short step has one slot per unit.
+        if constexpr (nSlots >= 32) {
+          constexpr int u = t / 2, w = t % 2;
+          ee[u % 2][w] = __builtin_amdgcn_exp2f(S_r[u / 8][2 * (u % 8) + w]);
+          asm volatile("" : "+v"(ee[u % 2][w]));
+          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (u > 0) {
+            constexpr int pu = u - 1;
+            if constexpr (w == 0) {
+              ls[pu / 8] += ee[pu % 2][0];
+              asm volatile("" : "+v"(ls[pu / 8]));
+            } else {
+              P_w[pu / 8][pu % 8] = __builtin_convertvector(floatx2{ee[pu % 2][0], ee[pu % 2][1]}, bf16x2);
+              ls[pu / 8] += ee[pu % 2][1];
+              asm volatile("" : "+v"(P_w[pu / 8][pu % 8]), "+v"(ls[pu / 8]));
+            }
+          }
+        } else {
+          constexpr int u = t;
           ee[u % 2][0] = __builtin_amdgcn_exp2f(S_r[u / 8][2 * (u % 8)]);
           ee[u % 2][1] = __builtin_amdgcn_exp2f(S_r[u / 8][2 * (u % 8) + 1]);
           asm volatile("" : "+v"(ee[u % 2][0]), "+v"(ee[u % 2][1]));
-          // the previous unit is packed BEHIND these exponentials (a result of the transcendental
-          // unit cannot be used by the very next instructions)
+          // the previous unit is packed behind these exponentials
           __builtin_amdgcn_sched_barrier(0);
           if constexpr (u > 0) pack_unit(std::integral_constant<int, u - 1>{});
         }
@@ -713,8 +746,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
 
     // ---- periods 1 .. n_tiles-1: the steady state ----
     for (int j = 1; j < n_tiles; ++j) {
+      request_entry();  // before the barrier, whose wait covers the entry's latency
       period_barrier();
-      request_entry();  // before this period's loads: it has returned when the period ends
       const TileRef tq = decode_ref(rw0[0], rw1[0]);
       if constexpr (ROPE) {
         // this period computes the scores of an entry of another segment: rebuild Q for it (every matrix
@@ -730,8 +763,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
 
     // ---- drain: the last tile's second probabilities and both of its products (no loads) ----
     period_barrier();
-    // the rows this Q tile writes; then the next Q tile's rows of Q are requested, and arrive
-    // during the drain steps and the epilogue
+    // the rows this Q tile writes; then the next Q tile's rows of Q are requested along the drain steps,
+    // and arrive during the epilogue
     const int o_start = q_start, o_len = q_len;
     int o_head[2], o_tok[2], o_slot[2];
     bool o_valid[2];
@@ -750,12 +783,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
       e0 = nq_e0;
       n_tiles = nq_n;
       place_rows();
-      if constexpr (!ROPE) load_q();
     }
     {
+      // (no Q tile follows: the pieces of the current rows come once more, into registers nobody reads)
+      constexpr int kQ0 = ROPE ? 0 : 3, kQ1 = ROPE ? 0 : 4;
+      if constexpr (!ROPE) aim_q();
       const TileRef none{0, kBN, false, false};
-      step(StepCfg<false, true, true, 0, 0, false, false, 0, false>{}, s_e, s_o, p_o, p_e, none);
-      step(StepCfg<false, false, true, 0, 1, false, false, 0, false>{}, s_o, s_e, p_e, p_o, none);
+      step(StepCfg<false, true, true, 0, 0, false, false, kQ0, false>{}, s_e, s_o, p_o, p_e, none);
+      step(StepCfg<false, false, true, 0, 1, false, false, kQ1, false>{}, s_o, s_e, p_e, p_o, none);
     }
     // the sums of the last step (a sum that is too large is caught by the product step after it, and
     // the last one is followed by none)
