@@ -188,12 +188,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
   // ---- global -> LDS loads: this wave fills blocks wave*kBlocksPerWave .. of each operand ----
   // lane -> (row, slot) inside block b: row = 4*b + lane/16, slot = lane%16; the piece fetched
   // into that slot is column (slot ^ swizzle(row)): K by row % 16, V by 4 * (row % 4).
+  // The loads a step spreads over its matrix instructions come in groups of four 1-KiB blocks: the first of a
+  // group sets the LDS base (m0), the others reach their block with the instruction's offset field, which moves
+  // the global address along with the LDS address.  The per-lane offsets therefore carry lane_bias(j) =
+  // kDmaBias - 1024 * (j % 4) (never negative, whatever row a lane fetches), and bases are taken kDmaBias lower.
+  constexpr unsigned kDmaBias = 3072;
+  auto lane_bias = [](int j) { return kDmaBias - 1024u * static_cast<unsigned>(j % 4); };
   unsigned k_lane_off[kBlocksPerWave], v_lane_off[kBlocksPerWave];
 #pragma unroll
   for (int j = 0; j < kBlocksPerWave; ++j) {
     const int row_in = 4 * (wave * kBlocksPerWave + j) + lane / 16;
-    k_lane_off[j] = static_cast<unsigned>(row_in * kp_stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u;
-    v_lane_off[j] = static_cast<unsigned>(row_in * vp_stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u;
+    k_lane_off[j] = static_cast<unsigned>(row_in * kp_stride + (((lane % 16) ^ (row_in % 16)) * 8)) * 2u + lane_bias(j);
+    v_lane_off[j] = static_cast<unsigned>(row_in * vp_stride + (((lane % 16) ^ (4 * (row_in % 4))) * 8)) * 2u + lane_bias(j);
   }
   auto issue_k = [&](const TileRef& t, int stage) DBSA_INLINE {
     const uint64_t base = pick(t.self, kself, kpool) + static_cast<uint64_t>(static_cast<unsigned>(t.start)) *
@@ -201,7 +207,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
     const unsigned dst = lds0 + stage * kTileBytes + wave * kBlocksPerWave * 1024;
     if (__builtin_expect(!t.self && t.len == kBN, 1)) {
 #pragma unroll
-      for (int j = 0; j < kBlocksPerWave; ++j) dma16(base, k_lane_off[j], dst + j * 1024);
+      for (int j = 0; j < kBlocksPerWave; ++j) dma16(base, k_lane_off[j] - lane_bias(j), dst + j * 1024);
     } else {
       const int stride = pick(t.self, ks_stride, kp_stride);
 #pragma unroll
@@ -218,7 +224,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
     const unsigned dst = lds0 + (KS + stage) * kTileBytes + wave * kBlocksPerWave * 1024;
     if (__builtin_expect(!t.self && t.len == kBN, 1)) {
 #pragma unroll
-      for (int j = 0; j < kBlocksPerWave; ++j) dma16(base, v_lane_off[j], dst + j * 1024);
+      for (int j = 0; j < kBlocksPerWave; ++j) dma16(base, v_lane_off[j] - lane_bias(j), dst + j * 1024);
     } else {
       const int stride = pick(t.self, vs_stride, vp_stride);
 #pragma unroll
@@ -586,7 +592,17 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
       if constexpr (C::DMA == 1 || C::DMA == 2) {
         constexpr int every = nSlots / kBlocksPerWave;
         if constexpr (t % every == every - 1)
-          dma16(dma_base, C::DMA == 1 ? k_lane_off[t / every] : v_lane_off[t / every], dma_dst + (t / every) * 1024);
+        {
+          constexpr int b = t / every;
+          const unsigned off = C::DMA == 1 ? k_lane_off[b] : v_lane_off[b];
+          if constexpr (b % 4 == 0)
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dma_dst + b * 1024), "v"(off), "s"(dma_base)
+                         : "memory");
+          else  // (nothing between the loads of a group writes m0: LDS reads do not use it on this chip)
+            asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" : : "v"(off), "s"(dma_base), "n"((b % 4) * 1024) : "memory");
+        }
       }
       if constexpr (C::DMA == 3 || C::DMA == 4) {
         static_assert(C::DMA < 3 || nSlots == 2 * (kD / 16), "one piece of Q every other slot");
@@ -650,7 +666,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
       const int row_in = 4 * (wave * kBlocksPerWave + i) + lane / 16;
       const int row = min(row_in, t.len - 1);  // rows past the tail repeat the last key
       const int sw = for_v ? 4 * (row_in % 4) : row_in % 16;
-      off[i] = static_cast<unsigned>(row * stride + (((lane % 16) ^ sw) * 8)) * 2u;
+      off[i] = static_cast<unsigned>(row * stride + (((lane % 16) ^ sw) * 8)) * 2u + lane_bias(i);
     }
   };
   // the K tile (entry 1+SL ahead) / the V tile (entry SL-1 ahead) a period loads
@@ -662,7 +678,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
     // (made uniform again by hand: under register pressure the compiler forms these with vector
     // instructions, and the load instruction takes them in scalar registers only)
     dma_base = uniform64(pick(tk.self, kself, kpool) + static_cast<uint64_t>(static_cast<unsigned>(tk.start)) *
-                                                           static_cast<unsigned>(2 * pick(tk.self, ks_stride, kp_stride)));
+                                                           static_cast<unsigned>(2 * pick(tk.self, ks_stride, kp_stride)) -
+                         kDmaBias);
     dma_dst = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(
         static_cast<int>(lds0 + k_wr * kTileBytes + wave * kBlocksPerWave * 1024)));
   };
@@ -672,7 +689,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
     if (__builtin_expect(special || v_special, 0)) lane_offsets(v_lane_off, tv, pick(tv.self, vs_stride, vp_stride), true);
     v_special = special;
     dma_base = uniform64(pick(tv.self, vself, vpool) + static_cast<uint64_t>(static_cast<unsigned>(tv.start)) *
-                                                           static_cast<unsigned>(2 * pick(tv.self, vs_stride, vp_stride)));
+                                                           static_cast<unsigned>(2 * pick(tv.self, vs_stride, vp_stride)) -
+                         kDmaBias);
     dma_dst = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(
         static_cast<int>(lds0 + (KS + v_wr) * kTileBytes + wave * kBlocksPerWave * 1024)));
   };
