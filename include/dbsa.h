@@ -199,12 +199,17 @@ int dbsa_layout_export_positions(const dbsa_layout* layout, const int32_t** list
  *               segments ascending (those with a user), runs ascending (a segment of t
  *               tiles is cut into n = ceil(t / chunk_tiles) runs of equal length to within
  *               one tile, run i = tiles [i t / n, (i+1) t / n)), users in ascending query
- *               order in batches of 32.  The sink's users are all queries.
+ *               order in batches of 32.  The sink's users are all queries.  A layout whose
+ *               contraction records would fill 55 % of their rows (row_fill of
+ *               dbsa_layout_export_matrix_records) cuts runs to measure instead
+ *               (dbsa_layout_export_matrix_plan): per segment, batch of 64 users by batch,
+ *               the runs of that batch in order, each with its one or two items of 32.
  *   qrefs     : int32 [n_qrefs][2] = (query, slot).
  *   slot_ptr  : int64 [B+1]: slots of query u are slot_ptr[u] .. slot_ptr[u+1]-1, numbered
  *               in item order; the last one is the own-cache slot.
  *   chunk_tiles: most tiles per run: ceil(longest segment with a user / n_split) when the
- *               caller gave n_split > 0, else chosen by the library (at most 32).
+ *               caller gave n_split > 0, else chosen by the library (at most 32; the longest
+ *               run where runs are cut to measure).
  */
 int dbsa_layout_export_decode_groups(const dbsa_layout* layout, const int64_t** seg_ptr, const int32_t** seg_ent,
                                      int64_t* n_seg_ent, const int32_t** items, int64_t* n_items,
@@ -242,6 +247,18 @@ int dbsa_layout_export_schedule(const dbsa_layout* layout, int32_t n_classes, co
  */
 int dbsa_layout_export_matrix_records(const dbsa_layout* layout, const int32_t** records, int64_t* n_records,
                                       float* row_fill);
+
+/*
+ * How a layout with row_fill >= 0.55 deals the records above to the workers of a contraction step
+ * (plumbing).  Such a layout cuts its runs to measure at build time: the (segment, 64 queries) units
+ * are laid end to end and cut into equal shares for `nominal_workers` = compute units / 8 workers per
+ * KV head (fewer shares when one would hold under 12 tiles); worker c of a step whose compute units
+ * per head block equal nominal_workers takes records plan_ptr[c] .. plan_ptr[c+1]-1 (n_workers + 1
+ * entries).  Other layouts, and steps with another worker count, deal runs of one length at launch:
+ * n_workers = 0.  The array belongs to the layout.  Errors: INVALID_ARG.
+ */
+int dbsa_layout_export_matrix_plan(const dbsa_layout* layout, const int32_t** plan_ptr, int32_t* n_workers,
+                                   int32_t* nominal_workers);
 
 /*
  * Device blocks (each with a pinned host twin) that hold the lists of destroyed layouts and wait

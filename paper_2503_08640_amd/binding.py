@@ -43,6 +43,7 @@ EXPORTED_SYMBOLS = (
     "dbsa_layout_export_decode_groups", "dbsa_layout_export_order", "dbsa_layout_export_positions", "dbsa_layout_destroy", "dbsa_workspace_bytes", "dbsa_preencode_attn",
     "dbsa_query_attn", "dbsa_decode_attn", "dbsa_rope_table", "dbsa_rope_apply", "dbsa_query_attn_rope",
     "dbsa_decode_attn_rope", "dbsa_decode_attn_kv8", "dbsa_decode_attn_kv8_rope", "dbsa_decode_attn_static", "dbsa_pooled_list_blocks", "dbsa_layout_export_matrix_records",
+    "dbsa_layout_export_matrix_plan",
     "dbsa_layout_export_schedule",
 )
 DBSA_STATIC_SCRATCH_BYTES = 32 << 20
@@ -110,6 +111,9 @@ def lib() -> C.CDLL:
     L.dbsa_layout_export_matrix_records.restype = C.c_int
     L.dbsa_layout_export_matrix_records.argtypes = [C.c_void_p, C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int64),
                                                     C.POINTER(C.c_float)]
+    L.dbsa_layout_export_matrix_plan.restype = C.c_int
+    L.dbsa_layout_export_matrix_plan.argtypes = [C.c_void_p, C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int32),
+                                                 C.POINTER(C.c_int32)]
     L.dbsa_pooled_list_blocks.restype = C.c_int32
     L.dbsa_pooled_list_blocks.argtypes = []
     L.dbsa_layout_destroy.restype = None
@@ -252,6 +256,14 @@ class Layout:
                "dbsa_layout_export_matrix_records")
         rec = np.ctypeslib.as_array(rp, shape=(n.value, 4)).copy() if n.value else np.zeros((0, 4), np.int32)
         return rec, float(fill.value)
+
+    def export_matrix_plan(self):
+        """-> (plan_ptr [n_workers + 1] int32 copy, or an empty array when records are dealt at launch; nominal workers)."""
+        pp, n, nominal = C.POINTER(C.c_int32)(), C.c_int32(), C.c_int32()
+        _check(lib().dbsa_layout_export_matrix_plan(self.handle, C.byref(pp), C.byref(n), C.byref(nominal)),
+               "dbsa_layout_export_matrix_plan")
+        ptr = np.ctypeslib.as_array(pp, shape=(n.value + 1,)).copy() if n.value else np.zeros(0, np.int32)
+        return ptr, int(nominal.value)
 
     def export_schedule(self, n_classes: int):
         """-> (class_ptr [n_classes+1], records [n_qtiles, 4]) int32 copies."""

@@ -357,12 +357,18 @@ bool ensure_schedule(const dbsa_layout* L, int32_t n_classes, hipStream_t stream
 }
 
 // the schedule of a decode step that runs its pool items as a contraction (dbsa_layout::mx_rec)
-bool ensure_matrix_schedule(const dbsa_layout* L, int32_t n_classes, hipStream_t stream) {
+// (planned: the layout cut its runs for exactly these workers, mx_plan_ptr deals them)
+bool ensure_matrix_schedule(const dbsa_layout* L, int32_t n_classes, bool planned, hipStream_t stream) {
   if (L->mx_rec.empty()) return false;
   const ScheduleSlot slot{&L->mx_classes, &L->mx_sched_ptr, &L->mx_sched_rec, &L->mx_on_device, L->dev.mx_sched_rec,
                           L->dev.mx_sched_ptr, &L->dev.mx_uploaded, &L->dev.mx_stream};
   return ensure_slot(L, slot, n_classes, stream, [&](int32_t n, std::vector<int32_t>* ptr, std::vector<int32_t>* rec) {
-    dbsa_balance_records(L->mx_rec, n, ptr, rec);
+    if (planned) {
+      *ptr = L->mx_plan_ptr;
+      *rec = L->mx_rec;
+    } else {
+      dbsa_balance_records(L->mx_rec, n, ptr, rec);
+    }
   });
 }
 
@@ -692,6 +698,15 @@ int dbsa_layout_export_schedule(const dbsa_layout* L, int32_t n_classes, const i
   return DBSA_OK;
 }
 
+int dbsa_layout_export_matrix_plan(const dbsa_layout* L, const int32_t** plan_ptr, int32_t* n_workers,
+                                   int32_t* nominal_workers) {
+  if (!L || !L->query_stage) return DBSA_ERR_INVALID_ARG;
+  if (plan_ptr) *plan_ptr = L->mx_plan_ptr.data();
+  if (n_workers) *n_workers = L->mx_plan_ptr.empty() ? 0 : static_cast<int32_t>(L->mx_plan_ptr.size()) - 1;
+  if (nominal_workers) *nominal_workers = L->mx_plan_workers;
+  return DBSA_OK;
+}
+
 int dbsa_layout_export_matrix_records(const dbsa_layout* L, const int32_t** records, int64_t* n_records, float* row_fill) {
   if (!L || !L->query_stage) return DBSA_ERR_INVALID_ARG;
   if (records) *records = L->mx_rec.data();
@@ -945,9 +960,12 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
       if (r % 4 == 0 && !rope_table && L->mx_row_fill >= kMatrixRowFill) {
         // one workgroup per compute unit, or per record where there are fewer
         const int32_t head_blocks = n_q_heads / 4;
-        const int32_t classes = static_cast<int32_t>(
-            std::min<int64_t>(L->compute_units / head_blocks, static_cast<int64_t>(L->mx_rec.size() / 4)));
-        if (classes >= 1 && ensure_matrix_schedule(L, classes, s)) {
+        const bool planned = !L->mx_plan_ptr.empty() && L->compute_units / head_blocks == L->mx_plan_workers;
+        const int32_t classes =
+            planned ? static_cast<int32_t>(L->mx_plan_ptr.size()) - 1
+                    : static_cast<int32_t>(std::min<int64_t>(L->compute_units / head_blocks,
+                                                             static_cast<int64_t>(L->mx_rec.size() / 4)));
+        if (classes >= 1 && ensure_matrix_schedule(L, classes, planned, s)) {
           p.decode_matrix = 1;
           p.decode_waves = 1;
           p.mx_sched_rec = L->dev.mx_sched_rec;

@@ -243,42 +243,94 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
     int64_t chunk = sel->n_split > 0 ? (max_tiles + sel->n_split - 1) / sel->n_split
                                      : std::min<int64_t>(32, (tile_batches + run_slots - 1) / run_slots);
     chunk = std::max<int64_t>(1, chunk);
+    // Steps that will run their pool items as a contraction (64 queries per wave, one persistent
+    // workgroup per compute unit and KV head: mx_rec below) are bound by arithmetic, and what counts is
+    // that every worker gets the same work.  Runs of ONE length cannot do that (90 runs of 32 tiles over
+    // 32 workers: three rounds for 2.8 rounds of work), so such a layout cuts its runs to measure: the
+    // (segment, 64 queries) units are walked in order and dealt to W workers (W = compute units / 8 per
+    // KV head, fewer when a worker's share would fall below kMinShare tiles), each taking tiles until
+    // its cost (tiles + kRunCost per run, what starting and finishing a run costs in tiles) reaches the
+    // mean; a unit that does not fit is cut there, but no run is shorter than kSnap tiles: a worker
+    // rather stops a little early or takes the few tiles that are left.  Worker c takes the runs
+    // mx_plan_ptr[c] .. mx_plan_ptr[c+1]-1, in order.  cuts[s][b] = the run boundaries of the b-th
+    // batch of 64 queries of segment s.
+    std::vector<std::vector<std::vector<int64_t>>> cuts;
     if (sel->n_split == 0) {
-      // Steps that will run their pool items as a contraction (64 queries per wave, one persistent
-      // workgroup per compute unit and KV head: mx_rec below) are bound by arithmetic, and what
-      // counts is how evenly whole records fill the workers: with W workers per KV head (8 KV heads
-      // assumed, as above) a step takes ceil(records / W) rounds of one record each.  Among the run
-      // lengths of 12..64 tiles take the one with the smallest estimate rounds x (tiles of a run x
-      // cycles per tile + cycles per record), the longer run on a tie (fewer partial states to merge).
       double rows = 0.0, used = 0.0;
+      int64_t line = 0, n_units = 0;
       for (int32_t s = 0; s <= G; ++s) {
         const int64_t t = L->gm_seg_ptr[s + 1] - L->gm_seg_ptr[s];
         const int64_t n_u = static_cast<int64_t>(users[s].size());
         if (n_u == 0 || t == 0) continue;
         rows += 64.0 * static_cast<double>(t) * static_cast<double>((n_u + 63) / 64);
         used += static_cast<double>(t) * static_cast<double>(n_u);
+        line += t * ((n_u + 63) / 64);
+        n_units += (n_u + 63) / 64;
       }
       if (rows > 0.0 && used / rows >= kMatrixRowFill) {
-        constexpr double kCyclesPerTile = 3200.0, kCyclesPerRecord = 13000.0;
-        const int64_t workers = std::max<int64_t>(1, L->compute_units / 8);
-        double best = 0.0;
-        for (int64_t c = 12; c <= 64; ++c) {
-          int64_t records = 0;
-          double longest = 0.0;
+        constexpr int64_t kMinShare = 12, kSnap = 4;
+        constexpr double kRunCost = 4.5;
+        const int64_t nominal = std::max<int64_t>(1, L->compute_units / 8);
+        const int64_t workers = std::max<int64_t>(1, std::min<int64_t>(nominal, line / kMinShare));
+        int64_t n_rec = 0, longest = 1;
+        // one walk for a given share; returns what is left for the last worker, who takes the rest
+        auto deal = [&](double target) {
+          cuts.assign(static_cast<size_t>(G) + 1, {});
+          L->mx_plan_ptr.assign(1, 0);
+          n_rec = 0;
+          longest = 1;
+          double acc = 0.0;
+          auto next_worker = [&]() {
+            L->mx_plan_ptr.push_back(static_cast<int32_t>(n_rec));
+            acc = 0.0;
+          };
           for (int32_t s = 0; s <= G; ++s) {
-            const int64_t t = L->gm_seg_ptr[s + 1] - L->gm_seg_ptr[s];
+            const int64_t t0 = L->gm_seg_ptr[s], t = L->gm_seg_ptr[s + 1] - t0;
             const int64_t n_u = static_cast<int64_t>(users[s].size());
             if (n_u == 0 || t == 0) continue;
-            const int64_t n_runs = (t + c - 1) / c;
-            records += n_runs * ((n_u + 63) / 64);
-            longest = std::max(longest, static_cast<double>((t + n_runs - 1) / n_runs));
+            for (int64_t b = 0; b < (n_u + 63) / 64; ++b) {
+              std::vector<int64_t> bounds(1, t0);
+              int64_t pos = 0;
+              while (pos < t) {
+                const bool last = static_cast<int64_t>(L->mx_plan_ptr.size()) >= workers;
+                const double room = target - acc - kRunCost;
+                const int64_t rem = t - pos;
+                if (last || static_cast<double>(rem) <= room + static_cast<double>(kSnap)) {
+                  acc += kRunCost + static_cast<double>(rem);  // the rest of the unit is one run
+                  longest = std::max(longest, rem);
+                  pos = t;
+                } else if (room < static_cast<double>(kSnap) && acc > 0.0) {
+                  next_worker();  // no room worth a run
+                } else {
+                  const int64_t take = std::min(rem - kSnap, std::max<int64_t>(kSnap, static_cast<int64_t>(room)));
+                  pos += take;
+                  bounds.push_back(t0 + pos);
+                  longest = std::max(longest, take);
+                  n_rec += 1;
+                  next_worker();
+                }
+              }
+              bounds.push_back(t0 + t);
+              n_rec += 1;
+              cuts[static_cast<size_t>(s)].push_back(std::move(bounds));
+            }
           }
-          const double est = static_cast<double>((records + workers - 1) / workers) * (longest * kCyclesPerTile + kCyclesPerRecord);
-          if (best == 0.0 || est <= best) {
-            best = est;
-            chunk = c;
-          }
+          const double last_cost = static_cast<int64_t>(L->mx_plan_ptr.size()) >= workers ? acc : 0.0;
+          while (static_cast<int64_t>(L->mx_plan_ptr.size()) < workers) L->mx_plan_ptr.push_back(static_cast<int32_t>(n_rec));
+          L->mx_plan_ptr.push_back(static_cast<int32_t>(n_rec));
+          return last_cost;
+        };
+        L->mx_plan_workers = static_cast<int32_t>(nominal);
+        // the smallest share with which the last worker is left no more than the others (the number of
+        // runs, and with it the total cost, depends on the share itself)
+        double lo = static_cast<double>(line) / static_cast<double>(workers);
+        double hi = 2.0 * lo + 16.0 * kRunCost + static_cast<double>(kSnap);
+        for (int it = 0; it < 24; ++it) {
+          const double mid = 0.5 * (lo + hi);
+          (deal(mid) <= mid + static_cast<double>(kSnap) ? hi : lo) = mid;
         }
+        deal(hi);
+        chunk = longest;
       }
     }
     L->gm_chunk_tiles = static_cast<int32_t>(chunk);
@@ -304,6 +356,32 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
       for (int32_t s = 0; s <= G; ++s) {
         const int64_t t0 = L->gm_seg_ptr[s], t1 = L->gm_seg_ptr[s + 1];
         if (users[s].empty()) continue;
+        if (!cuts.empty()) {
+          // runs cut to measure: batch of 64 queries by batch, run by run, its one or two items of 32
+          const auto& per_batch = cuts[static_cast<size_t>(s)];
+          for (size_t b = 0; b < per_batch.size(); ++b)
+            for (size_t run = 0; run + 1 < per_batch[b].size(); ++run) {
+              const int64_t c0 = per_batch[b][run], c1 = per_batch[b][run + 1];
+              for (size_t b0 = 64 * b; b0 < std::min(users[s].size(), 64 * b + 64); b0 += kItemQueries) {
+                const size_t b1 = std::min(users[s].size(), b0 + kItemQueries);
+                if (pass == 1)
+                  L->gm_items.insert(L->gm_items.end(),
+                                     {static_cast<int32_t>(c0), static_cast<int32_t>(c1 - c0),
+                                      static_cast<int32_t>(L->gm_qrefs.size() / 2), static_cast<int32_t>(b1 - b0)});
+                for (size_t k = b0; k < b1; ++k) {
+                  const int32_t u = users[s][k];
+                  if (pass == 0)
+                    ++n_slots[u];
+                  else {
+                    L->gm_qrefs.push_back(u);
+                    L->gm_qrefs.push_back(static_cast<int32_t>(L->gm_slot_ptr[u] + next[u]++));
+                    L->gm_qshift.push_back(seg_shift[static_cast<size_t>(u) * (G + 1) + s]);
+                  }
+                }
+              }
+            }
+          continue;
+        }
         // the segment's tiles are cut into ceil(tiles / chunk) runs of equal length (to within one
         // tile): a short last run would leave its workgroup idle while the full ones finish
         const int64_t n_runs = (t1 - t0 + chunk - 1) / chunk;

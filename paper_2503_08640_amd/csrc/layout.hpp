@@ -95,6 +95,11 @@ struct dbsa_layout {
   // a query, weighted by tiles.
   std::vector<int32_t> mx_rec;
   float mx_row_fill = 0.f;
+  // Layouts whose steps will run as a contraction cut their runs for mx_plan_workers workers per KV head
+  // (compute units / 8): worker c of such a step takes records mx_plan_ptr[c] .. mx_plan_ptr[c+1]-1 of
+  // mx_rec (mx_plan_ptr.size() - 1 workers carry records).  Empty: runs of one length, dealt at launch.
+  std::vector<int32_t> mx_plan_ptr;
+  int32_t mx_plan_workers = 0;
   // figures the attention calls need on every launch, taken once at build time
   int32_t gm_max_queries = 1;       // most queries any schedule item serves
   int64_t shortest_list = 0;        // fewest entries any Q tile lists

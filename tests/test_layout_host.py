@@ -400,30 +400,68 @@ def test_rotation_ids_known_to_the_host_must_lie_inside_the_table():
 
 def expected_decode_chunk(tiles, users, compute_units):
     """The default run length of the decode schedule, restated: tiles[s] / users[s] = tiles of segment s and
-    queries that use it (segments without users or tiles left out)."""
-    run_slots = max(1, compute_units * 6 // 8 * 3 // 4)
-    batches = sum(t * -(-u // 32) for t, u in zip(tiles, users))
-    chunk = max(1, min(32, -(-batches // run_slots)))
+    queries that use it (segments without users or tiles left out).  Layouts that fill 55 % of the 64 rows of a
+    contraction record cut their runs to measure instead (expected_matrix_plan): for them this is the longest run."""
     rows = sum(64.0 * t * -(-u // 64) for t, u in zip(tiles, users))
     used = sum(float(t) * u for t, u in zip(tiles, users))
     if rows > 0 and used / rows >= 0.55:
-        # contraction-eligible: fewest rounds of whole records over compute_units / 8 workers per KV head
-        workers = max(1, compute_units // 8)
-        best = 0.0
-        for c in range(12, 65):
-            records = sum(-(-t // c) * -(-u // 64) for t, u in zip(tiles, users))
-            longest = max(float(-(-t // -(-t // c))) for t in tiles)
-            est = float(-(-records // workers)) * (longest * 3200.0 + 13000.0)
-            if best == 0.0 or est <= best:
-                best, chunk = est, c
-    return chunk
+        runs, _ = expected_matrix_plan(tiles, users, compute_units)
+        return max(runs)
+    run_slots = max(1, compute_units * 6 // 8 * 3 // 4)
+    batches = sum(t * -(-u // 32) for t, u in zip(tiles, users))
+    return max(1, min(32, -(-batches // run_slots)))
+
+
+def expected_matrix_plan(tiles, users, compute_units):
+    """Runs cut to measure, restated: the (segment, 64 queries) units are walked in order; a worker takes tiles
+    until its cost (tiles + 4.5 per run) reaches the share, a unit that does not fit is cut there, no run is shorter
+    than 4 tiles; the share is the smallest (by bisection) that leaves the last worker no more than the others + 4.
+    -> (run lengths in order, plan_ptr)."""
+    k_run, k_snap, k_min_share = 4.5, 4, 12
+    units = [t for t, u in zip(tiles, users) for _ in range(-(-u // 64))]
+    line = sum(units)
+    workers = max(1, min(max(1, compute_units // 8), line // k_min_share))
+
+    def deal(target):
+        plan, runs, acc = [0], [], 0.0
+        for t in units:
+            pos = 0
+            while pos < t:
+                room, rem = target - acc - k_run, t - pos
+                if len(plan) >= workers or rem <= room + k_snap:
+                    acc += k_run + rem
+                    runs.append(rem)
+                    pos = t
+                elif room < k_snap and acc > 0.0:
+                    plan.append(len(runs))
+                    acc = 0.0
+                else:
+                    take = min(rem - k_snap, max(k_snap, int(room)))
+                    pos += take
+                    runs.append(take)
+                    plan.append(len(runs))
+                    acc = 0.0
+        last = acc if len(plan) >= workers else 0.0
+        plan += [len(runs)] * (workers + 1 - len(plan))
+        return runs, plan, last
+
+    lo = line / workers
+    hi = 2.0 * lo + 16.0 * k_run + k_snap
+    for _ in range(24):
+        mid = 0.5 * (lo + hi)
+        if deal(mid)[2] <= mid + k_snap:
+            hi = mid
+        else:
+            lo = mid
+    runs, plan, _ = deal(hi)
+    return runs, plan
 
 
 def test_default_decode_chunk_follows_the_compute_unit_count():
     """A layout built without a device is sized for 256 compute units.  Few queries per group: runs of pool
     tiles are cut so that about 144 single-wave workgroups per KV head (six per compute unit over eight KV
     heads, three quarters of them for pool runs) cover the step, never longer than 32 tiles.  Most of 64 rows
-    filled: the run length that lets whole records fill 32 workers per KV head in the fewest rounds."""
+    filled: runs cut to measure for 32 workers per KV head, every worker within a few tiles of the mean cost."""
     pc = synth.make_pool_case("chunkpool", 11, dtype="bf16", n_q_heads=2, n_kv_heads=1, head_dim=16, sink_len=64,
                               pool_tokens=60000, demo_len_range=(200, 600), n_groups=6).pool
     assert 256 * 6 // 8 * 3 // 4 == 144
@@ -440,8 +478,18 @@ def test_default_decode_chunk_follows_the_compute_unit_count():
         assert got["chunk_tiles"] == want, (nq, got["chunk_tiles"], want)
         seen.add(want)
         assert got["items"][:, 1].max() <= want                         # no run is longer than the chunk
-        _, fill = lay.export_matrix_records()
+        rec, fill = lay.export_matrix_records()
+        plan, nominal = lay.export_matrix_plan()
         assert (fill >= 0.55) == (nq in (40, 100, 200)), (nq, fill)
+        assert nominal == (32 if fill >= 0.55 else 0) and (len(plan) > 0) == (fill >= 0.55)
+        if fill >= 0.55:
+            runs, want_plan = expected_matrix_plan(tiles, [nq] * len(tiles), 256)
+            assert rec[:, 3].tolist() == runs and plan.tolist() == want_plan
+            # every unit's runs tile its segment in order; a worker's records are consecutive
+            assert plan[0] == 0 and plan[-1] == len(rec) and np.all(np.diff(plan) >= 0)
+            cost = np.array([rec[plan[c]:plan[c + 1], 3].sum() + 4.5 * (plan[c + 1] - plan[c]) for c in range(len(plan) - 1)])
+            assert cost.max() <= cost.mean() + 8.5, (nq, cost.max(), cost.mean())
+            assert rec[:, 3].min() >= min(4, min(tiles))
     assert len(seen) >= 3
 
 
