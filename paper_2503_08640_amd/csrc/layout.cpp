@@ -324,7 +324,10 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
         // the smallest share with which the last worker is left no more than the others (the number of
         // runs, and with it the total cost, depends on the share itself)
         double lo = static_cast<double>(line) / static_cast<double>(workers);
-        double hi = 2.0 * lo + 16.0 * kRunCost + static_cast<double>(kSnap);
+        // (a worker stops less than kRunCost + kSnap short of the share, and there are at most units + W runs:
+        // with this share the last worker is sure to be left no more than the others)
+        double hi = (static_cast<double>(line) + kRunCost * static_cast<double>(n_units + workers)) / static_cast<double>(workers) +
+                    kRunCost + 2.0 * static_cast<double>(kSnap);
         for (int it = 0; it < 24; ++it) {
           const double mid = 0.5 * (lo + hi);
           (deal(mid) <= mid + static_cast<double>(kSnap) ? hi : lo) = mid;

@@ -446,7 +446,7 @@ def expected_matrix_plan(tiles, users, compute_units):
         return runs, plan, last
 
     lo = line / workers
-    hi = 2.0 * lo + 16.0 * k_run + k_snap
+    hi = (line + k_run * (len(units) + workers)) / workers + k_run + 2.0 * k_snap
     for _ in range(24):
         mid = 0.5 * (lo + hi)
         if deal(mid)[2] <= mid + k_snap:
@@ -491,6 +491,55 @@ def test_default_decode_chunk_follows_the_compute_unit_count():
             assert cost.max() <= cost.mean() + 8.5, (nq, cost.max(), cost.mean())
             assert rec[:, 3].min() >= min(4, min(tiles))
     assert len(seen) >= 3
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_runs_cut_to_measure_tile_every_unit_and_balance_the_workers(seed):
+    """Random pools (a few huge groups, many tiny ones, ragged user counts): wherever a layout cuts its runs to
+    measure, the runs of a (segment, 64 users) unit tile it in order, none is shorter than 4 tiles unless the unit is,
+    the plan hands every record to one worker, and no worker but the last carries more than the share allows."""
+    rng = np.random.default_rng(100 + seed)
+    n_groups = int(rng.integers(1, 40))
+    small = seed % 3 == 0                      # many groups of a tile or two / a few long ones
+    pc = synth.make_pool_case("planpool", 200 + seed, dtype="bf16", n_q_heads=2, n_kv_heads=1, head_dim=16,
+                              sink_len=int(rng.integers(1, 300)), pool_tokens=int(n_groups * (60 if small else rng.integers(300, 5000))),
+                              demo_len_range=(5, 40) if small else (30, 400), n_groups=n_groups).pool
+    n_groups = pc.n_groups
+    n_q = int(rng.integers(40, 400))
+    sels = [np.sort(rng.choice(n_groups, size=int(rng.integers(max(1, n_groups // 2), n_groups + 1)), replace=False)) for _ in range(n_q)]
+    sel_ptr = np.concatenate([[0], np.cumsum([len(x) for x in sels])]).astype(np.int32)
+    sel_idx = np.concatenate(sels).astype(np.int32)
+    cu = np.arange(n_q + 1, dtype=np.int32)
+    lay = B.dbsa_layout_build(pc.sink_len, pc.demo_offsets, pc.group_demo_offsets, cu_qlens=cu, sel_ptr=sel_ptr,
+                              sel_idx=sel_idx, n_split=0, block_m=64, block_n=64, host_only=True)
+    got = lay.export_decode_groups(n_groups, n_q)
+    rec, fill = lay.export_matrix_records()
+    plan, nominal = lay.export_matrix_plan()
+    if fill < 0.55:
+        assert len(plan) == 0 and nominal == 0
+        return
+    assert nominal == 32 and plan[0] == 0 and plan[-1] == len(rec) and np.all(np.diff(plan) >= 0) and len(plan) - 1 <= 32
+    seg_ptr = got["seg_ptr"]
+    users = [n_q] + [int((sel_idx == g).sum()) for g in range(n_groups)]
+    tiles = np.diff(seg_ptr).tolist()
+    # the records, in order, walk the units (segment, batch of 64 users) and tile each of them
+    i = 0
+    for s, (t, u) in enumerate(zip(tiles, users)):
+        if t == 0 or u == 0:
+            continue
+        for b in range(-(-u // 64)):
+            at = int(seg_ptr[s])
+            while at < seg_ptr[s + 1]:
+                r0, nq, e0, en = rec[i]
+                assert e0 == at and nq == min(64, u - 64 * b) and en >= min(4, t), (s, b, rec[i].tolist())
+                at += int(en)
+                i += 1
+            assert at == seg_ptr[s + 1]
+    assert i == len(rec)
+    runs, want_plan = expected_matrix_plan(tiles, users, 256)
+    assert rec[:, 3].tolist() == runs and plan.tolist() == want_plan
+    cost = np.array([rec[plan[c]:plan[c + 1], 3].sum() + 4.5 * (plan[c + 1] - plan[c]) for c in range(len(plan) - 1)])
+    assert cost[:-1].max(initial=0.0) <= cost.mean() + 4.5 + 2 * 4 + 4.5 * 2 or len(cost) == 1, (cost.max(), cost.mean())
 
 
 @pytest.mark.parametrize("n_classes", [1, 7, 64, 512])
