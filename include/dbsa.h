@@ -200,7 +200,7 @@ int dbsa_layout_export_positions(const dbsa_layout* layout, const int32_t** list
  *               tiles is cut into n = ceil(t / chunk_tiles) runs of equal length to within
  *               one tile, run i = tiles [i t / n, (i+1) t / n)), users in ascending query
  *               order in batches of 32.  The sink's users are all queries.  A layout whose
- *               contraction records would fill 55 % of their rows (row_fill of
+ *               contraction records would fill 22 % of their rows (row_fill of
  *               dbsa_layout_export_matrix_records) cuts runs to measure instead
  *               (dbsa_layout_export_matrix_plan): per segment, batch of 64 users by batch,
  *               the runs of that batch in order, each with its one or two items of 32.
@@ -241,7 +241,7 @@ int dbsa_layout_export_schedule(const dbsa_layout* layout, int32_t n_classes, co
  * tiles seg_ent[first tile .. + tiles) of one run of one segment.  Every (item, query) pair of the
  * decode schedule appears in exactly one record, with the slot it has there.  row_fill = share of
  * the 64 rows of a record that carry a query, weighted by tiles: a decode step with query heads
- * in fours per KV head, no re-positioning and row_fill >= 0.55 runs these records as a dense
+ * in fours per KV head, no re-positioning and row_fill >= 0.22 runs these records as a dense
  * contraction (64 queries per wavefront) instead of the 32-column work items; the partial states
  * and the merge are the same.  The array belongs to the layout.  Errors: INVALID_ARG.
  */
@@ -249,7 +249,7 @@ int dbsa_layout_export_matrix_records(const dbsa_layout* layout, const int32_t**
                                       float* row_fill);
 
 /*
- * How a layout with row_fill >= 0.55 deals the records above to the workers of a contraction step
+ * How a layout with row_fill >= 0.22 deals the records above to the workers of a contraction step
  * (plumbing).  Such a layout cuts its runs to measure at build time: the (segment, 64 queries) units
  * are laid end to end and cut into equal shares for `nominal_workers` = compute units / 8 workers per
  * KV head (fewer shares when one would hold under 12 tiles); worker c of a step whose compute units

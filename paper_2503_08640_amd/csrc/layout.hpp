@@ -137,9 +137,9 @@ struct dbsa_layout {
 
 constexpr int32_t kMaxSchedClasses = 512;
 // share of a wave's 64 rows that must carry a query before a decode step runs its pool items as a
-// contraction (measured on a 90k-token pool, 8 KV heads: at 0.64-1.0 the step is 11-30 % faster than
-// with 32-column work items, at 0.5 it is even, below that slower)
-constexpr float kMatrixRowFill = 0.55f;
+// contraction (measured on a 90k-token pool, 8 KV heads, 32-256 queries, with the runs cut to measure:
+// at 0.24-0.5 the step is 3-26 % faster than with 32-column work items, at 0.18 and below 10-20 % slower)
+constexpr float kMatrixRowFill = 0.22f;
 
 // Deals the Q tiles of a layout to n_classes workers for a launch in which every worker walks its
 // tiles one after the other: tiles are taken in launch order (owner-major, so that at any time all

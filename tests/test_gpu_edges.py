@@ -249,7 +249,7 @@ def test_decode_with_many_queries_per_group_as_a_contraction(n_queries, n_select
     qc = synth.make_query_case("mxq", 3501, pc, n_queries=n_queries, q_len=q_len, n_select=n_select, n_decode=2)
     lay, kp, vp = _query_setup(pc, qc, 32, 0)
     rec, fill = lay.export_matrix_records()
-    assert fill >= 0.55 and rec[:, 1].max() > 32, "this case is meant to take the contraction path"
+    assert fill >= 0.22 and rec[:, 1].max() > 32, "this case is meant to take the contraction path"
     _run_decode_steps(pc, qc, lay, kp, vp, range(2), f"{n_queries} queries x {n_select} of {groups} groups")
     # twice the same step on twin layouts: bitwise equal (static schedule, no atomics)
     lay2, _, _ = _query_setup(pc, qc, 32, 0)
