@@ -417,8 +417,9 @@ int dbsa_rope_apply(dbsa_tensor x, dbsa_tensor out, int32_t n_tokens, int32_t n_
  * rotated at their index inside the query; k_pool holds pool keys rotated at their token index.
  * rope_table as written by dbsa_rope_table with n_pos > list_shift[e] + rows of the Q tile for
  * every list entry (else INVALID_ARG; 2 * pool tokens + the longest query always suffices: a
- * group that moves towards the front of the cache is reached by rotating the query FORWARD).  bf16, head_dim 128, tile sizes of the MFMA kernels (else
- * UNSUPPORTED).  Everything else as dbsa_query_attn.
+ * group that moves towards the front of the cache is reached by rotating the query FORWARD).  Same
+ * dtypes and shapes as dbsa_query_attn: bf16 with head_dim 128 runs the pipelined matrix kernel, any
+ * other shape the plain fp32-arithmetic one.  Everything else as dbsa_query_attn.
  */
 int dbsa_query_attn_rope(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_tensor k_self, dbsa_tensor v_self,
                          dbsa_tensor k_pool, dbsa_tensor v_pool, dbsa_tensor o, float* lse, const float* rope_table,
@@ -432,7 +433,8 @@ int dbsa_query_attn_rope(const dbsa_layout* layout, dbsa_tensor q_self, dbsa_ten
  * what a query's cache can hold, Tmax = stride_query / k_selfcache.stride_tok tokens: INVALID_ARG
  * unless rope_n_pos > max(qref_shift) + Tmax - 1 (2 * pool tokens + Tmax always suffices).  A
  * self_len beyond Tmax is the caller's error; the kernel clamps the id to the table.
- * bf16, head_dim 128, 32 % (n_q_heads / n_kv_heads) == 0 (else UNSUPPORTED).
+ * Same dtypes and shapes as dbsa_decode_attn: bf16 with head_dim 128 and 32 % (n_q_heads /
+ * n_kv_heads) == 0 runs the group-major matrix kernel, any other shape the plain one.
  */
 int dbsa_decode_attn_rope(const dbsa_layout* layout, dbsa_tensor q_step, dbsa_tensor k_selfcache,
                           dbsa_tensor v_selfcache, const int32_t* self_len, int64_t stride_query, dbsa_tensor k_pool,

@@ -148,12 +148,12 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
                b_grp = L->gm_ref_pad.size() * sizeof(int32_t), b_grw = L->gm_rows.size() * sizeof(int32_t),
                b_gse = L->gm_seg_ent.size() * sizeof(int32_t), b_gqr = L->gm_qrefs.size() * sizeof(int32_t),
                b_srec = L->qtile_tab.size() * sizeof(int32_t), b_sptr = (kMaxSchedClasses + 1) * sizeof(int32_t),
-               b_mrec = L->mx_rec.size() * sizeof(int32_t);
+               b_mrec = L->mx_rec.size() * sizeof(int32_t), b_dsh = L->dec_shift.size() * sizeof(int32_t);
   const size_t o_tab = 0, o_ptr = o_tab + pad(b_tab), o_ent = o_ptr + pad(b_ptr), o_ord = o_ent + pad(b_ent),
                o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), o_gsp = o_spl + pad(b_spl),
                o_lsh = o_gsp + pad(b_gsp), o_gir = o_lsh + pad(b_lsh), o_grp = o_gir + pad(b_gir),
                o_grw = o_grp + pad(b_grp), o_gse = o_grw + pad(b_grw), o_gqr = o_gse + pad(b_gse),
-               o_srec = o_gqr + pad(b_gqr), o_sptr = o_srec + pad(b_srec), o_mrec = o_sptr + pad(b_sptr),
+               o_dsh = o_gqr + pad(b_gqr), o_srec = o_dsh + pad(b_dsh), o_sptr = o_srec + pad(b_srec), o_mrec = o_sptr + pad(b_sptr),
                o_mptr = o_mrec + pad(b_mrec), lists_end = o_srec, total = o_mptr + pad(b_sptr) + 256;
   ListBlock blk{};
   hipError_t e = acquire_block(total, &blk);
@@ -175,6 +175,7 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   put(o_grw, L->gm_rows.data(), b_grw);
   put(o_gse, L->gm_seg_ent.data(), b_gse);
   put(o_gqr, L->gm_qrefs.data(), b_gqr);
+  put(o_dsh, L->dec_shift.data(), b_dsh);
   // the staging twin stays with the block, so nothing has to wait for the copy here; calls on
   // other streams are ordered behind it through the event
   hipEvent_t uploaded = nullptr;
@@ -212,6 +213,7 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   L->dev.gm_rows = reinterpret_cast<int32_t*>(b + o_grw);
   L->dev.gm_seg_ent = reinterpret_cast<int32_t*>(b + o_gse);
   L->dev.gm_qrefs = reinterpret_cast<int32_t*>(b + o_gqr);
+  L->dev.dec_shift = reinterpret_cast<int32_t*>(b + o_dsh);
   L->dev.sched_rec = reinterpret_cast<int32_t*>(b + o_srec);
   L->dev.sched_ptr = reinterpret_cast<int32_t*>(b + o_sptr);
   L->dev.mx_sched_rec = reinterpret_cast<int32_t*>(b + o_mrec);
@@ -469,6 +471,7 @@ void fill_lists(AttnParams& p, const dbsa_layout* L) {
   p.split_ptr = L->dev.split_ptr;
   p.gm_slot_ptr = L->dev.gm_slot_ptr;
   p.list_shift = L->dev.list_shift;
+  p.dec_shift = L->dev.dec_shift;
   p.gm_item_run = L->dev.gm_item_run;
   p.gm_ref_pad = L->dev.gm_ref_pad;
   p.n_gm_items = static_cast<int32_t>(L->gm_items.size() / 4);
@@ -511,13 +514,16 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
   hipError_t e = order_behind_upload(L, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return DBSA_ERR_HIP;
   if (dtype == DBSA_BF16) {
-    if (!mfma_tile_sizes_ok(L)) return DBSA_ERR_UNSUPPORTED;
-    p.heads_per_block = pick_heads_per_block(hq / hkv, L->block_m);
     // the pipelined kernel addresses a tile's rows with 32-bit byte offsets
     const int64_t max_stride = std::max(std::max(p.k_pool.stride_tok, p.v_pool.stride_tok),
                                         std::max(p.k_self.stride_tok, p.v_self.stride_tok));
-    // only the pipelined kernel re-positions
-    if (rope_table && !(d == 128 && max_stride < (int64_t{1} << 24))) return DBSA_ERR_UNSUPPORTED;
+    // of the matrix kernels only the pipelined one re-positions: other shapes take the plain kernel then
+    if (rope_table && !(d == 128 && max_stride < (int64_t{1} << 24))) {
+      e = launch_prefill_plain(p, d, /*bf16_storage=*/true, static_cast<hipStream_t>(stream));
+      return e == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;
+    }
+    if (!mfma_tile_sizes_ok(L)) return DBSA_ERR_UNSUPPORTED;
+    p.heads_per_block = pick_heads_per_block(hq / hkv, L->block_m);
     // A query prefill with fewer workgroups than the chip holds (two per compute unit) cuts every
     // list into runs of at least kMinRun tiles, up to kMaxQuerySplit of them, if the caller gave the workspace.
     p.n_rows = L->n_query_tokens;
@@ -554,7 +560,6 @@ int prefill_common(const dbsa_layout* L, bool want_query_stage, dbsa_tensor q, d
             ? launch_prefill_pipelined(p, static_cast<hipStream_t>(stream))
             : launch_prefill_mfma(p, d, static_cast<hipStream_t>(stream));
   } else {
-    if (rope_table) return DBSA_ERR_UNSUPPORTED;
     e = launch_prefill_plain(p, d, /*bf16_storage=*/false, static_cast<hipStream_t>(stream));
   }
   return e == hipSuccess ? DBSA_OK : DBSA_ERR_HIP;
@@ -938,10 +943,7 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
       return DBSA_ERR_WORKSPACE;
     p.partial = static_cast<float*>(workspace);
   }
-  if (rope_table) {
-    if (!group_major) return DBSA_ERR_UNSUPPORTED;  // only the group-major kernel re-positions
-    if (!decode_ids_in_table(L, stride_query, k_selfcache.stride_tok, rope_n_pos)) return DBSA_ERR_INVALID_ARG;
-  }
+  if (rope_table && !decode_ids_in_table(L, stride_query, k_selfcache.stride_tok, rope_n_pos)) return DBSA_ERR_INVALID_ARG;
   hipError_t e = order_behind_upload(L, s);
   if (e != hipSuccess) return DBSA_ERR_HIP;
   p.decode_reverse = next_walk_direction(L);
@@ -977,6 +979,9 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
       }
       fill_decode_rows(p, L, r / p.decode_waves);
       e = launch_decode_group(p, s);
+    } else if (rope_table) {
+      // of the matrix kernels only the group-major one re-positions
+      e = launch_decode_plain(p, head_dim, /*bf16_storage=*/true, s);
     } else {
       e = launch_decode_mfma(p, head_dim, s);
       if (e == hipSuccess) e = launch_decode_merge(p, head_dim, /*out_bf16=*/true, s);

@@ -77,6 +77,7 @@ struct AttnParams {
   const float* rope_table;    // [rope_n_pos][D/2][2] fp32 (cos, sin) of id * inv_freq
   int32_t rope_n_pos;
   const int32_t* list_shift;  // [n_ent]: rotation id of row i of a Q tile for entry e = list_shift[e] + i
+  const int32_t* dec_shift;   // [n_dec_ent]: rotation id of a decode row for dec_ent entry e = dec_shift[e] + self_len - 1
   const int32_t* gm_item_run; // group-major decode: [n_gm_items][4] = (first key row, keys, queries, 0)
   const int32_t* gm_ref_pad;  // [n_gm_items][32][4] = (query, slot, shift, 0), tail repeats the last reference;
                               // rotation id of a decode row = shift + self_len - 1

@@ -181,6 +181,8 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
         new_first += gs.end - gs.begin;
       }
 
+      L->dec_shift.insert(L->dec_shift.end(), dec_shift.begin(), dec_shift.end());
+
       const Seg self{sel->cu_qlens[u], sel->cu_qlens[u + 1]};
       for (int64_t q0 = self.begin; q0 < self.end; q0 += block_m) {
         const int32_t qn = static_cast<int32_t>(std::min<int64_t>(block_m, self.end - q0));

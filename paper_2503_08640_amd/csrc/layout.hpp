@@ -22,6 +22,7 @@ struct dbsa_device_lists {
   int64_t* split_ptr = nullptr;   // [B][n_split+1]
   int64_t* gm_slot_ptr = nullptr; // [B+1]
   int32_t* list_shift = nullptr;  // [n_ent]
+  int32_t* dec_shift = nullptr;   // [n_dec_ent]
   int32_t* gm_item_run = nullptr; // [n_items][4]
   int32_t* gm_ref_pad = nullptr;  // [n_items][32][4]
   int32_t* gm_rows = nullptr;
@@ -75,6 +76,9 @@ struct dbsa_layout {
   // (a - first local index of its Q tile);  a decode row of query u scores the keys of a
   // schedule item after a rotation at id  gm_qshift[ref] + self_len[u] - 1.
   std::vector<int32_t> list_shift;  // [n_ent]
+  // the same for the per-query decode lists: the new token of a query whose cache holds n tokens (itself
+  // included) scores the keys of dec_ent entry e after a rotation at id dec_shift[e] + n - 1
+  std::vector<int32_t> dec_shift;   // [n_dec_ent]
   std::vector<int32_t> gm_qshift;   // [n_qrefs]
   std::vector<int32_t> cache_len;   // [B]: |D'| of query u = sink + its selected groups
   // what the decode kernel reads, flattened so that nothing it needs first hangs off another load:

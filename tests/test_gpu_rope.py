@@ -145,21 +145,32 @@ def test_repositioned_stage_matches_the_position_free_stage_when_ids_do_not_move
     assert_close(to_f64(got), to_f64(want), "re-positioned vs position-free on rotated inputs")
 
 
-def test_repositioned_calls_reject_what_they_do_not_implement():
+def test_repositioned_calls_reject_a_table_shorter_than_the_ids_in_use():
     pc = synth.config0_pool()                      # fp32, head_dim 64
     qc = synth.config0_query(pc)
     p = pc.pool
     lay = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, cu_qlens=qc.cu_qlens,
                               sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, block_m=64, block_n=64)
-    tab = B.dbsa_rope_table(ro.inv_freq(10000.0, 64), 1000)
-    with pytest.raises(B.DbsaError) as ei:
-        B.dbsa_query_attn_rope(lay, to_dev(qc.q), to_dev(qc.k), to_dev(qc.v), to_dev(pc.k), to_dev(pc.v), tab, pc.scale)
-    assert ei.value.code == B.DBSA_ERR_UNSUPPORTED
-    small = B.dbsa_rope_table(ro.inv_freq(10000.0, 64), 8)           # table shorter than the ids in use
+    small = B.dbsa_rope_table(ro.inv_freq(10000.0, 64), 8)
     with pytest.raises(B.DbsaError) as ei:
         B.dbsa_query_attn_rope(lay, to_dev(qc.q), to_dev(qc.k), to_dev(qc.v), to_dev(pc.k), to_dev(pc.v), small,
                                pc.scale)
     assert ei.value.code == B.DBSA_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d,block_m", [("f32", 4, 2, 64, 64), ("f32", 6, 2, 128, 32), ("bf16", 4, 2, 64, 64),
+                                                    ("bf16", 6, 2, 128, 64), ("bf16", 3, 1, 64, 32)])
+def test_repositioned_query_and_decode_on_the_shapes_of_the_plain_kernels(dtype, hq, hkv, d, block_m):
+    """fp32 storage, head_dim 64, three query heads per KV head (32 % 3 != 0: no group-major decode): the shapes
+    the matrix kernels with re-positioning do not serve run the plain fp32-arithmetic kernels, prefill and decode,
+    against the same oracle (bf16 with head_dim 128 and r = 3: the prefill is the pipelined kernel, the decode the
+    plain one)."""
+    pc = synth.make_pool_case("ropeplain", 4100 + hq + d, dtype=dtype, n_q_heads=hq, n_kv_heads=hkv, head_dim=d,
+                              sink_len=70, pool_tokens=2500, demo_len_range=(30, 120), n_groups=5)
+    sels = [[3, 0], [], [4, 1, 2, 0, 3], [2], [1, 4]]
+    qc = synth.make_query_case("ropeplainq", 4101, pc, n_queries=5, q_len=[64, 37, 70, 1, 33], selections=sels,
+                               n_decode=2)
+    _repositioned_case(pc, qc, block_m, 10000.0, decode_steps=range(2), what=f"{dtype} Hq={hq} Hkv={hkv} D={d}")
 
 
 def test_repositioned_config3_full_size():
