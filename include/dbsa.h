@@ -241,7 +241,7 @@ int dbsa_layout_export_schedule(const dbsa_layout* layout, int32_t n_classes, co
  * tiles seg_ent[first tile .. + tiles) of one run of one segment.  Every (item, query) pair of the
  * decode schedule appears in exactly one record, with the slot it has there.  row_fill = share of
  * the 64 rows of a record that carry a query, weighted by tiles: a decode step with query heads
- * in fours per KV head, no re-positioning and row_fill >= 0.22 runs these records as a dense
+ * in fours per KV head and row_fill >= 0.22 (with or without re-positioning) runs these records as a dense
  * contraction (64 queries per wavefront) instead of the 32-column work items; the partial states
  * and the merge are the same.  The array belongs to the layout.  Errors: INVALID_ARG.
  */

@@ -148,12 +148,13 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
                b_grp = L->gm_ref_pad.size() * sizeof(int32_t), b_grw = L->gm_rows.size() * sizeof(int32_t),
                b_gse = L->gm_seg_ent.size() * sizeof(int32_t), b_gqr = L->gm_qrefs.size() * sizeof(int32_t),
                b_srec = L->qtile_tab.size() * sizeof(int32_t), b_sptr = (kMaxSchedClasses + 1) * sizeof(int32_t),
-               b_mrec = L->mx_rec.size() * sizeof(int32_t), b_dsh = L->dec_shift.size() * sizeof(int32_t);
+               b_mrec = L->mx_rec.size() * sizeof(int32_t), b_dsh = L->dec_shift.size() * sizeof(int32_t),
+               b_gqs = L->gm_qshift.size() * sizeof(int32_t);
   const size_t o_tab = 0, o_ptr = o_tab + pad(b_tab), o_ent = o_ptr + pad(b_ptr), o_ord = o_ent + pad(b_ent),
                o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), o_gsp = o_spl + pad(b_spl),
                o_lsh = o_gsp + pad(b_gsp), o_gir = o_lsh + pad(b_lsh), o_grp = o_gir + pad(b_gir),
                o_grw = o_grp + pad(b_grp), o_gse = o_grw + pad(b_grw), o_gqr = o_gse + pad(b_gse),
-               o_dsh = o_gqr + pad(b_gqr), o_srec = o_dsh + pad(b_dsh), o_sptr = o_srec + pad(b_srec), o_mrec = o_sptr + pad(b_sptr),
+               o_dsh = o_gqr + pad(b_gqr), o_gqs = o_dsh + pad(b_dsh), o_srec = o_gqs + pad(b_gqs), o_sptr = o_srec + pad(b_srec), o_mrec = o_sptr + pad(b_sptr),
                o_mptr = o_mrec + pad(b_mrec), lists_end = o_srec, total = o_mptr + pad(b_sptr) + 256;
   ListBlock blk{};
   hipError_t e = acquire_block(total, &blk);
@@ -176,6 +177,7 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   put(o_gse, L->gm_seg_ent.data(), b_gse);
   put(o_gqr, L->gm_qrefs.data(), b_gqr);
   put(o_dsh, L->dec_shift.data(), b_dsh);
+  put(o_gqs, L->gm_qshift.data(), b_gqs);
   // the staging twin stays with the block, so nothing has to wait for the copy here; calls on
   // other streams are ordered behind it through the event
   hipEvent_t uploaded = nullptr;
@@ -214,6 +216,7 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   L->dev.gm_seg_ent = reinterpret_cast<int32_t*>(b + o_gse);
   L->dev.gm_qrefs = reinterpret_cast<int32_t*>(b + o_gqr);
   L->dev.dec_shift = reinterpret_cast<int32_t*>(b + o_dsh);
+  L->dev.gm_qshift = reinterpret_cast<int32_t*>(b + o_gqs);
   L->dev.sched_rec = reinterpret_cast<int32_t*>(b + o_srec);
   L->dev.sched_ptr = reinterpret_cast<int32_t*>(b + o_sptr);
   L->dev.mx_sched_rec = reinterpret_cast<int32_t*>(b + o_mrec);
@@ -959,7 +962,7 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
       // as a contraction: 64 queries per wave, four heads of a KV head as the four waves of a
       // workgroup, one workgroup per compute unit walking a balanced share of the records
       // (kernels.hpp: launch_decode_matrix_items).  Worth it once enough of the 64 rows carry a query.
-      if (r % 4 == 0 && !rope_table && L->mx_row_fill >= kMatrixRowFill) {
+      if (r % 4 == 0 && L->mx_row_fill >= kMatrixRowFill) {
         // one workgroup per compute unit, or per record where there are fewer
         const int32_t head_blocks = n_q_heads / 4;
         const bool planned = !L->mx_plan_ptr.empty() && L->compute_units / head_blocks == L->mx_plan_workers;
@@ -975,6 +978,7 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
           p.mx_ent = L->dev.gm_seg_ent;
           p.mx_classes = classes;
           p.gather_refs = L->dev.gm_qrefs;
+          p.gather_shift = L->dev.gm_qshift;
         }
       }
       fill_decode_rows(p, L, r / p.decode_waves);

@@ -971,12 +971,14 @@ hipError_t launch_decode_group(const AttnParams& p_in, hipStream_t stream) {
     g.query_stage = 0;
     g.q_split = 1;
     g.lse = nullptr;
-    g.rope_table = nullptr;
     e = launch_decode_matrix_items(g, stream);
     if (e != hipSuccess) return e;
     p.row_offset = p.gm_pool_rows;
     p.launch_rows = p.gm_n_rows - p.gm_pool_rows;
-    decode_group_kernel<false><<<decode_grid(p), dim3(64), kLdsBytes, stream>>>(p);
+    if (p.rope_table)
+      decode_group_kernel<true><<<decode_grid(p), dim3(64), kLdsBytes, stream>>>(p);
+    else
+      decode_group_kernel<false><<<decode_grid(p), dim3(64), kLdsBytes, stream>>>(p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     decode_group_merge_kernel<<<dim3(p.n_queries * p.n_q_heads), dim3(kMergeThreads), 0, stream>>>(p);

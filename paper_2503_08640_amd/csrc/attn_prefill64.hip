@@ -121,15 +121,20 @@ struct StepCfg {
 // tiles with up to 64 of the queries that selected the group, the four waves are four query heads
 // of one KV head, and the merge pass of the decode step combines the slots.
 //
-// ROPE (query prefill only): Q is un-rotated; the keys carry the rotation of the id they were encoded
+// ROPE: Q is un-rotated; the keys carry the rotation of the id they were encoded
 // with.  A row is rotated at the id list_shift[e] + (its index inside the Q tile) before it meets
 // the keys of list entry e (Sec. 2.2: the retrieved caches get new in-order positions; rotating the
 // row instead of the keys lets all queries read the same key bytes).  Entries of one segment share
 // the shift, so the fragments are rebuilt only where it changes, from the rows in memory.
+// With GATHER (decode step) a record lies inside one segment, so its rows are rotated once, at the record's
+// start, each at its own id gather_shift[reference] + self_len[query] - 1.
 template <int NW, int SL, bool SELF, bool PERSIST, bool GATHER = false, bool ROPE = false>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_prefill64_kernel(AttnParams p) {
   static_assert(!GATHER || (PERSIST && !SELF), "gathered rows come with a schedule and pool tiles only");
-  static_assert(!ROPE || (SELF && !GATHER), "rows are re-positioned at the query prefill only");
+  static_assert(!ROPE || (SELF != GATHER), "rows are re-positioned at the query prefill and at the decode step");
+  // the query prefill rotates a Q tile per list entry (the ids ride with the entries); gathered rows are
+  // rotated once per record, each at its own id
+  constexpr bool kEntryIds = ROPE && !GATHER;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   constexpr int kBlocksPerWave = 16 / NW;  // 1-KiB load blocks of one operand per wave
   constexpr int KS = 2 + SL, VS = 1 + SL;  // LDS stages of K and of V
@@ -285,7 +290,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
   // its last entry: every period loads one K and one V tile, the last ones into stages nobody
   // reads any more, so that the waits can count on a fixed number of loads in flight.
   const_words f_ent = all_ent + 2 * static_cast<int64_t>(e0);
-  const_words f_sh = all_shift + (ROPE ? static_cast<int64_t>(e0) : 0);  // ROPE: the entries' rotation ids, in step with f_ent
+  const_words f_sh = all_shift + (kEntryIds ? static_cast<int64_t>(e0) : 0);  // the entries' rotation ids, in step with f_ent
   int f_left = n_tiles, f_k = rec_k;
   int nx_e0 = 0, nx_n = 0;  // PERSIST: list of record f_k + 1 (requested when the stream entered record f_k)
   if constexpr (PERSIST) {
@@ -300,7 +305,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
       if (PERSIST && f_k + 1 < rec_end) {
         f_k += 1;
         f_ent = all_ent + 2 * static_cast<int64_t>(nx_e0);
-        if constexpr (ROPE) f_sh = all_shift + static_cast<int64_t>(nx_e0);
+        if constexpr (kEntryIds) f_sh = all_shift + static_cast<int64_t>(nx_e0);
         f_left = nx_n;
         if (f_k + 1 < rec_end) {
           nx_e0 = sched[4 * (f_k + 1) + 2];
@@ -308,14 +313,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
         }
       } else {
         f_ent -= 2;
-        if constexpr (ROPE) f_sh -= 1;
+        if constexpr (kEntryIds) f_sh -= 1;
         f_left = 1;
       }
     }
     in_w0 = f_ent[0];
     in_w1 = f_ent[1];
     f_ent += 2;
-    if constexpr (ROPE) {
+    if constexpr (kEntryIds) {
       in_w2 = f_sh[0];
       f_sh += 1;
     }
@@ -346,6 +351,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
   const float c2 = p.scale_log2e;
   int head[2], row_local[2], row_tok[2], q_pos[2];
   int row_slot[2] = {0, 0};  // GATHER: where the row's partial state goes
+  int row_rot[2] = {0, 0};   // GATHER with ROPE: the row's rotation id
   bool row_valid[2];
   auto place_rows = [&]() DBSA_INLINE {
 #pragma unroll
@@ -360,6 +366,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
         // (rows past the last reference repeat it: they compute on its row and store nothing)
         typedef int intx2 __attribute__((ext_vector_type(2)));
         const intx2 ref = *reinterpret_cast<const intx2*>(p.gather_refs + 2 * static_cast<int64_t>(row_tok[rb]));
+        if constexpr (ROPE)  // the decode row of query ref[0] sits at index self_len - 1 of its own cache
+          row_rot[rb] = p.gather_shift[row_tok[rb]] + p.self_len[ref[0]] - 1;
         row_tok[rb] = ref[0];
         row_slot[rb] = ref[1];
       }
@@ -411,7 +419,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
     for (int rb = 0; rb < 2; ++rb) {
       const __bf16* qp = static_cast<const __bf16*>(p.q.ptr) + static_cast<int64_t>(row_tok[rb]) * p.q.stride_tok +
                          static_cast<int64_t>(head[rb]) * p.q.stride_head + 8 * half;
-      const int id = min(max(shift + row_local[rb], 0), p.rope_n_pos - 1);
+      const int id = min(max(GATHER ? row_rot[rb] : shift + row_local[rb], 0), p.rope_n_pos - 1);
       const float* rot = p.rope_table + static_cast<int64_t>(id) * kD + 16 * half;
       bf16x8 frag[kD / 16];
       load_query_fragments<true>(qp, rot, c2, frag);
@@ -700,11 +708,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
     for (int i = 0; i < 1 + SL; ++i) {
       rw0[i] = rw0[i + 1];
       rw1[i] = rw1[i + 1];
-      if constexpr (ROPE) rw2[i] = rw2[i + 1];
+      if constexpr (kEntryIds) rw2[i] = rw2[i + 1];
     }
     rw0[1 + SL] = in_w0;
     rw1[1 + SL] = in_w1;
-    if constexpr (ROPE) rw2[1 + SL] = in_w2;
+    if constexpr (kEntryIds) rw2[1 + SL] = in_w2;
     k_wr = (k_wr + 1 == KS) ? 0 : k_wr + 1;
     v_wr = (v_wr + 1 == VS) ? 0 : v_wr + 1;
   };
@@ -721,7 +729,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
   for (;;) {
     // ---- a Q tile: its rows of Q are in q_raw (requested before the previous tile's epilogue) ----
     if constexpr (ROPE)
-      rotate_q(rw2[0]);
+      rotate_q(kEntryIds ? rw2[0] : 0);
     else
       scale_q();
     int nq_start = 0, nq_len = 0, nq_e0 = 0, nq_n = 0;  // PERSIST: the record after this one
@@ -767,7 +775,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(1, 1)))
       request_entry();  // before the barrier, whose wait covers the entry's latency
       period_barrier();
       const TileRef tq = decode_ref(rw0[0], rw1[0]);
-      if constexpr (ROPE) {
+      if constexpr (kEntryIds) {
         // this period computes the scores of an entry of another segment: rebuild Q for it (every matrix
         // instruction that read the old fragments was issued a period ago)
         if (__builtin_expect(rw2[0] != cur_shift, 0)) rotate_q(rw2[0]);
@@ -974,5 +982,9 @@ hipError_t launch_decode_matrix_items(const AttnParams& p, hipStream_t stream) {
   if (!p.sched_rec || !p.sched_ptr || !p.gather_refs || !p.partial || p.sched_classes < 1) return hipErrorInvalidValue;
   if (p.heads_per_block != 4 || p.block_m != 64 || p.n_q_heads % (4 * p.n_kv_heads) != 0 || p.n_head_blocks != p.n_q_heads / 4)
     return hipErrorInvalidValue;
+  if (p.rope_table) {
+    if (!p.gather_shift || !p.self_len) return hipErrorInvalidValue;
+    return launch_cfg64<4, 2, false, true, true, true>(p, stream);
+  }
   return launch_cfg64<4, 2, false, true, true>(p, stream);
 }

@@ -64,6 +64,7 @@ struct AttnParams {
   int32_t sched_classes, n_head_blocks;
   // rows gathered through references (launch_decode_matrix_items): [n_refs][2] = (row of q, partial slot)
   const int32_t* gather_refs;
+  const int32_t* gather_shift;  // [n_refs]: with re-positioning, rotation id of reference i's row = gather_shift[i] + self_len - 1
   // decode step: 1 = the pool items run as a contraction through launch_decode_matrix_items with the
   // schedule mx_sched_* over list entries mx_ent, the self items in the ordinary kernel (gm_rows then
   // holds the table of single-wave workgroups)

@@ -23,6 +23,7 @@ struct dbsa_device_lists {
   int64_t* gm_slot_ptr = nullptr; // [B+1]
   int32_t* list_shift = nullptr;  // [n_ent]
   int32_t* dec_shift = nullptr;   // [n_dec_ent]
+  int32_t* gm_qshift = nullptr;   // [n_qrefs]
   int32_t* gm_item_run = nullptr; // [n_items][4]
   int32_t* gm_ref_pad = nullptr;  // [n_items][32][4]
   int32_t* gm_rows = nullptr;

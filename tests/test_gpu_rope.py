@@ -96,8 +96,8 @@ def test_repositioned_query_and_decode_small(hq, hkv, block_m, base):
 
 @pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 2), (16, 2)])
 def test_repositioned_decode_with_many_queries_per_group(hq, hkv):
-    """40 queries on 3 groups: every group serves several batches of 32 / r queries, so the
-    decode step runs the kernel whose waves share an item's tiles (2 or 4 waves per workgroup)."""
+    """40 queries on 3 groups: every group serves several batches of 32 / r queries, so the decode step runs the
+    kernel whose waves share an item's tiles (r = 2) or, with query heads in fours per KV head, the contraction."""
     # (channel scales of sigma 0.35: with 0.5 one of the 16 heads of the third case gets scores beyond +-60,
     # where rounding the rotated, pre-scaled Q to bf16 alone moves single outputs by up to 2e-2, the whole
     # tolerance; the kernels agree with each other there to 7e-3)
@@ -105,6 +105,13 @@ def test_repositioned_decode_with_many_queries_per_group(hq, hkv):
                               sink_len=40, pool_tokens=2500, demo_len_range=(30, 120), n_groups=3,
                               k_channel_sigma=0.35)
     qc = synth.make_query_case("ropemanyq", 4021, pc, n_queries=40, q_len=9, n_select=2, n_decode=2)
+    if (hq // hkv) % 4 == 0:
+        # query heads in fours per KV head and 27 of 64 rows filled: the pool items run as the contraction, whose
+        # rows are rotated once per record, each at its own id
+        p = pc.pool
+        host = B.dbsa_layout_build(p.sink_len, p.demo_offsets, p.group_demo_offsets, pc.prev_window, cu_qlens=qc.cu_qlens,
+                                   sel_ptr=qc.sel_ptr, sel_idx=qc.sel_idx, n_split=0, block_m=32, block_n=64, host_only=True)
+        assert host.export_matrix_records()[1] >= 0.22
     _repositioned_case(pc, qc, 32, 10000.0, decode_steps=range(2), what=f"many queries Hq={hq} Hkv={hkv}")
 
 
