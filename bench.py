@@ -162,6 +162,8 @@ def config4_sweep(torch, B, pc, k, v, iters: int = 20):
         return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
 
     rows = []
+    # rotary table for the re-positioned decode step (timing only: the keys are used as they are)
+    tab = B.dbsa_rope_table(500000.0 ** (-np.arange(0, d, 2, dtype=np.float64) / d), 2 * p.n_tokens + 256)
     for ratio in synth.RETRIEVAL_RATIOS:
         qc = synth.config4_query(pc, ratio)
         qs, ks, vs = dev(qc.q), dev(qc.k), dev(qc.v)
@@ -181,6 +183,8 @@ def config4_sweep(torch, B, pc, k, v, iters: int = 20):
                (lambda: B.dbsa_decode_attn(lay, dq[0], kc, vc, self_len, k, v, pc.scale, out=od, workspace=ws),
                 max(5 * iters, MIN_STAGE_LAUNCHES)))]
         ms = [x["median_ms"] for x in st]
+        rope_ms = stats(launch_samples(torch, lambda: B.dbsa_decode_attn_rope(lay, dq[0], kc, vc, self_len, k, v, tab, pc.scale,
+                                                                              out=od, workspace=ws), MIN_STAGE_LAUNCHES))["median_ms"]
         keys = selected_keys(p, qc)
         flops = 4.0 * d * hq * float((lens * keys).sum() + (lens * (lens + 1) // 2).sum())
         # a decode row scores and weighs every key it attends: 4 D flops per (query head, key)
@@ -190,7 +194,7 @@ def config4_sweep(torch, B, pc, k, v, iters: int = 20):
         unique_bytes = (union + float((lens + 1).sum())) * hkv * d * 2 * 2
         rows.append({"retrieval_ratio": ratio, "groups_per_query": int(qc.sel_ptr[1]), "mean_keys_per_query": float(keys.mean()),
                      "query_prefill_ms": ms[0], "query_prefill_useful_tflops": flops / ms[0] / 1e9,
-                     "decode_step_ms": ms[1],
+                     "decode_step_ms": ms[1], "decode_step_repositioned_ms": rope_ms,
                      "decode_useful_tflops": flops_dec / ms[1] / 1e9,
                      "decode_frac_of_mfma_peak": flops_dec / ms[1] / 1e9 / PEAK_BF16_TFLOPS,
                      "decode_unique_gbs": unique_bytes / ms[1] / 1e6,
