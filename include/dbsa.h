@@ -199,17 +199,12 @@ int dbsa_layout_export_positions(const dbsa_layout* layout, const int32_t** list
  *               segments ascending (those with a user), runs ascending (a segment of t
  *               tiles is cut into n = ceil(t / chunk_tiles) runs of equal length to within
  *               one tile, run i = tiles [i t / n, (i+1) t / n)), users in ascending query
- *               order in batches of 32.  The sink's users are all queries.  A layout whose
- *               contraction records would fill 22 % of their rows (row_fill of
- *               dbsa_layout_export_matrix_records) cuts runs to measure instead
- *               (dbsa_layout_export_matrix_plan): per segment, batch of 64 users by batch,
- *               the runs of that batch in order, each with its one or two items of 32.
+ *               order in batches of 32.  The sink's users are all queries.
  *   qrefs     : int32 [n_qrefs][2] = (query, slot).
  *   slot_ptr  : int64 [B+1]: slots of query u are slot_ptr[u] .. slot_ptr[u+1]-1, numbered
  *               in item order; the last one is the own-cache slot.
  *   chunk_tiles: most tiles per run: ceil(longest segment with a user / n_split) when the
- *               caller gave n_split > 0, else chosen by the library (at most 32; the longest
- *               run where runs are cut to measure).
+ *               caller gave n_split > 0, else chosen by the library (at most 32).
  */
 int dbsa_layout_export_decode_groups(const dbsa_layout* layout, const int64_t** seg_ptr, const int32_t** seg_ent,
                                      int64_t* n_seg_ent, const int32_t** items, int64_t* n_items,
@@ -235,30 +230,37 @@ int dbsa_layout_export_schedule(const dbsa_layout* layout, int32_t n_classes, co
                                 const int32_t** records);
 
 /*
- * The decode schedule's work items with up to 64 queries each (plumbing; query-stage layouts):
- * record i = four int32 (first reference, references, first tile, tiles): the queries
- * qrefs[first reference .. + references) of dbsa_layout_export_decode_groups, at most 64, over the
- * tiles seg_ent[first tile .. + tiles) of one run of one segment.  Every (item, query) pair of the
- * decode schedule appears in exactly one record, with the slot it has there.  row_fill = share of
- * the 64 rows of a record that carry a query, weighted by tiles: a decode step with query heads
- * in fours per KV head and row_fill >= 0.22 (with or without re-positioning) runs these records as a dense
- * contraction (64 queries per wavefront) instead of the 32-column work items; the partial states
- * and the merge are the same.  The array belongs to the layout.  Errors: INVALID_ARG.
+ * The records of a decode step that runs as a contraction (plumbing; query-stage layouts): record i =
+ * four int32 (first reference, references, first tile, tiles): at most 64 queries over the tiles
+ * seg_ent[first tile .. + tiles) of one run of one segment.  row_fill = share of the 64 rows of a
+ * record that carry a query, weighted by tiles: a decode step with query heads in fours per KV head and
+ * row_fill >= 0.22 (with or without re-positioning) runs these records as a dense contraction (64
+ * queries per wavefront) instead of the 32-column work items, into partial states that the same merge
+ * combines.
+ * Below that fill the records are the work items' runs taken in pairs: the references are qrefs of
+ * dbsa_layout_export_decode_groups and every (item, query) pair appears in exactly one record with
+ * the slot it has there.  From that fill on the records have runs, references and slots of their own,
+ * see dbsa_layout_export_matrix_plan.  The array belongs to the layout.  Errors: INVALID_ARG.
  */
 int dbsa_layout_export_matrix_records(const dbsa_layout* layout, const int32_t** records, int64_t* n_records,
                                       float* row_fill);
 
 /*
- * How a layout with row_fill >= 0.22 deals the records above to the workers of a contraction step
- * (plumbing).  Such a layout cuts its runs to measure at build time: the (segment, 64 queries) units
- * are laid end to end and cut into equal shares for `nominal_workers` = compute units / 8 workers per
- * KV head (fewer shares when one would hold under 12 tiles); worker c of a step whose compute units
- * per head block equal nominal_workers takes records plan_ptr[c] .. plan_ptr[c+1]-1 (n_workers + 1
- * entries).  Other layouts, and steps with another worker count, deal runs of one length at launch:
- * n_workers = 0.  The array belongs to the layout.  Errors: INVALID_ARG.
+ * How a layout with row_fill >= 0.22 cuts and deals the records above (plumbing).  At build time the
+ * (segment, 64 queries) units are walked in order and dealt to `nominal_workers` = compute units / 8
+ * workers per KV head (fewer when a worker's share would hold under 12 tiles), each taking tiles until
+ * its cost (tiles + 4.5 per run) reaches the share; a unit that does not fit is cut there, no run is
+ * shorter than 4 tiles.  Worker c of a step whose compute units per head block equal nominal_workers
+ * takes records plan_ptr[c] .. plan_ptr[c+1]-1 (n_workers + 1 entries); a step with another worker
+ * count deals the same records at launch.  qrefs: int32 [n_qrefs][2] = (query, slot), the references
+ * of the records; slot_ptr: int64 [B+1], slots of query u are slot_ptr[u] .. slot_ptr[u+1]-1 in
+ * record order, the last one its own-cache slot (a contraction step uses these slots, every other step
+ * those of dbsa_layout_export_decode_groups; dbsa_workspace_bytes covers both).  Layouts below that
+ * fill have no plan: n_workers = 0, n_qrefs = 0.  The arrays belong to the layout.  Errors: INVALID_ARG.
  */
 int dbsa_layout_export_matrix_plan(const dbsa_layout* layout, const int32_t** plan_ptr, int32_t* n_workers,
-                                   int32_t* nominal_workers);
+                                   int32_t* nominal_workers, const int32_t** qrefs, int64_t* n_qrefs,
+                                   const int64_t** slot_ptr);
 
 /*
  * Device blocks (each with a pinned host twin) that hold the lists of destroyed layouts and wait

@@ -113,7 +113,8 @@ def lib() -> C.CDLL:
                                                     C.POINTER(C.c_float)]
     L.dbsa_layout_export_matrix_plan.restype = C.c_int
     L.dbsa_layout_export_matrix_plan.argtypes = [C.c_void_p, C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int32),
-                                                 C.POINTER(C.c_int32)]
+                                                 C.POINTER(C.c_int32), C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_int64),
+                                                 C.POINTER(C.POINTER(C.c_int64))]
     L.dbsa_pooled_list_blocks.restype = C.c_int32
     L.dbsa_pooled_list_blocks.argtypes = []
     L.dbsa_layout_destroy.restype = None
@@ -257,13 +258,19 @@ class Layout:
         rec = np.ctypeslib.as_array(rp, shape=(n.value, 4)).copy() if n.value else np.zeros((0, 4), np.int32)
         return rec, float(fill.value)
 
-    def export_matrix_plan(self):
-        """-> (plan_ptr [n_workers + 1] int32 copy, or an empty array when records are dealt at launch; nominal workers)."""
+    def export_matrix_plan(self, n_queries: int = None):
+        """-> (plan_ptr [n_workers + 1] int32 copy, or an empty array when records are dealt at launch; nominal workers)
+        [, qrefs [n, 2], slot_ptr [n_queries + 1]: the references and slots of the plan's records, when n_queries is given]."""
         pp, n, nominal = C.POINTER(C.c_int32)(), C.c_int32(), C.c_int32()
-        _check(lib().dbsa_layout_export_matrix_plan(self.handle, C.byref(pp), C.byref(n), C.byref(nominal)),
-               "dbsa_layout_export_matrix_plan")
+        qp, nq, sp = C.POINTER(C.c_int32)(), C.c_int64(), C.POINTER(C.c_int64)()
+        _check(lib().dbsa_layout_export_matrix_plan(self.handle, C.byref(pp), C.byref(n), C.byref(nominal), C.byref(qp),
+                                                    C.byref(nq), C.byref(sp)), "dbsa_layout_export_matrix_plan")
         ptr = np.ctypeslib.as_array(pp, shape=(n.value + 1,)).copy() if n.value else np.zeros(0, np.int32)
-        return ptr, int(nominal.value)
+        if n_queries is None:
+            return ptr, int(nominal.value)
+        qrefs = np.ctypeslib.as_array(qp, shape=(nq.value, 2)).copy() if nq.value else np.zeros((0, 2), np.int32)
+        slots = np.ctypeslib.as_array(sp, shape=(n_queries + 1,)).copy() if nq.value else np.zeros(0, np.int64)
+        return ptr, int(nominal.value), qrefs, slots
 
     def export_schedule(self, n_classes: int):
         """-> (class_ptr [n_classes+1], records [n_qtiles, 4]) int32 copies."""

@@ -149,12 +149,14 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
                b_gse = L->gm_seg_ent.size() * sizeof(int32_t), b_gqr = L->gm_qrefs.size() * sizeof(int32_t),
                b_srec = L->qtile_tab.size() * sizeof(int32_t), b_sptr = (kMaxSchedClasses + 1) * sizeof(int32_t),
                b_mrec = L->mx_rec.size() * sizeof(int32_t), b_dsh = L->dec_shift.size() * sizeof(int32_t),
-               b_gqs = L->gm_qshift.size() * sizeof(int32_t);
+               b_gqs = L->gm_qshift.size() * sizeof(int32_t), b_mqr = L->mx_qrefs.size() * sizeof(int32_t),
+               b_mqs = L->mx_qshift.size() * sizeof(int32_t), b_msp = L->mx_slot_ptr.size() * sizeof(int64_t);
   const size_t o_tab = 0, o_ptr = o_tab + pad(b_tab), o_ent = o_ptr + pad(b_ptr), o_ord = o_ent + pad(b_ent),
                o_dec = o_ord + pad(b_ord), o_spl = o_dec + pad(b_dec), o_gsp = o_spl + pad(b_spl),
                o_lsh = o_gsp + pad(b_gsp), o_gir = o_lsh + pad(b_lsh), o_grp = o_gir + pad(b_gir),
                o_grw = o_grp + pad(b_grp), o_gse = o_grw + pad(b_grw), o_gqr = o_gse + pad(b_gse),
-               o_dsh = o_gqr + pad(b_gqr), o_gqs = o_dsh + pad(b_dsh), o_srec = o_gqs + pad(b_gqs), o_sptr = o_srec + pad(b_srec), o_mrec = o_sptr + pad(b_sptr),
+               o_dsh = o_gqr + pad(b_gqr), o_gqs = o_dsh + pad(b_dsh), o_mqr = o_gqs + pad(b_gqs), o_mqs = o_mqr + pad(b_mqr), o_msp = o_mqs + pad(b_mqs),
+               o_srec = o_msp + pad(b_msp), o_sptr = o_srec + pad(b_srec), o_mrec = o_sptr + pad(b_sptr),
                o_mptr = o_mrec + pad(b_mrec), lists_end = o_srec, total = o_mptr + pad(b_sptr) + 256;
   ListBlock blk{};
   hipError_t e = acquire_block(total, &blk);
@@ -178,6 +180,9 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   put(o_gqr, L->gm_qrefs.data(), b_gqr);
   put(o_dsh, L->dec_shift.data(), b_dsh);
   put(o_gqs, L->gm_qshift.data(), b_gqs);
+  put(o_mqr, L->mx_qrefs.data(), b_mqr);
+  put(o_mqs, L->mx_qshift.data(), b_mqs);
+  put(o_msp, L->mx_slot_ptr.data(), b_msp);
   // the staging twin stays with the block, so nothing has to wait for the copy here; calls on
   // other streams are ordered behind it through the event
   hipEvent_t uploaded = nullptr;
@@ -217,6 +222,9 @@ hipError_t upload_lists(dbsa_layout* L, hipStream_t stream) {
   L->dev.gm_qrefs = reinterpret_cast<int32_t*>(b + o_gqr);
   L->dev.dec_shift = reinterpret_cast<int32_t*>(b + o_dsh);
   L->dev.gm_qshift = reinterpret_cast<int32_t*>(b + o_gqs);
+  L->dev.mx_qrefs = reinterpret_cast<int32_t*>(b + o_mqr);
+  L->dev.mx_qshift = reinterpret_cast<int32_t*>(b + o_mqs);
+  L->dev.mx_slot_ptr = reinterpret_cast<int64_t*>(b + o_msp);
   L->dev.sched_rec = reinterpret_cast<int32_t*>(b + o_srec);
   L->dev.sched_ptr = reinterpret_cast<int32_t*>(b + o_sptr);
   L->dev.mx_sched_rec = reinterpret_cast<int32_t*>(b + o_mrec);
@@ -420,7 +428,8 @@ int64_t workgroup_slots(const dbsa_layout* L) { return 2 * static_cast<int64_t>(
 // bytes of partial states one decode step writes: the larger of its two schedules
 size_t decode_workspace_need(const dbsa_layout* L, int32_t n_q_heads, int32_t head_dim) {
   const size_t slots = std::max<size_t>(static_cast<size_t>(L->n_queries) * L->n_split,
-                                        L->gm_slot_ptr.empty() ? 0 : static_cast<size_t>(L->gm_slot_ptr.back()));
+                                        std::max<size_t>(L->gm_slot_ptr.empty() ? 0 : static_cast<size_t>(L->gm_slot_ptr.back()),
+                                                   L->mx_slot_ptr.empty() ? 0 : static_cast<size_t>(L->mx_slot_ptr.back())));
   return slots * n_q_heads * (head_dim + kPartialPad) * sizeof(float);
 }
 
@@ -707,11 +716,15 @@ int dbsa_layout_export_schedule(const dbsa_layout* L, int32_t n_classes, const i
 }
 
 int dbsa_layout_export_matrix_plan(const dbsa_layout* L, const int32_t** plan_ptr, int32_t* n_workers,
-                                   int32_t* nominal_workers) {
+                                   int32_t* nominal_workers, const int32_t** qrefs, int64_t* n_qrefs,
+                                   const int64_t** slot_ptr) {
   if (!L || !L->query_stage) return DBSA_ERR_INVALID_ARG;
   if (plan_ptr) *plan_ptr = L->mx_plan_ptr.data();
   if (n_workers) *n_workers = L->mx_plan_ptr.empty() ? 0 : static_cast<int32_t>(L->mx_plan_ptr.size()) - 1;
   if (nominal_workers) *nominal_workers = L->mx_plan_workers;
+  if (qrefs) *qrefs = L->mx_qrefs.data();
+  if (n_qrefs) *n_qrefs = static_cast<int64_t>(L->mx_qrefs.size() / 2);
+  if (slot_ptr) *slot_ptr = L->mx_slot_ptr.data();
   return DBSA_OK;
 }
 
@@ -737,7 +750,8 @@ void dbsa_layout_destroy(dbsa_layout* L) {
 size_t dbsa_workspace_bytes(const dbsa_layout* L, int32_t n_q_heads, int32_t head_dim) {
   if (!L || !L->query_stage || n_q_heads <= 0 || head_dim <= 0) return 0;
   size_t slots = std::max<size_t>(static_cast<size_t>(L->n_queries) * L->n_split,
-                                  L->gm_slot_ptr.empty() ? 0 : static_cast<size_t>(L->gm_slot_ptr.back()));
+                                  std::max<size_t>(L->gm_slot_ptr.empty() ? 0 : static_cast<size_t>(L->gm_slot_ptr.back()),
+                                                   L->mx_slot_ptr.empty() ? 0 : static_cast<size_t>(L->mx_slot_ptr.back())));
   // a split query prefill keeps up to kMaxQuerySplit partial states per row; it is only used when
   // the launch has fewer workgroups than the chip holds, which bounds the number of Q tiles
   if (L->n_qtiles() < workgroup_slots(L)) slots = std::max<size_t>(slots, static_cast<size_t>(L->n_query_tokens) * kMaxQuerySplit);
@@ -977,8 +991,12 @@ int decode_common(const dbsa_layout* L, dbsa_tensor q_step, dbsa_tensor k_selfca
           p.mx_sched_ptr = L->dev.mx_sched_ptr;
           p.mx_ent = L->dev.gm_seg_ent;
           p.mx_classes = classes;
-          p.gather_refs = L->dev.gm_qrefs;
-          p.gather_shift = L->dev.gm_qshift;
+          // a layout with a plan has references and slots of its own for these records: the own-cache items
+          // and the merge then go by its slot table too
+          const bool own = !L->mx_plan_ptr.empty();
+          p.gather_refs = own ? L->dev.mx_qrefs : L->dev.gm_qrefs;
+          p.gather_shift = own ? L->dev.mx_qshift : L->dev.gm_qshift;
+          if (own) p.gm_slot_ptr = L->dev.mx_slot_ptr;
         }
       }
       fill_decode_rows(p, L, r / p.decode_waves);

@@ -210,6 +210,12 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
     }
   }
 
+  // runs cut to measure for the steps that run as a contraction (below): [segment][batch of 64 users] -> run
+  // boundaries, the segments' users, the rotation shift of (query, segment), the share of rows that carry a query
+  std::vector<std::vector<std::vector<int64_t>>> plan_cuts;
+  std::vector<std::vector<int32_t>> plan_users;
+  std::vector<int32_t> plan_shift;
+  float plan_fill = 0.f;
   if (sel) {
     // ---- group-major decode schedule ----
     // Queries that selected the same group read the same KV, so at decode a chunk of a
@@ -254,9 +260,8 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
     // its cost (tiles + kRunCost per run, what starting and finishing a run costs in tiles) reaches the
     // mean; a unit that does not fit is cut there, but no run is shorter than kSnap tiles: a worker
     // rather stops a little early or takes the few tiles that are left.  Worker c takes the runs
-    // mx_plan_ptr[c] .. mx_plan_ptr[c+1]-1, in order.  cuts[s][b] = the run boundaries of the b-th
+    // mx_plan_ptr[c] .. mx_plan_ptr[c+1]-1, in order.  plan_cuts[s][b] = the run boundaries of the b-th
     // batch of 64 queries of segment s.
-    std::vector<std::vector<std::vector<int64_t>>> cuts;
     if (sel->n_split == 0) {
       double rows = 0.0, used = 0.0;
       int64_t line = 0, n_units = 0;
@@ -277,7 +282,7 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
         int64_t n_rec = 0, longest = 1;
         // one walk for a given share; returns what is left for the last worker, who takes the rest
         auto deal = [&](double target) {
-          cuts.assign(static_cast<size_t>(G) + 1, {});
+          plan_cuts.assign(static_cast<size_t>(G) + 1, {});
           L->mx_plan_ptr.assign(1, 0);
           n_rec = 0;
           longest = 1;
@@ -314,7 +319,7 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
               }
               bounds.push_back(t0 + t);
               n_rec += 1;
-              cuts[static_cast<size_t>(s)].push_back(std::move(bounds));
+              plan_cuts[static_cast<size_t>(s)].push_back(std::move(bounds));
             }
           }
           const double last_cost = static_cast<int64_t>(L->mx_plan_ptr.size()) >= workers ? acc : 0.0;
@@ -335,7 +340,7 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
           (deal(mid) <= mid + static_cast<double>(kSnap) ? hi : lo) = mid;
         }
         deal(hi);
-        chunk = longest;
+        plan_fill = static_cast<float>(used / rows);
       }
     }
     L->gm_chunk_tiles = static_cast<int32_t>(chunk);
@@ -361,32 +366,6 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
       for (int32_t s = 0; s <= G; ++s) {
         const int64_t t0 = L->gm_seg_ptr[s], t1 = L->gm_seg_ptr[s + 1];
         if (users[s].empty()) continue;
-        if (!cuts.empty()) {
-          // runs cut to measure: batch of 64 queries by batch, run by run, its one or two items of 32
-          const auto& per_batch = cuts[static_cast<size_t>(s)];
-          for (size_t b = 0; b < per_batch.size(); ++b)
-            for (size_t run = 0; run + 1 < per_batch[b].size(); ++run) {
-              const int64_t c0 = per_batch[b][run], c1 = per_batch[b][run + 1];
-              for (size_t b0 = 64 * b; b0 < std::min(users[s].size(), 64 * b + 64); b0 += kItemQueries) {
-                const size_t b1 = std::min(users[s].size(), b0 + kItemQueries);
-                if (pass == 1)
-                  L->gm_items.insert(L->gm_items.end(),
-                                     {static_cast<int32_t>(c0), static_cast<int32_t>(c1 - c0),
-                                      static_cast<int32_t>(L->gm_qrefs.size() / 2), static_cast<int32_t>(b1 - b0)});
-                for (size_t k = b0; k < b1; ++k) {
-                  const int32_t u = users[s][k];
-                  if (pass == 0)
-                    ++n_slots[u];
-                  else {
-                    L->gm_qrefs.push_back(u);
-                    L->gm_qrefs.push_back(static_cast<int32_t>(L->gm_slot_ptr[u] + next[u]++));
-                    L->gm_qshift.push_back(seg_shift[static_cast<size_t>(u) * (G + 1) + s]);
-                  }
-                }
-              }
-            }
-          continue;
-        }
         // the segment's tiles are cut into ceil(tiles / chunk) runs of equal length (to within one
         // tile): a short last run would leave its workgroup idle while the full ones finish
         const int64_t n_runs = (t1 - t0 + chunk - 1) / chunk;
@@ -412,13 +391,50 @@ int dbsa_build_host_lists(const dbsa_pool_desc* pool, const dbsa_select_desc* se
         }
       }
     }
+    if (!plan_cuts.empty()) {
+      plan_users = users;
+      plan_shift = seg_shift;
+    }
   }
 
   for (size_t i = 3; i < L->gm_items.size(); i += 4) L->gm_max_queries = std::max(L->gm_max_queries, L->gm_items[i]);
   for (const int32_t shift : L->gm_qshift) L->max_decode_shift = std::max<int64_t>(L->max_decode_shift, shift);
-  // The same runs with up to 64 queries each: consecutive items of one run (its batches of 32
-  // queries, whose references follow each other) are taken in pairs.  Slots do not change.
-  {
+  if (!plan_cuts.empty()) {
+    // Records of the runs cut to measure, with references and slots of their own (the work items above keep
+    // their runs of one length for the steps that do not run as a contraction): per unit, run by run, the
+    // unit's users with one slot each; a query's last slot is again its own cache.
+    const int32_t B = L->n_queries;
+    std::vector<int64_t> n_slots(static_cast<size_t>(B), 0), next(static_cast<size_t>(B), 0);
+    for (int pass = 0; pass < 2; ++pass) {
+      if (pass == 1) {
+        L->mx_slot_ptr.assign(static_cast<size_t>(B) + 1, 0);
+        for (int32_t u = 0; u < B; ++u) L->mx_slot_ptr[u + 1] = L->mx_slot_ptr[u] + n_slots[u] + 1;
+      }
+      for (size_t s = 0; s < plan_cuts.size(); ++s)
+        for (size_t b = 0; b < plan_cuts[s].size(); ++b)
+          for (size_t run = 0; run + 1 < plan_cuts[s][b].size(); ++run) {
+            const size_t b0 = 64 * b, b1 = std::min(plan_users[s].size(), b0 + 64);
+            if (pass == 1)
+              L->mx_rec.insert(L->mx_rec.end(),
+                               {static_cast<int32_t>(L->mx_qrefs.size() / 2), static_cast<int32_t>(b1 - b0),
+                                static_cast<int32_t>(plan_cuts[s][b][run]),
+                                static_cast<int32_t>(plan_cuts[s][b][run + 1] - plan_cuts[s][b][run])});
+            for (size_t k = b0; k < b1; ++k) {
+              const int32_t u = plan_users[s][k];
+              if (pass == 0) {
+                ++n_slots[static_cast<size_t>(u)];
+              } else {
+                L->mx_qrefs.push_back(u);
+                L->mx_qrefs.push_back(static_cast<int32_t>(L->mx_slot_ptr[u] + next[static_cast<size_t>(u)]++));
+                L->mx_qshift.push_back(plan_shift[static_cast<size_t>(u) * plan_cuts.size() + s]);
+              }
+            }
+          }
+    }
+    L->mx_row_fill = plan_fill;
+  } else {
+    // No plan: the work items' runs with up to 64 queries each: consecutive items of one run (its batches of
+    // 32 queries, whose references follow each other) are taken in pairs.  Slots do not change.
     const size_t n_items = L->gm_items.size() / 4;
     double rows = 0.0, used = 0.0;
     for (size_t it = 0; it < n_items; ++it) {

@@ -24,6 +24,9 @@ struct dbsa_device_lists {
   int32_t* list_shift = nullptr;  // [n_ent]
   int32_t* dec_shift = nullptr;   // [n_dec_ent]
   int32_t* gm_qshift = nullptr;   // [n_qrefs]
+  int32_t* mx_qrefs = nullptr;    // [n_mx_qrefs][2]
+  int32_t* mx_qshift = nullptr;   // [n_mx_qrefs]
+  int64_t* mx_slot_ptr = nullptr; // [B+1]
   int32_t* gm_item_run = nullptr; // [n_items][4]
   int32_t* gm_ref_pad = nullptr;  // [n_items][32][4]
   int32_t* gm_rows = nullptr;
@@ -94,17 +97,21 @@ struct dbsa_layout {
   int32_t gm_rows_off[7] = {0, 0, 0, 0, 0, 0, 0};   // table k is gm_rows[off[k] .. off[k+1])
   int32_t gm_pool_rows[6] = {0, 0, 0, 0, 0, 0};     // rows of table k that belong to pool items
   float gm_walks_per_key[6] = {1, 1, 1, 1, 1, 1};   // batches per pool item at 32 >> k queries per wave, weighted by keys
-  // The decode schedule's runs with up to 64 queries each, for steps that run as a contraction
-  // (64 query rows per wave): [n_mx][4] = (first reference in gm_qrefs, references, first tile entry
-  // in gm_seg_ent, entries), in the order of gm_items.  mx_row_fill: share of the 64 rows that carry
-  // a query, weighted by tiles.
+  // Records for steps that run as a contraction (64 query rows per wave): [n_mx][4] = (first reference,
+  // references (at most 64), first tile entry in gm_seg_ent, entries).  mx_row_fill: share of the 64 rows
+  // that carry a query, weighted by tiles.
+  // Layouts that fill kMatrixRowFill of the rows cut these records' runs to measure for mx_plan_workers
+  // workers per KV head (compute units / 8): worker c of such a step takes records mx_plan_ptr[c] ..
+  // mx_plan_ptr[c+1]-1 (mx_plan_ptr.size() - 1 workers carry records), and the records have references
+  // and partial-state slots of their own (mx_qrefs = (query, slot), mx_qshift, mx_slot_ptr as gm_*; the
+  // work items keep their runs of one length for every other kernel).  Other layouts: mx_plan_ptr empty,
+  // the records are the work items' runs taken in pairs and refer to gm_qrefs.
   std::vector<int32_t> mx_rec;
   float mx_row_fill = 0.f;
-  // Layouts whose steps will run as a contraction cut their runs for mx_plan_workers workers per KV head
-  // (compute units / 8): worker c of such a step takes records mx_plan_ptr[c] .. mx_plan_ptr[c+1]-1 of
-  // mx_rec (mx_plan_ptr.size() - 1 workers carry records).  Empty: runs of one length, dealt at launch.
   std::vector<int32_t> mx_plan_ptr;
   int32_t mx_plan_workers = 0;
+  std::vector<int32_t> mx_qrefs, mx_qshift;
+  std::vector<int64_t> mx_slot_ptr;
   // figures the attention calls need on every launch, taken once at build time
   int32_t gm_max_queries = 1;       // most queries any schedule item serves
   int64_t shortest_list = 0;        // fewest entries any Q tile lists

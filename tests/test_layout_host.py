@@ -352,9 +352,14 @@ def test_group_major_schedule_batches_users_and_defaults_to_a_bounded_chunk():
     for key in ("seg_ptr", "seg_ent", "items", "qrefs", "slot_ptr"):
         assert np.array_equal(got[key], want[key]), key
     assert 1 <= got["chunk_tiles"] <= 64
-    # 40 of 64 rows filled: the group's two tiles stay one run (see expected_decode_chunk); the sink tile is another
-    assert sorted(got["items"][:, 3].tolist()) == [8, 8, 32, 32]
-    assert sorted(got["items"][:, 1].tolist()) == [1, 1, 2, 2]
+    # so little work that a run is one tile: the sink tile and the group's two tiles, each for 32 + 8 users
+    assert sorted(got["items"][:, 3].tolist()) == [8, 8, 8, 32, 32, 32]
+    assert got["items"][:, 1].tolist() == [1] * 6
+    # 40 of 64 rows filled: the contraction's records are whole segments (nothing worth cutting), with slots of their own
+    rec, fill = lay.export_matrix_records()
+    plan, nominal, refs, mx_slots = lay.export_matrix_plan(nq)
+    assert fill >= 0.22 and rec[:, 1].tolist() == [40, 40] and rec[:, 3].tolist() == [1, 2] and plan.tolist() == [0, 2]
+    assert np.diff(mx_slots).tolist() == [3] * nq
     slots = np.sort(got["qrefs"][:, 1])
     own = got["slot_ptr"][1:] - 1
     assert np.array_equal(np.sort(np.concatenate([slots, own])), np.arange(got["slot_ptr"][-1]))
@@ -400,13 +405,7 @@ def test_rotation_ids_known_to_the_host_must_lie_inside_the_table():
 
 def expected_decode_chunk(tiles, users, compute_units):
     """The default run length of the decode schedule, restated: tiles[s] / users[s] = tiles of segment s and
-    queries that use it (segments without users or tiles left out).  Layouts that fill 22 % of the 64 rows of a
-    contraction record cut their runs to measure instead (expected_matrix_plan): for them this is the longest run."""
-    rows = sum(64.0 * t * -(-u // 64) for t, u in zip(tiles, users))
-    used = sum(float(t) * u for t, u in zip(tiles, users))
-    if rows > 0 and used / rows >= 0.22:
-        runs, _ = expected_matrix_plan(tiles, users, compute_units)
-        return max(runs)
+    queries that use it (segments without users or tiles left out)."""
     run_slots = max(1, compute_units * 6 // 8 * 3 // 4)
     batches = sum(t * -(-u // 32) for t, u in zip(tiles, users))
     return max(1, min(32, -(-batches // run_slots)))
@@ -538,6 +537,10 @@ def test_runs_cut_to_measure_tile_every_unit_and_balance_the_workers(seed):
     assert i == len(rec)
     runs, want_plan = expected_matrix_plan(tiles, users, 256)
     assert rec[:, 3].tolist() == runs and plan.tolist() == want_plan
+    _, _, plan_refs, plan_slots = lay.export_matrix_plan(n_q)
+    _check_plan_covers_segments(rec, plan_refs, plan_slots, seg_ptr, sel_ptr, sel_idx, n_q)
+    # the work items keep runs of one length
+    assert got["items"][:, 1].max() <= got["chunk_tiles"] <= 32
     cost = np.array([rec[plan[c]:plan[c + 1], 3].sum() + 4.5 * (plan[c + 1] - plan[c]) for c in range(len(plan) - 1)])
     assert cost[:-1].max(initial=0.0) <= cost.mean() + 4.5 + 2 * 4 + 4.5 * 2 or len(cost) == 1, (cost.max(), cost.mean())
 
@@ -577,6 +580,27 @@ def test_persistent_schedule_deals_every_tile_once_and_balances(n_classes):
     assert B.lib().dbsa_layout_export_schedule(None, 4, None, None) == B.DBSA_ERR_INVALID_ARG
 
 
+def _check_plan_covers_segments(rec, refs, slots, seg_ptr, sel_ptr, sel_idx, n_queries):
+    assert rec[0, 0] == 0 and np.array_equal(rec[1:, 0], (rec[:, 0] + rec[:, 1])[:-1]) and rec[-1, 0] + rec[-1, 1] == len(refs)
+    seen = {}                      # (segment, query) -> tiles covered so far
+    used_slots = [[] for _ in range(n_queries)]
+    seg_of_tile = np.searchsorted(seg_ptr, np.arange(seg_ptr[-1]), side="right") - 1
+    for r0, nq, e0, en in rec:
+        s = int(seg_of_tile[e0])
+        assert seg_ptr[s] <= e0 and e0 + en <= seg_ptr[s + 1]
+        for q, slot in refs[r0:r0 + nq]:
+            assert seen.get((s, int(q)), int(seg_ptr[s])) == e0, "a user's runs of a segment follow each other"
+            seen[(s, int(q))] = int(e0 + en)
+            used_slots[int(q)].append(int(slot))
+    for u in range(n_queries):
+        segs = [0] + [int(g) + 1 for g in sel_idx[sel_ptr[u]:sel_ptr[u + 1]]]
+        for s in segs:
+            if seg_ptr[s + 1] > seg_ptr[s]:
+                assert seen.pop((s, u)) == seg_ptr[s + 1], (s, u)
+        assert used_slots[u] == list(range(int(slots[u]), int(slots[u + 1]) - 1)), u
+    assert not seen
+
+
 @pytest.mark.parametrize("n_queries,n_select", [(5, 2), (70, 2), (130, 3), (300, 1)])
 def test_matrix_records_cover_every_item_query_pair_once(n_queries, n_select):
     """The decode schedule's runs with up to 64 queries per record: each (item, query) pair of the 32-query
@@ -592,6 +616,14 @@ def test_matrix_records_cover_every_item_query_pair_once(n_queries, n_select):
     rec, fill = lay.export_matrix_records()
     items, qrefs = got["items"], got["qrefs"]
     assert np.all(rec[:, 1] >= 1) and np.all(rec[:, 1] <= 64)
+    plan, _, plan_refs, plan_slots = lay.export_matrix_plan(n_queries)
+    if len(plan):
+        # runs, references and slots of the records' own: every (segment, user) pair sees each tile of the segment once,
+        # a query's slots are its records in order plus one for its own cache
+        assert fill >= 0.22
+        _check_plan_covers_segments(rec, plan_refs, plan_slots, got["seg_ptr"], sel_ptr, sel_idx, n_queries)
+        return
+    assert fill < 0.22
     # references of the records tile the reference array in order, without gaps
     assert rec[0, 0] == 0 and np.array_equal(rec[1:, 0], (rec[:, 0] + rec[:, 1])[:-1]) and rec[-1, 0] + rec[-1, 1] == len(qrefs)
     pairs_items = sorted((int(e0), int(en), int(q), int(s)) for e0, en, r0, nq in items for q, s in qrefs[r0:r0 + nq])
